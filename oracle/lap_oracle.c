@@ -1,0 +1,371 @@
+/*
+ * lap_oracle.c -- plain CPU reference for the lifetime-aware pool planner.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct
+ * definition that the HIP library is checked against.  It shares no code,
+ * header, table or helper with the HIP path and must never be called from the
+ * product path (only tests, the smoke check and the benchmark's CPU-baseline
+ * leg use it).  Everything is single-threaded, fp64/integer, host pointers.
+ *
+ * Conventions (all integer unless noted):
+ *   variable i : size[i] bytes > 0, live during steps alloc[i] .. free[i]-1
+ *                (half-open [alloc, free), 0 <= alloc < free <= T).
+ *   two variables overlap in time  <=>  alloc_i < free_j && alloc_j < free_i
+ *                (edge E_ij of the weighted interval graph, Section III-B).
+ *   accesses gap_lo[i] <= gap_hi[i] bound the idle gap used for swapping
+ *                (the two consecutive accesses t_i, t_{i+1} of Section IV-B).
+ *
+ * Parity status of each function (what pins it, see tests/test_oracle_*.py):
+ *   lapo_load_profile : pinned (literal definition, closed-form special
+ *                       cases of Section VI-A, hand-worked examples).
+ *   lapo_make_perm    : kinds 0..3 pinned against numpy lexsort and the
+ *                       hand-worked example; kind 4 (seeded) is pinned only as
+ *                       "a permutation, deterministic, published splitmix64
+ *                       test vector" -- the paper defines no seeded order:
+ *                       PARITY UNPINNED by the paper for kind 4.
+ *   lapo_place        : pinned (granule brute force, validity and lower-bound
+ *                       invariants of Eq. 2, exhaustive orderings on N<=8
+ *                       against an independent exhaustive offset search).
+ *   lapo_score_swaps  : DOA/AOA/WDOA pinned (hand-worked example, closed
+ *                       forms, sign rule of Section IV-B); the peak-cut score
+ *                       is this build's reading of "how much the peak drops",
+ *                       pinned against a literal re-simulation of the load
+ *                       curve with the variable removed.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum {
+    LAPO_OK = 0,
+    LAPO_E_NULL = -1,
+    LAPO_E_SIZE = -2,
+    LAPO_E_ORDERING = -4,
+    LAPO_E_LINK = -5,
+    LAPO_E_TRACE = -6,
+    LAPO_E_RANGE = -7,
+    LAPO_E_NOMEM = -100
+};
+
+/* ------------------------------------------------------------------------ */
+/* (a) memory load profile and its peak                                      */
+/* ------------------------------------------------------------------------ */
+
+/* Section II, Definition 2: the load at a time point is the sum of the sizes
+ * of the variables resident at that point.  Definition 4 / Eq. 1: the peak
+ * load is its maximum over the iteration (the weighted clique number), the
+ * peak time is where it occurs; when the maximum is reached more than once
+ * the earliest step is reported.  Written as the definition: every variable
+ * adds its size to every step of its lifetime. */
+int lapo_load_profile(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                      const uint32_t *free_, uint64_t *load, uint64_t *peak, uint32_t *t_peak)
+{
+    if (!size || !alloc || !free_ || !load || !peak || !t_peak) return LAPO_E_NULL;
+    if (n == 0 || T == 0) return LAPO_E_SIZE;
+    for (uint32_t t = 0; t < T; ++t) load[t] = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint32_t t = alloc[i]; t < free_[i]; ++t) load[t] += size[i];
+    uint64_t best = load[0];
+    uint32_t at = 0;
+    for (uint32_t t = 1; t < T; ++t)
+        if (load[t] > best) { best = load[t]; at = t; }
+    *peak = best;
+    *t_peak = at;
+    return LAPO_OK;
+}
+
+/* Number of edges of the interval graph G (Section III-B): pairs of variables
+ * whose lifetimes overlap.  Used only as a work measure. */
+uint64_t lapo_count_edges(uint32_t n, const uint32_t *alloc, const uint32_t *free_)
+{
+    uint64_t e = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint32_t j = i + 1; j < n; ++j)
+            if (alloc[i] < free_[j] && alloc[j] < free_[i]) ++e;
+    return e;
+}
+
+/* ------------------------------------------------------------------------ */
+/* trace validation                                                          */
+/* ------------------------------------------------------------------------ */
+
+int lapo_validate_trace(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                        const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                        const uint64_t *step_ns)
+{
+    if (!size || !alloc || !free_) return LAPO_E_NULL;
+    if ((gap_lo == NULL) != (gap_hi == NULL)) return LAPO_E_NULL;
+    if (n == 0 || T == 0) return LAPO_E_SIZE;
+    const uint64_t two53 = (uint64_t)1 << 53, two63 = (uint64_t)1 << 63;
+    uint64_t sum = 0, maxsize = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (size[i] == 0 || alloc[i] >= free_[i] || free_[i] > T) return LAPO_E_TRACE;
+        if (gap_lo && (gap_lo[i] < alloc[i] || gap_hi[i] > free_[i] - 1 || gap_lo[i] > gap_hi[i]))
+            return LAPO_E_TRACE;
+    }
+    if (step_ns)
+        for (uint32_t t = 0; t < T; ++t)
+            if (step_ns[t] == 0) return LAPO_E_TRACE;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (size[i] >= two53) return LAPO_E_RANGE;
+        sum += size[i];
+        if (sum >= two63) return LAPO_E_RANGE;
+        if (size[i] > maxsize) maxsize = size[i];
+    }
+    /* max size * T must fit 64 bits (area key, load prefix sums) */
+    if (maxsize > UINT64_MAX / T) return LAPO_E_RANGE;
+    uint64_t total_ns = 0;
+    for (uint32_t t = 0; t < T; ++t) {
+        uint64_t ns = step_ns ? step_ns[t] : 1000000u;
+        if (ns >= two53) return LAPO_E_RANGE;
+        total_ns += ns;
+        if (total_ns >= two53) return LAPO_E_RANGE;
+    }
+    return LAPO_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* (b) orderings                                                             */
+/* ------------------------------------------------------------------------ */
+
+/* Key of the seeded shuffle: the splitmix64 output function (Steele, Lea,
+ * Flood 2014; Vigna's public-domain formulation) applied to the counter
+ * seed + (i+1)*golden-gamma.  Counter based: no state is carried between
+ * variables. */
+static uint64_t mix64(uint64_t seed, uint32_t i)
+{
+    uint64_t z = seed + ((uint64_t)i + 1u) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+uint64_t lapo_mix64(uint64_t seed, uint32_t i) { return mix64(seed, i); }
+
+typedef struct { uint64_t key; uint32_t idx; } keyed;
+
+static int cmp_key_asc(const void *a, const void *b)
+{
+    const keyed *x = (const keyed *)a, *y = (const keyed *)b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    return x->idx < y->idx ? -1 : (x->idx > y->idx);
+}
+
+static int cmp_key_desc(const void *a, const void *b)
+{
+    const keyed *x = (const keyed *)a, *y = (const keyed *)b;
+    if (x->key != y->key) return x->key > y->key ? -1 : 1;
+    return x->idx < y->idx ? -1 : (x->idx > y->idx);
+}
+
+/* Section III-C sorts the variables by size, largest first (kind 0).  The
+ * other kinds are the extra heuristic orders evaluated in parallel:
+ *   1 lifetime descending, 2 size x lifetime descending, 3 alloc step
+ *   ascending (arrival order, what an online pool would see), 4 seeded
+ *   shuffle (ascending mix64 key), 5 caller-supplied permutation.
+ * Equal keys keep ascending variable index (a stable sort). */
+int lapo_make_perm(uint32_t n, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                   uint32_t kind, uint64_t seed, const uint32_t *explicit_perm, uint32_t *perm)
+{
+    if (!size || !alloc || !free_ || !perm) return LAPO_E_NULL;
+    if (n == 0) return LAPO_E_SIZE;
+    if (kind > 5) return LAPO_E_ORDERING;
+    if (kind == 5) {
+        if (!explicit_perm) return LAPO_E_NULL;
+        unsigned char *seen = (unsigned char *)calloc(n, 1);
+        if (!seen) return LAPO_E_NOMEM;
+        for (uint32_t r = 0; r < n; ++r) {
+            uint32_t v = explicit_perm[r];
+            if (v >= n || seen[v]) { free(seen); return LAPO_E_ORDERING; }
+            seen[v] = 1;
+            perm[r] = v;
+        }
+        free(seen);
+        return LAPO_OK;
+    }
+    keyed *k = (keyed *)malloc((size_t)n * sizeof(keyed));
+    if (!k) return LAPO_E_NOMEM;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint64_t life = (uint64_t)(free_[i] - alloc[i]);
+        k[i].idx = i;
+        switch (kind) {
+        case 0: k[i].key = size[i]; break;
+        case 1: k[i].key = life; break;
+        case 2: k[i].key = size[i] * life; break;
+        case 3: k[i].key = alloc[i]; break;
+        default: k[i].key = mix64(seed, i); break;
+        }
+    }
+    qsort(k, n, sizeof(keyed), kind <= 2 ? cmp_key_desc : cmp_key_asc);
+    for (uint32_t r = 0; r < n; ++r) perm[r] = k[r].idx;
+    free(k);
+    return LAPO_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* (b) first-fit placement                                                   */
+/* ------------------------------------------------------------------------ */
+
+typedef struct { uint64_t off, end; } span;
+
+static int cmp_span(const void *a, const void *b)
+{
+    const span *x = (const span *)a, *y = (const span *)b;
+    if (x->off != y->off) return x->off < y->off ? -1 : 1;
+    return x->end < y->end ? -1 : (x->end > y->end);
+}
+
+/* Section III-C: take the variables in the given order; each one gets an
+ * address range that none of its already-placed, time-overlapping neighbours
+ * uses.  First-fit: the first (lowest) hole between the neighbours' blocks
+ * that is large enough -- a hole of exactly the variable's size fits -- and
+ * when no hole fits the block goes above the topmost neighbour (the pool is
+ * extended).  Blocks of variables that do not overlap in time are invisible
+ * to each other.  footprint = highest end address over all variables. */
+int lapo_place(uint32_t n, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+               const uint32_t *perm, uint64_t *off, uint64_t *footprint)
+{
+    if (!size || !alloc || !free_ || !perm || !off || !footprint) return LAPO_E_NULL;
+    if (n == 0) return LAPO_E_SIZE;
+    /* placed variables in placement order */
+    uint32_t *pa = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
+    uint32_t *pf = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
+    span *ps = (span *)malloc((size_t)n * sizeof(span));
+    span *nb = (span *)malloc((size_t)n * sizeof(span));
+    if (!pa || !pf || !ps || !nb) { free(pa); free(pf); free(ps); free(nb); return LAPO_E_NOMEM; }
+    uint64_t fp = 0;
+    for (uint32_t r = 0; r < n; ++r) {
+        const uint32_t v = perm[r];
+        const uint32_t a = alloc[v], f = free_[v];
+        const uint64_t s = size[v];
+        /* neighbours: placed earlier and overlapping in lifetime */
+        uint32_t m = 0;
+        for (uint32_t j = 0; j < r; ++j)
+            if (pa[j] < f && a < pf[j]) nb[m++] = ps[j];
+        qsort(nb, m, sizeof(span), cmp_span);
+        /* walk the neighbours' blocks upward from address 0 */
+        uint64_t o = 0;
+        for (uint32_t j = 0; j < m; ++j) {
+            if (nb[j].off >= o && nb[j].off - o >= s) break;   /* hole [o, nb.off) fits */
+            if (nb[j].end > o) o = nb[j].end;
+        }
+        off[v] = o;
+        pa[r] = a; pf[r] = f; ps[r].off = o; ps[r].end = o + s;
+        if (o + s > fp) fp = o + s;
+    }
+    *footprint = fp;
+    free(pa); free(pf); free(ps); free(nb);
+    return LAPO_OK;
+}
+
+/* Evaluate B orderings and keep the smallest footprint (lowest ordering index
+ * on ties).  kinds/seeds are host arrays; for kind 5 the seed field is the
+ * host address of a u32[n] permutation.  footprints / all_off may be NULL. */
+int lapo_plan_pool(uint32_t n, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                   uint32_t B, const uint32_t *kinds, const uint64_t *seeds,
+                   uint64_t *best_off, uint64_t *best_fp, uint32_t *best_idx,
+                   uint64_t *footprints, uint64_t *all_off)
+{
+    if (!kinds || !seeds || !best_off || !best_fp || !best_idx) return LAPO_E_NULL;
+    if (n == 0 || B == 0) return LAPO_E_SIZE;
+    uint32_t *perm = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
+    uint64_t *off = (uint64_t *)malloc((size_t)n * sizeof(uint64_t));
+    if (!perm || !off) { free(perm); free(off); return LAPO_E_NOMEM; }
+    int rc = LAPO_OK;
+    uint64_t bfp = 0;
+    uint32_t bidx = 0;
+    for (uint32_t b = 0; b < B; ++b) {
+        const uint32_t *ex = kinds[b] == 5 ? (const uint32_t *)(uintptr_t)seeds[b] : NULL;
+        rc = lapo_make_perm(n, size, alloc, free_, kinds[b], seeds[b], ex, perm);
+        if (rc) break;
+        uint64_t fp;
+        rc = lapo_place(n, size, alloc, free_, perm, off, &fp);
+        if (rc) break;
+        if (footprints) footprints[b] = fp;
+        if (all_off) memcpy(all_off + (size_t)b * n, off, (size_t)n * sizeof(uint64_t));
+        if (b == 0 || fp < bfp) {
+            bfp = fp; bidx = b;
+            memcpy(best_off, off, (size_t)n * sizeof(uint64_t));
+        }
+    }
+    if (!rc) { *best_fp = bfp; *best_idx = bidx; }
+    free(perm); free(off);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* (c) swap-candidate scores                                                 */
+/* ------------------------------------------------------------------------ */
+
+/* Section IV.  Per variable, with t_lo = gap_lo, t_hi = gap_hi its two
+ * consecutive accesses (defaults: alloc and free-1) and step t occupying wall
+ * clock [C[t], C[t+1]) where C is the prefix sum of step_ns:
+ *   candidate (IV-A): size >= min_bytes, lifetime spans the peak time
+ *                     (alloc <= t_peak < free), and the gap is not empty.
+ *   transfer time   : delta = ceil(size*1000 / bpus) ns each way, with
+ *                     bpus = llround(link_GBps*1000) bytes per microsecond.
+ *   DOA (IV-B i)    : time between the accesses minus swap-out and swap-in:
+ *                     C[t_hi] - C[t_lo+1] - 2*delta (may be negative).
+ *   AOA (IV-B ii)   : DOA*size when DOA >= 0, DOA/size otherwise (binary64,
+ *                     one operation).
+ *   WDOA (IV-B iii) : area under the ORIGINAL load curve between the two
+ *                     accesses: sum of load over steps t_lo+1 .. t_hi-1.
+ *   peak cut        : the variable is absent for the whole steps that lie
+ *                     inside [C[t_lo+1]+delta, C[t_hi]-delta); cut = peak -
+ *                     peak of the load curve with size removed on those steps
+ *                     (0 when DOA < 0 or no whole step fits).
+ * Variables with gap_hi == gap_lo get 0 in every output. */
+int lapo_score_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                     const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                     const uint64_t *step_ns, double link_GBps, uint64_t min_bytes,
+                     uint8_t *cand, int64_t *doa, double *aoa, uint64_t *wdoa, uint64_t *cut)
+{
+    if (!size || !alloc || !free_ || !cand || !doa || !aoa || !wdoa || !cut) return LAPO_E_NULL;
+    if ((gap_lo == NULL) != (gap_hi == NULL)) return LAPO_E_NULL;
+    if (n == 0 || T == 0) return LAPO_E_SIZE;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps) || link_GBps * 1000.0 >= 9.0e18) return LAPO_E_LINK;
+    const long long bpus_ll = llround(link_GBps * 1000.0);
+    if (bpus_ll <= 0) return LAPO_E_LINK;
+    const uint64_t bpus = (uint64_t)bpus_ll;
+
+    uint64_t *load = (uint64_t *)malloc((size_t)T * sizeof(uint64_t));
+    uint64_t *C = (uint64_t *)malloc(((size_t)T + 1) * sizeof(uint64_t));
+    if (!load || !C) { free(load); free(C); return LAPO_E_NOMEM; }
+    uint64_t peak; uint32_t t_peak;
+    int rc = lapo_load_profile(n, T, size, alloc, free_, load, &peak, &t_peak);
+    if (rc) { free(load); free(C); return rc; }
+    C[0] = 0;
+    for (uint32_t t = 0; t < T; ++t) C[t + 1] = C[t] + (step_ns ? step_ns[t] : 1000000u);
+
+    for (uint32_t i = 0; i < n; ++i) {
+        const uint32_t tl = gap_lo ? gap_lo[i] : alloc[i];
+        const uint32_t th = gap_hi ? gap_hi[i] : free_[i] - 1;
+        cand[i] = 0; doa[i] = 0; aoa[i] = 0.0; wdoa[i] = 0; cut[i] = 0;
+        if (th <= tl) continue;
+        const uint64_t s = size[i];
+        cand[i] = (s >= min_bytes && alloc[i] <= t_peak && t_peak < free_[i]) ? 1 : 0;
+        const uint64_t delta = (s * 1000u + bpus - 1) / bpus;
+        const int64_t d = (int64_t)(C[th] - C[tl + 1]) - 2 * (int64_t)delta;
+        doa[i] = d;
+        aoa[i] = d >= 0 ? (double)d * (double)s : (double)d / (double)s;
+        uint64_t area = 0;
+        for (uint32_t t = tl + 1; t < th; ++t) area += load[t];
+        wdoa[i] = area;
+        if (d < 0) continue;
+        /* whole steps inside [out_done, in_start) */
+        const uint64_t out_done = C[tl + 1] + delta, in_start = C[th] - delta;
+        uint32_t lo = 0, hi = 0;
+        while (C[lo] < out_done) ++lo;                 /* first step starting at/after out_done */
+        for (uint32_t t = 0; t <= T; ++t) if (C[t] <= in_start) hi = t;   /* last boundary <= in_start */
+        if (hi <= lo) continue;
+        uint64_t np = 0;
+        for (uint32_t t = 0; t < T; ++t) {
+            uint64_t l = (t >= lo && t < hi) ? load[t] - s : load[t];
+            if (l > np) np = l;
+        }
+        cut[i] = peak - np;
+    }
+    free(load); free(C);
+    return LAPO_OK;
+}

@@ -1,0 +1,155 @@
+"""Pins for the oracle's orderings and first-fit placement (Section III)."""
+import itertools
+
+import numpy as np
+import pytest
+
+from helpers import (all_perms, check_valid, check_valid_fast, grid_first_fit, mk_trace,
+                     optimal_footprint, read_golden)
+from traces import make_config, make_orderings, random_trace
+
+
+def _e1():
+    g = read_golden("e1_placement.txt")
+    tr = mk_trace(np.array(g["size"][0], dtype=np.uint64) * 512, g["alloc"][0], g["free"][0], T=5)
+    return g, tr
+
+
+def test_e1_orderings_and_offsets(oracle_mod):
+    g, tr = _e1()
+    n = tr.n_vars
+    for row in g["order"]:
+        kind = int(row[0])
+        perm = [int(x) for x in row[1:1 + n]]
+        offs = [int(x) for x in row[1 + n:1 + 2 * n]]
+        fp = int(row[1 + 2 * n])
+        if kind < 5:
+            assert oracle_mod.make_perm(tr, kind).tolist() == perm
+        off, got_fp = oracle_mod.place(tr, np.array(perm, np.uint32))
+        assert (off // 512).tolist() == offs and got_fp == fp * 512
+
+
+def test_e1_all_720_orderings(oracle_mod):
+    g, tr = _e1()
+    hist = {}
+    for p in all_perms(6):
+        _, fp = oracle_mod.place(tr, np.array(p, np.uint32))
+        hist[fp // 512] = hist.get(fp // 512, 0) + 1
+    assert hist == {int(k): int(v) for k, v in g["hist"]}
+    r = oracle_mod.plan_pool(tr, [0, 1, 2, 3], [0] * 4)
+    assert r["best_ordering"] == 0 and r["best_footprint"] == 14 * 512   # tie 0/2 -> lower index
+    assert r["footprints"].tolist() == [14 * 512, 15 * 512, 14 * 512, 16 * 512]
+
+
+def test_splitmix64_published_vector(oracle_mod):
+    # first outputs of splitmix64 seeded with 0 (Vigna's reference implementation)
+    assert oracle_mod.mix64(0, 0) == 0xE220A8397B1DCDAF
+    assert oracle_mod.mix64(0, 1) == 0x6E789E6AA1B965F4
+    assert oracle_mod.mix64(0, 2) == 0x06C45D188009454F
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_fixed_kinds_match_lexsort(oracle_mod, seed):
+    tr = random_trace(seed, 500, 23, size_choices=[1, 2, 2, 3, 64])
+    idx = np.arange(tr.n_vars)
+    life = (tr.free - tr.alloc).astype(np.uint64)
+    keys = {0: -tr.size.astype(np.int64), 1: -life.astype(np.int64),
+            2: -(tr.size * life).astype(np.int64), 3: tr.alloc.astype(np.int64)}
+    for kind, key in keys.items():
+        want = np.lexsort((idx, key))
+        assert oracle_mod.make_perm(tr, kind).tolist() == want.tolist()
+    p = oracle_mod.make_perm(tr, 4, seed=631 + seed)
+    assert sorted(p.tolist()) == idx.tolist()
+    k = [oracle_mod.mix64(631 + seed, int(i)) for i in p]
+    assert k == sorted(k)
+    assert oracle_mod.make_perm(tr, 4, seed=631 + seed).tolist() == p.tolist()
+    assert oracle_mod.make_perm(tr, 4, seed=632 + seed).tolist() != p.tolist()
+
+
+def test_explicit_perm_is_validated(oracle_mod):
+    tr = random_trace(1, 5, 4)
+    with pytest.raises(RuntimeError):
+        oracle_mod.make_perm(tr, 5, explicit=[0, 1, 1, 2, 3])
+    with pytest.raises(RuntimeError):
+        oracle_mod.make_perm(tr, 9)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_first_fit_equals_occupancy_grid(oracle_mod, seed):
+    """Lowest feasible offset, checked against a time x address bitmap."""
+    tr = random_trace(200 + seed, 40, 9, size_choices=[1, 1, 2, 3, 5, 8], granule=512)
+    for kind in range(5):
+        perm = oracle_mod.make_perm(tr, kind, seed=seed)
+        off, fp = oracle_mod.place(tr, perm)
+        want = grid_first_fit(tr, perm, 512)
+        assert off.tolist() == want.tolist()
+        assert fp == int((want + tr.size).max())
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_validity_and_lower_bound(oracle_mod, seed):
+    """Eq. 2 (footprint >= peak load) and neighbours never share addresses."""
+    tr = random_trace(300 + seed, 400, 31)
+    _, peak, _ = oracle_mod.load_profile(tr)
+    kinds, seeds = make_orderings(12)
+    r = oracle_mod.plan_pool(tr, kinds, seeds)
+    for b in range(12):
+        off = r["all_offsets"][b]
+        assert check_valid(tr, off) and check_valid_fast(tr, off)
+        assert r["footprints"][b] >= peak
+        assert r["footprints"][b] == int((off + tr.size).max())
+    assert r["best_footprint"] == r["footprints"].min()
+    assert r["best_ordering"] == int(np.argmin(r["footprints"]))
+    assert r["best_offsets"].tolist() == r["all_offsets"][r["best_ordering"]].tolist()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_exhaustive_orderings_reach_dsa_optimum(oracle_mod, seed):
+    """Placing in ascending order of an optimal packing's offsets, first-fit puts every block
+    no higher than the optimum does, so min over ALL orderings is the true offline-DSA optimum.
+    Checked against an independent exhaustive search over offsets."""
+    n = 6 if seed % 2 else 7
+    tr = random_trace(400 + seed, n, 5, size_choices=[1, 2, 3, 4], one_step_frac=0.2)
+    best = min(oracle_mod.place(tr, np.array(p, np.uint32))[1] for p in all_perms(n))
+    assert best == optimal_footprint(tr, 512)
+    _, peak, _ = oracle_mod.load_profile(tr)
+    assert best >= peak
+
+
+def test_exhaustive_n8(oracle_mod):
+    tr = random_trace(77, 8, 6, size_choices=[1, 2, 3], one_step_frac=0.1)
+    perms = np.array(list(all_perms(8)), np.uint32)
+    best = min(oracle_mod.place(tr, p)[1] for p in perms)
+    assert best == optimal_footprint(tr, 512)
+
+
+def test_special_cases(oracle_mod):
+    # identical lifetimes: blocks stack, footprint = sum of sizes for every ordering
+    tr = mk_trace([512 * k for k in (3, 1, 4, 1, 5)], [2] * 5, [6] * 5, T=8)
+    for p in itertools.islice(all_perms(5), 0, 120, 7):
+        off, fp = oracle_mod.place(tr, np.array(p, np.uint32))
+        assert fp == 14 * 512
+        assert off[p[0]] == 0
+    # disjoint lifetimes: everything at offset 0, footprint = largest variable
+    tr = mk_trace([512 * k for k in (3, 9, 1, 4)], [0, 1, 2, 3], [1, 2, 3, 4])
+    off, fp = oracle_mod.place(tr, np.array([3, 1, 0, 2], np.uint32))
+    assert off.tolist() == [0, 0, 0, 0] and fp == 9 * 512
+    # a single variable
+    tr = mk_trace([12345], [0], [1])
+    off, fp = oracle_mod.place(tr, np.array([0], np.uint32))
+    assert off.tolist() == [0] and fp == 12345
+    # a hole of exactly the variable's size is used
+    tr = mk_trace([512, 1024, 512, 1024], [0, 0, 0, 1], [2, 1, 2, 2], T=2)
+    off, fp = oracle_mod.place(tr, np.array([0, 1, 2, 3], np.uint32))
+    assert off.tolist() == [0, 512, 1536, 512] and fp == 2048
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_config_sanity_band(oracle_mod, cfg):
+    """Section VI-A reports at most a few percent fragmentation for size-descending order on
+    DNN traces (a sanity band for the synthetic stand-ins, not a parity value)."""
+    tr = make_config(cfg)
+    _, peak, _ = oracle_mod.load_profile(tr)
+    off, fp = oracle_mod.place(tr, oracle_mod.make_perm(tr, 0))
+    assert check_valid_fast(tr, off)
+    assert peak <= fp <= 1.10 * peak
