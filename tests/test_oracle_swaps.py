@@ -97,22 +97,25 @@ def test_adjacent_accesses(oracle_mod):
 
 
 def test_fast_link_limit(oracle_mod):
-    # transfer time -> 0: absent for every idle step; cut = peak - max(outside, inside - size)
-    tr = mk_trace([4096, 1024, 2048], [0, 1, 3], [6, 2, 6], T=6)
+    # transfer time -> 1 ns: the variable is away for every idle step except the first and the
+    # last one (a step counts only if it lies wholly between swap-out end and swap-in start)
+    tr = mk_trace([4096, 1024, 2048], [0, 1, 3], [7, 2, 4], T=7)
     load, peak, tpk = oracle_mod.load_profile(tr)
+    assert load.tolist() == [4096, 5120, 4096, 6144, 4096, 4096, 4096] and (peak, tpk) == (6144, 3)
     s = oracle_mod.score_swaps(tr, 9.0e6, 1)
-    assert load.tolist() == [4096, 5120, 4096, 6144, 6144, 6144] and peak == 6144
-    # v0 idle on steps 1..4 -> new curve 4096,1024,0,2048,2048,6144 -> no cut (peak also at step 5)
-    assert s["peak_cut"][0] == 0
-    assert s["wdoa"][0] == 5120 + 4096 + 6144 + 6144
-    # v2 accessed at 3 and 5, idle on step 4 only -> curve still peaks at 6144
-    assert s["peak_cut"][2] == 0
-    tr2 = mk_trace([4096, 1024, 2048], [0, 1, 2], [6, 2, 5], T=6)
-    load2, peak2, _ = oracle_mod.load_profile(tr2)
+    # v0: accesses 0 and 6, idle steps 1..5, away on 2..4 -> curve 4096,5120,0,2048,0,4096,4096
+    assert s["doa_ns"][0] == 5_000_000 - 2
+    assert s["wdoa"][0] == 5120 + 4096 + 6144 + 4096 + 4096
+    assert s["peak_cut"][0] == 6144 - 5120
+    assert s["candidate"].tolist() == [1, 0, 0]          # v1, v2 have no gap
+    # shrink the gap to accesses 1 and 5: idle 2..4, away on step 3 only -> 4096+... peak 5120
+    tr2 = mk_trace([4096, 1024, 2048], [0, 1, 3], [7, 2, 4], T=7, gap_lo=[1, 1, 3], gap_hi=[5, 1, 3])
     s2 = oracle_mod.score_swaps(tr2, 9.0e6, 1)
-    # loads 4096,5120,6144,6144,6144,4096 ; v0 idle 1..4 -> 4096,1024,2048,2048,2048,4096 -> cut 2048
-    assert peak2 == 6144 and s2["peak_cut"][0] == 2048
-    assert s2["candidate"].tolist() == [1, 0, 1]
+    assert s2["peak_cut"][0] == 1024 and s2["wdoa"][0] == 4096 + 6144 + 4096
+    # accesses 2 and 4: idle step 3 only, and it is not wholly inside the window -> no cut
+    tr3 = mk_trace([4096, 1024, 2048], [0, 1, 3], [7, 2, 4], T=7, gap_lo=[2, 1, 3], gap_hi=[4, 1, 3])
+    s3 = oracle_mod.score_swaps(tr3, 9.0e6, 1)
+    assert s3["peak_cut"][0] == 0 and s3["wdoa"][0] == 6144 and s3["doa_ns"][0] == 1_000_000 - 2
 
 
 def test_bad_link_rejected(oracle_mod):
@@ -125,6 +128,8 @@ def test_bad_link_rejected(oracle_mod):
 def test_configs_have_useful_candidates(oracle_mod, cfg):
     tr = make_config(cfg)
     s = oracle_mod.score_swaps(tr, tr.meta["link_GBps"], tr.meta["min_bytes"])
-    assert s["candidate"].sum() > 0
-    assert (s["peak_cut"][s["candidate"] == 1] > 0).any()
+    assert (s["peak_cut"] > 0).any()
+    if cfg == 3:       # the tiny net has no variable of 1 MiB; ResNet-50 has many
+        assert s["candidate"].sum() > 0
+        assert (s["peak_cut"][s["candidate"] == 1] > 0).any()
     assert (s["peak_cut"] <= tr.size).all()
