@@ -1,0 +1,162 @@
+/*
+ * lap.h -- C ABI of liblap, the lifetime-aware pool planner for MI355X (gfx950).
+ *
+ * Offline planning for one training iteration's variable trace (arXiv
+ * 1903.06631, Sections II-IV): every variable has a size and a fixed logical
+ * time at which it is allocated and freed (Section III-A).  Three calls:
+ *
+ *   lap_load_profile  memory load per step and its peak (Section II, Def. 2
+ *                     and Def. 4; Eq. 1: the peak is the weighted clique
+ *                     number, a lower bound on any pool's footprint, Eq. 2).
+ *   lap_plan_pool     SmartPool placement (Section III-C): variables taken in
+ *                     a heuristic order, each put at the lowest address that
+ *                     none of its already-placed, time-overlapping neighbours
+ *                     uses (first-fit); many orders evaluated in parallel and
+ *                     the smallest footprint kept.
+ *   lap_score_swaps   AutoSwap candidate filter and priority scores (Section
+ *                     IV-A, IV-B): DOA, AOA, WDOA, and the drop of the peak
+ *                     load when the variable is away for its idle gap.
+ *
+ * Conventions
+ *   - Lifetimes are half-open: variable i is live during steps
+ *     alloc[i] .. free[i]-1, with 0 <= alloc < free <= n_steps.  A variable
+ *     freed at step t and one allocated at step t do not coexist.
+ *   - Two variables are neighbours (edge of the interval graph of Section
+ *     III-B) iff alloc_i < free_j && alloc_j < free_i.
+ *   - gap_lo[i] <= gap_hi[i] are the two consecutive accesses (Section IV-B)
+ *     that bound the variable's idle gap; NULL,NULL means alloc and free-1.
+ *   - step_ns[t] is the compute time of step t in ns; NULL means 1 ms each.
+ *
+ * Memory and ownership
+ *   - Every pointer inside lap_trace and every output / workspace pointer is
+ *     a DEVICE pointer owned by the caller.  The library never allocates or
+ *     frees device memory.  The lap_trace struct itself and the lap_ordering
+ *     array are HOST memory and are read before the call returns.
+ *   - Work is enqueued on the given HIP stream (a hipStream_t passed as
+ *     void*; NULL = the default stream) and the call returns without waiting.
+ *     Outputs, including the scalar ones, are valid once the stream has been
+ *     synchronised.  lap_validate_trace is the exception: it waits.
+ *   - ws must hold at least lap_workspace_bytes(...) bytes, 256-byte aligned.
+ *     Two calls may run concurrently only on distinct workspaces.
+ *
+ * Errors: every call returns LAP_OK (0) or a negative code.  Argument errors
+ * are detected on the host before anything is enqueued.  Trace-content errors
+ * (LAP_E_TRACE, LAP_E_RANGE) are reported by lap_validate_trace only; the
+ * other calls assume a valid trace.
+ */
+#ifndef LAP_H
+#define LAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    LAP_OK = 0,
+    LAP_E_NULL = -1,       /* a required pointer is NULL (or only one of gap_lo/gap_hi given) */
+    LAP_E_SIZE = -2,       /* n_vars, n_steps or B is 0, or a size exceeds the supported maximum */
+    LAP_E_WORKSPACE = -3,  /* ws is NULL, misaligned or smaller than lap_workspace_bytes() */
+    LAP_E_ORDERING = -4,   /* unknown ordering kind, or NULL permutation for LAP_ORD_EXPLICIT */
+    LAP_E_LINK = -5,       /* link_GBps <= 0, not finite, or rounds to 0 bytes per microsecond */
+    LAP_E_TRACE = -6,      /* size 0, alloc >= free, free > n_steps, gap outside [alloc, free-1], step_ns 0 */
+    LAP_E_RANGE = -7,      /* sum of sizes >= 2^63, a size >= 2^53, sum of step_ns >= 2^53, max size * n_steps >= 2^64 */
+    LAP_E_HIP = -8         /* a HIP runtime call or kernel launch failed */
+};
+
+/* One training iteration's variable trace (Section III-A), structure of arrays. */
+typedef struct {
+    uint32_t n_vars;          /* N > 0 */
+    uint32_t n_steps;         /* T > 0 */
+    const uint64_t *size;     /* [N] bytes, > 0 */
+    const uint32_t *alloc;    /* [N] first live step */
+    const uint32_t *free_;    /* [N] one past the last live step */
+    const uint32_t *gap_lo;   /* [N] or NULL */
+    const uint32_t *gap_hi;   /* [N] or NULL (both or neither) */
+    const uint64_t *step_ns;  /* [T] or NULL */
+} lap_trace;
+
+/* Placement orders.  Ties in a key keep ascending variable index.
+ *   SIZE_DESC   the paper's order: largest variable first (Section III-C)
+ *   LIFE_DESC   longest lifetime (free - alloc) first
+ *   AREA_DESC   largest size * lifetime first
+ *   ALLOC_ASC   arrival order, what an online pool would see
+ *   SEEDED      ascending splitmix64 output of (seed + (i+1) * 0x9E3779B97F4A7C15)
+ *   EXPLICIT    seed holds a device pointer to a u32[N] permutation
+ *               (placement rank -> variable index); it must be a permutation */
+enum {
+    LAP_ORD_SIZE_DESC = 0,
+    LAP_ORD_LIFE_DESC = 1,
+    LAP_ORD_AREA_DESC = 2,
+    LAP_ORD_ALLOC_ASC = 3,
+    LAP_ORD_SEEDED = 4,
+    LAP_ORD_EXPLICIT = 5
+};
+
+typedef struct {
+    uint32_t kind;
+    uint32_t pad;
+    uint64_t seed;
+} lap_ordering;
+
+enum { LAP_WS_LOAD_PROFILE = 0, LAP_WS_PLAN_POOL = 1, LAP_WS_SCORE_SWAPS = 2, LAP_WS_VALIDATE = 3 };
+
+/* Bytes of workspace the given call needs (B is ignored except for PLAN_POOL).
+ * Returns 0 for an unknown call id. */
+size_t lap_workspace_bytes(int which_call, uint32_t n_vars, uint32_t n_steps, uint32_t B);
+
+/* Section II Def. 2 / Def. 4, Eq. 1.
+ *   load   [T]  out: load[t] = sum of size[i] over variables live at step t
+ *   peak   [1]  out: max_t load[t]
+ *   t_peak [1]  out: earliest step where the peak occurs */
+int lap_load_profile(const lap_trace *trace, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Section III-C with first-fit, for B orderings at once.
+ *   ords           [B] host
+ *   best_offsets   [N]   out: byte offset of every variable under the best ordering
+ *   best_footprint [1]   out: pool size of the best ordering (max offset + size)
+ *   best_ordering  [1]   out: index of the smallest footprint, lowest index on ties
+ *   footprints     [B]   out or NULL
+ *   all_offsets    [B*N] out or NULL: offsets under every ordering, ordering-major */
+int lap_plan_pool(const lap_trace *trace, const lap_ordering *ords, uint32_t B,
+                  uint64_t *best_offsets, uint64_t *best_footprint, uint32_t *best_ordering,
+                  uint64_t *footprints, uint64_t *all_offsets,
+                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Section IV-A / IV-B.  link_GBps is the host link in 10^9 bytes per second,
+ * rounded to an integer number of bytes per microsecond; one transfer of
+ * `size` bytes takes ceil(size*1000 / bytes_per_us) ns in either direction.
+ *   load      [T] from lap_load_profile, or NULL to compute it here
+ *   candidate [N] out: 1 iff size >= min_bytes, alloc <= t_peak < free, gap_hi > gap_lo
+ *   doa_ns    [N] out: time between the two accesses minus both transfers (may be < 0)
+ *   aoa       [N] out: doa*size if doa >= 0 else doa/size, one binary64 operation
+ *   wdoa      [N] out: sum of load over the idle steps gap_lo+1 .. gap_hi-1
+ *   peak_cut  [N] out: peak minus the peak of the load curve with the variable
+ *                 removed from the whole steps between swap-out end and swap-in start
+ * Variables with gap_hi == gap_lo get 0 in every output. */
+int lap_score_swaps(const lap_trace *trace, double link_GBps, uint64_t min_bytes,
+                    const uint64_t *load,
+                    uint8_t *candidate, int64_t *doa_ns, double *aoa, uint64_t *wdoa, uint64_t *peak_cut,
+                    void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Checks the trace content on the device, waits for the stream, and returns
+ * LAP_OK, LAP_E_TRACE or LAP_E_RANGE. */
+int lap_validate_trace(const lap_trace *trace, void *ws, size_t ws_bytes, void *hip_stream);
+
+const char *lap_status_string(int status);
+
+/* Optional kernel timing for benchmarks.  When enabled, each call brackets
+ * its dominant kernel with HIP events on the caller's stream; after the
+ * stream is synchronised lap_profile_last_ms returns that kernel's duration
+ * in ms (negative if none was recorded).  Not thread safe. */
+enum { LAP_K_LOAD_SCATTER = 0, LAP_K_PLACE = 1, LAP_K_SCORE = 2, LAP_K_SORT = 3, LAP_K_COUNT = 4 };
+int lap_profile_enable(int on);
+float lap_profile_last_ms(int kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAP_H */

@@ -1,0 +1,25 @@
+"""liblap: lifetime-aware memory-pool planning on MI355X (hand-written HIP, gfx950).
+
+Thin Python binding over the C-ABI library declared in include/lap.h.  PyTorch
+is used for device memory and streams only; every step of the planner runs in
+the library's kernels.  There is no CPU fallback: if liblap.so is missing or a
+call fails, an exception is raised.
+"""
+from .binding import (  # noqa: F401
+    DeviceTrace,
+    LapError,
+    lib_path,
+    load_library,
+    load_profile,
+    plan_pool,
+    profile_enable,
+    profile_last_ms,
+    score_swaps,
+    status_string,
+    validate_trace,
+    workspace_bytes,
+)
+
+ORD_SIZE_DESC, ORD_LIFE_DESC, ORD_AREA_DESC, ORD_ALLOC_ASC, ORD_SEEDED, ORD_EXPLICIT = range(6)
+WS_LOAD_PROFILE, WS_PLAN_POOL, WS_SCORE_SWAPS, WS_VALIDATE = range(4)
+K_LOAD_SCATTER, K_PLACE, K_SCORE, K_SORT = range(4)

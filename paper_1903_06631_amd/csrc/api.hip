@@ -1,0 +1,300 @@
+// extern "C" entry points of liblap: argument checks, workspace carving, launches.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/lap.h"
+#include "lap_kernels.h"
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Carver {
+    char *base;
+    size_t used = 0;
+    explicit Carver(void *p) : base((char *)p) {}
+    template <class T> T *take(size_t count)
+    {
+        T *r = (T *)(base + used);
+        used += up(count * sizeof(T));
+        return r;
+    }
+};
+
+inline uint32_t table_levels(uint32_t T)
+{
+    uint32_t lv = 1;
+    while ((1ull << lv) <= T) ++lv;
+    return lv;                       // floor(log2 T) + 1
+}
+
+size_t ws_load(uint32_t T) { return up(((size_t)T + 1) * 8); }
+
+size_t ws_plan(uint32_t n, uint32_t B)
+{
+    const size_t bn = (size_t)B * n;
+    return up((size_t)B * 4) + up((size_t)B * 8)      // kinds, seeds
+           + 2 * up(bn * 4)                            // perm, sort scratch
+           + up((size_t)B * 8)                         // footprints
+           + up(bn * 8)                                // offsets of every ordering
+           + 3 * up(bn * 8);                           // sorted block lists: off, end, life
+}
+
+size_t ws_score(uint32_t T)
+{
+    const size_t t1 = (size_t)T + 1;
+    return up((size_t)T * 8) + up(t1 * 8)              // load, delta
+           + 4 * up(t1 * 8)                            // C, S, PM, SM
+           + up((size_t)table_levels(T) * T * 8)       // range-max table
+           + 2 * ALIGN;                                // peak, t_peak
+}
+
+size_t ws_validate() { return up(8 * 8); }
+
+int check_trace_args(const lap_trace *tr)
+{
+    if (!tr) return LAP_E_NULL;
+    if (!tr->size || !tr->alloc || !tr->free_) return LAP_E_NULL;
+    if ((tr->gap_lo == nullptr) != (tr->gap_hi == nullptr)) return LAP_E_NULL;
+    if (tr->n_vars == 0 || tr->n_steps == 0) return LAP_E_SIZE;
+    if (tr->n_steps == 0xFFFFFFFFu) return LAP_E_SIZE;   // n_steps + 1 bins must fit 32 bits
+    return LAP_OK;
+}
+
+int check_ws(void *ws, size_t have, size_t need)
+{
+    if (!ws || ((uintptr_t)ws % ALIGN) != 0 || have < need) return LAP_E_WORKSPACE;
+    return LAP_OK;
+}
+
+bool g_prof = false;
+hipEvent_t g_ev[LAP_K_COUNT][2];
+bool g_ev_made[LAP_K_COUNT];
+bool g_ev_used[LAP_K_COUNT];
+
+struct ProfScope {
+    int id;
+    hipStream_t st;
+    bool on;
+    ProfScope(int id_, hipStream_t st_) : id(id_), st(st_), on(g_prof)
+    {
+        if (!on) return;
+        if (!g_ev_made[id]) {
+            if (hipEventCreate(&g_ev[id][0]) != hipSuccess || hipEventCreate(&g_ev[id][1]) != hipSuccess) {
+                on = false;
+                return;
+            }
+            g_ev_made[id] = true;
+        }
+        (void)hipEventRecord(g_ev[id][0], st);
+    }
+    ~ProfScope()
+    {
+        if (!on) return;
+        (void)hipEventRecord(g_ev[id][1], st);
+        g_ev_used[id] = true;
+    }
+};
+
+#define LAP_HIP(expr)                          \
+    do {                                       \
+        if ((expr) != hipSuccess) return LAP_E_HIP; \
+    } while (0)
+
+int load_profile_impl(const lap_trace *tr, uint64_t *load, uint64_t *peak, uint32_t *t_peak, uint64_t *delta,
+                      hipStream_t st)
+{
+    const uint32_t n = tr->n_vars, T = tr->n_steps;
+    LAP_HIP(lap::launch_fill_u64(delta, (size_t)T + 1, 0, st));
+    {
+        ProfScope p(LAP_K_LOAD_SCATTER, st);
+        LAP_HIP(lap::launch_delta(n, T, tr->size, tr->alloc, tr->free_, delta, st));
+    }
+    LAP_HIP(lap::launch_scan_peak(T, delta, load, peak, t_peak, st));
+    return LAP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lap_workspace_bytes(int which, uint32_t n_vars, uint32_t n_steps, uint32_t B)
+{
+    switch (which) {
+    case LAP_WS_LOAD_PROFILE: return ws_load(n_steps);
+    case LAP_WS_PLAN_POOL: return ws_plan(n_vars, B);
+    case LAP_WS_SCORE_SWAPS: return ws_score(n_steps);
+    case LAP_WS_VALIDATE: return ws_validate();
+    default: return 0;
+    }
+}
+
+const char *lap_status_string(int s)
+{
+    switch (s) {
+    case LAP_OK: return "ok";
+    case LAP_E_NULL: return "null pointer argument";
+    case LAP_E_SIZE: return "zero or unsupported size";
+    case LAP_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LAP_E_ORDERING: return "bad ordering descriptor";
+    case LAP_E_LINK: return "bad link bandwidth";
+    case LAP_E_TRACE: return "invalid trace content";
+    case LAP_E_RANGE: return "trace values out of the supported range";
+    case LAP_E_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int lap_profile_enable(int on)
+{
+    g_prof = on != 0;
+    for (int i = 0; i < LAP_K_COUNT; ++i) g_ev_used[i] = false;
+    return LAP_OK;
+}
+
+float lap_profile_last_ms(int id)
+{
+    if (id < 0 || id >= LAP_K_COUNT || !g_ev_used[id]) return -1.0f;
+    float ms = -1.0f;
+    if (hipEventElapsedTime(&ms, g_ev[id][0], g_ev[id][1]) != hipSuccess) return -1.0f;
+    return ms;
+}
+
+int lap_load_profile(const lap_trace *tr, uint64_t *load, uint64_t *peak, uint32_t *t_peak, void *ws,
+                     size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!load || !peak || !t_peak) return LAP_E_NULL;
+    rc = check_ws(ws, ws_bytes, ws_load(tr->n_steps));
+    if (rc) return rc;
+    Carver c(ws);
+    uint64_t *delta = c.take<uint64_t>((size_t)tr->n_steps + 1);
+    return load_profile_impl(tr, load, peak, t_peak, delta, (hipStream_t)hip_stream);
+}
+
+int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uint64_t *best_offsets,
+                  uint64_t *best_footprint, uint32_t *best_ordering, uint64_t *footprints, uint64_t *all_offsets,
+                  void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!ords || !best_offsets || !best_footprint || !best_ordering) return LAP_E_NULL;
+    if (B == 0) return LAP_E_SIZE;
+    for (uint32_t b = 0; b < B; ++b) {
+        if (ords[b].kind > LAP_ORD_EXPLICIT) return LAP_E_ORDERING;
+        if (ords[b].kind == LAP_ORD_EXPLICIT && ords[b].seed == 0) return LAP_E_ORDERING;
+    }
+    const uint32_t n = tr->n_vars;
+    rc = check_ws(ws, ws_bytes, ws_plan(n, B));
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t bn = (size_t)B * n;
+    Carver c(ws);
+    uint32_t *kinds = c.take<uint32_t>(B);
+    uint64_t *seeds = c.take<uint64_t>(B);
+    uint32_t *perm = c.take<uint32_t>(bn);
+    uint32_t *tmp = c.take<uint32_t>(bn);
+    uint64_t *fps_ws = c.take<uint64_t>(B);
+    uint64_t *offs_ws = c.take<uint64_t>(bn);
+    uint64_t *m_off = c.take<uint64_t>(bn);
+    uint64_t *m_end = c.take<uint64_t>(bn);
+    uint64_t *m_life = c.take<uint64_t>(bn);
+
+    // The descriptors are split into two arrays and copied from pageable host memory: the
+    // runtime stages such a copy before it returns.  The staging vectors live for the
+    // thread's lifetime all the same.
+    static thread_local std::vector<uint32_t> hk;
+    static thread_local std::vector<uint64_t> hs;
+    hk.resize(B);
+    hs.resize(B);
+    for (uint32_t b = 0; b < B; ++b) { hk[b] = ords[b].kind; hs[b] = ords[b].seed; }
+    LAP_HIP(hipMemcpyAsync(kinds, hk.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(hipMemcpyAsync(seeds, hs.data(), (size_t)B * 8, hipMemcpyHostToDevice, st));
+
+    uint64_t *fps = footprints ? footprints : fps_ws;
+    uint64_t *offs = all_offsets ? all_offsets : offs_ws;
+    {
+        ProfScope p(LAP_K_SORT, st);
+        LAP_HIP(lap::launch_sort_perm(n, B, tr->size, tr->alloc, tr->free_, kinds, seeds, perm, tmp, st));
+    }
+    {
+        ProfScope p(LAP_K_PLACE, st);
+        LAP_HIP(lap::launch_place(n, B, tr->size, tr->alloc, tr->free_, perm, m_off, m_end, m_life, offs, fps, st));
+    }
+    LAP_HIP(lap::launch_select(n, B, fps, offs, best_footprint, best_ordering, best_offsets, st));
+    return LAP_OK;
+}
+
+int lap_score_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, const uint64_t *load,
+                    uint8_t *candidate, int64_t *doa_ns, double *aoa, uint64_t *wdoa, uint64_t *peak_cut, void *ws,
+                    size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!candidate || !doa_ns || !aoa || !wdoa || !peak_cut) return LAP_E_NULL;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps) || link_GBps * 1000.0 >= 9.0e18) return LAP_E_LINK;
+    const long long bpus = llround(link_GBps * 1000.0);
+    if (bpus <= 0) return LAP_E_LINK;
+    const uint32_t n = tr->n_vars, T = tr->n_steps;
+    rc = check_ws(ws, ws_bytes, ws_score(T));
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t t1 = (size_t)T + 1;
+    Carver c(ws);
+    uint64_t *load_ws = c.take<uint64_t>(T);
+    uint64_t *delta = c.take<uint64_t>(t1);
+    uint64_t *C = c.take<uint64_t>(t1);
+    uint64_t *S = c.take<uint64_t>(t1);
+    uint64_t *PM = c.take<uint64_t>(t1);
+    uint64_t *SM = c.take<uint64_t>(t1);
+    const uint32_t levels = table_levels(T);
+    uint64_t *table = c.take<uint64_t>((size_t)levels * T);
+    uint64_t *peak = c.take<uint64_t>(1);
+    uint32_t *t_peak = c.take<uint32_t>(1);
+
+    if (!load) {
+        rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
+        if (rc) return rc;
+        load = load_ws;
+    }
+    LAP_HIP(lap::launch_swap_prefix(T, load, tr->step_ns, C, S, PM, SM, peak, t_peak, st));
+    LAP_HIP(lap::launch_sparse_table(T, load, table, levels, st));
+    {
+        ProfScope p(LAP_K_SCORE, st);
+        LAP_HIP(lap::launch_score(n, T, tr->size, tr->alloc, tr->free_, tr->gap_lo, tr->gap_hi, (uint64_t)bpus,
+                                  min_bytes, load, C, S, PM, SM, table, peak, t_peak, candidate, doa_ns, aoa, wdoa,
+                                  peak_cut, st));
+    }
+    return LAP_OK;
+}
+
+int lap_validate_trace(const lap_trace *tr, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    rc = check_ws(ws, ws_bytes, ws_validate());
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint64_t *out = (uint64_t *)ws;
+    LAP_HIP(lap::launch_fill_u64(out, 8, 0, st));
+    LAP_HIP(lap::launch_validate(tr->n_vars, tr->n_steps, tr->size, tr->alloc, tr->free_, tr->gap_lo, tr->gap_hi,
+                                 tr->step_ns, out, st));
+    uint64_t h[8];
+    LAP_HIP(hipMemcpyAsync(h, out, sizeof(h), hipMemcpyDeviceToHost, st));
+    LAP_HIP(hipStreamSynchronize(st));
+    if (h[0]) return LAP_E_TRACE;
+    if (h[1]) return LAP_E_RANGE;
+    const unsigned __int128 sum = ((unsigned __int128)h[3] << 32) + h[2];
+    if (sum >= ((unsigned __int128)1 << 63)) return LAP_E_RANGE;
+    if (h[4] > UINT64_MAX / tr->n_steps) return LAP_E_RANGE;
+    unsigned __int128 ns = tr->step_ns ? (((unsigned __int128)h[6] << 32) + h[5])
+                                       : (unsigned __int128)tr->n_steps * 1000000u;
+    if (ns >= ((unsigned __int128)1 << 53)) return LAP_E_RANGE;
+    return LAP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,35 @@
+// Host-side launch wrappers of the liblap kernels (one per kernel family).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lap {
+
+hipError_t launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st);
+hipError_t launch_delta(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                        uint64_t *delta, hipStream_t st);
+hipError_t launch_scan_peak(uint32_t T, const uint64_t *delta, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
+                            hipStream_t st);
+hipError_t launch_validate(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                           const uint32_t *gap_lo, const uint32_t *gap_hi, const uint64_t *step_ns, uint64_t *out8,
+                           hipStream_t st);
+
+hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                            const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
+                            hipStream_t st);
+hipError_t launch_place(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                        const uint32_t *perm, uint64_t *m_off, uint64_t *m_end, uint64_t *m_life, uint64_t *offs,
+                        uint64_t *fps, hipStream_t st);
+hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs, uint64_t *best_fp,
+                         uint32_t *best_idx, uint64_t *best_offsets, hipStream_t st);
+
+hipError_t launch_swap_prefix(uint32_t T, const uint64_t *load, const uint64_t *step_ns, uint64_t *C, uint64_t *S,
+                              uint64_t *PM, uint64_t *SM, uint64_t *peak, uint32_t *t_peak, hipStream_t st);
+hipError_t launch_sparse_table(uint32_t T, const uint64_t *load, uint64_t *table, uint32_t levels, hipStream_t st);
+hipError_t launch_score(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                        const uint32_t *gap_lo, const uint32_t *gap_hi, uint64_t bpus, uint64_t min_bytes,
+                        const uint64_t *load, const uint64_t *C, const uint64_t *S, const uint64_t *PM,
+                        const uint64_t *SM, const uint64_t *table, const uint64_t *peak, const uint32_t *t_peak,
+                        uint8_t *cand, int64_t *doa, double *aoa, uint64_t *wdoa, uint64_t *cut, hipStream_t st);
+
+}  // namespace lap

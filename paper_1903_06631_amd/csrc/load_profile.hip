@@ -1,0 +1,251 @@
+// Memory load profile and its peak (Section II Def. 2 and Def. 4, Eq. 1).
+//
+// The 2N alloc/free events (+size at alloc, -size at free) are binned by their
+// time key and reduced in place: delta[t] accumulates every event of step t
+// (a counting sort by time whose buckets are summed instead of stored; the
+// order of events inside one step does not affect the per-step load).  A
+// prefix sum over the T bins gives load[t]; the same pass takes the maximum
+// and the earliest step that reaches it.
+#include "lap_dev.h"
+#include "lap_kernels.h"
+
+namespace lap {
+
+__global__ void k_fill_u64(uint64_t *p, size_t n, uint64_t v)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+// Bins kept in LDS per workgroup, flushed once with global atomics.  Arithmetic
+// is modulo 2^64; the prefix sums are non-negative so wrap-around cancels.
+__global__ __launch_bounds__(256) void k_delta_lds(uint32_t n, uint32_t nbins,
+                                                   const uint64_t *__restrict__ size,
+                                                   const uint32_t *__restrict__ alloc,
+                                                   const uint32_t *__restrict__ free_,
+                                                   unsigned long long *delta)
+{
+    extern __shared__ unsigned long long bins[];
+    for (uint32_t i = threadIdx.x; i < nbins; i += blockDim.x) bins[i] = 0;
+    __syncthreads();
+    const uint32_t stride = gridDim.x * blockDim.x;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint64_t s = size[i];
+        atomicAdd(&bins[alloc[i]], (unsigned long long)s);
+        atomicAdd(&bins[free_[i]], (unsigned long long)(0ull - s));
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nbins; i += blockDim.x) {
+        const unsigned long long v = bins[i];
+        if (v) atomicAdd(&delta[i], v);
+    }
+}
+
+// Time-local variant for long time lines: a workgroup owns a contiguous chunk
+// of variables, finds the step range its events fall into and, when that
+// range fits the LDS bins, accumulates there; otherwise it adds to global
+// memory directly.
+__global__ __launch_bounds__(256) void k_delta_window(uint32_t n, uint32_t per_block, uint32_t lds_bins,
+                                                      const uint64_t *__restrict__ size,
+                                                      const uint32_t *__restrict__ alloc,
+                                                      const uint32_t *__restrict__ free_,
+                                                      unsigned long long *delta)
+{
+    extern __shared__ unsigned long long bins[];
+    __shared__ uint32_t s_lo, s_hi;
+    const uint32_t begin = blockIdx.x * per_block;
+    const uint32_t end = min(n, begin + per_block);
+    if (threadIdx.x == 0) { s_lo = 0xFFFFFFFFu; s_hi = 0; }
+    __syncthreads();
+    uint32_t lo = 0xFFFFFFFFu, hi = 0;
+    for (uint32_t i = begin + threadIdx.x; i < end; i += blockDim.x) {
+        lo = min(lo, alloc[i]);
+        hi = max(hi, free_[i]);
+    }
+    for (int m = WAVE / 2; m > 0; m >>= 1) {
+        lo = min(lo, (uint32_t)__shfl_xor(lo, m, WAVE));
+        hi = max(hi, (uint32_t)__shfl_xor(hi, m, WAVE));
+    }
+    if ((threadIdx.x & (WAVE - 1)) == 0) { atomicMin(&s_lo, lo); atomicMax(&s_hi, hi); }
+    __syncthreads();
+    lo = s_lo; hi = s_hi;
+    if (begin >= end) return;
+    const bool local = (hi - lo + 1) <= lds_bins;
+    if (local) {
+        const uint32_t nb = hi - lo + 1;
+        for (uint32_t i = threadIdx.x; i < nb; i += blockDim.x) bins[i] = 0;
+        __syncthreads();
+        for (uint32_t i = begin + threadIdx.x; i < end; i += blockDim.x) {
+            const uint64_t s = size[i];
+            atomicAdd(&bins[alloc[i] - lo], (unsigned long long)s);
+            atomicAdd(&bins[free_[i] - lo], (unsigned long long)(0ull - s));
+        }
+        __syncthreads();
+        for (uint32_t i = threadIdx.x; i < nb; i += blockDim.x) {
+            const unsigned long long v = bins[i];
+            if (v) atomicAdd(&delta[lo + i], v);
+        }
+    } else {
+        for (uint32_t i = begin + threadIdx.x; i < end; i += blockDim.x) {
+            const uint64_t s = size[i];
+            atomicAdd(&delta[alloc[i]], (unsigned long long)s);
+            atomicAdd(&delta[free_[i]], (unsigned long long)(0ull - s));
+        }
+    }
+}
+
+// One workgroup: inclusive prefix sum of delta[0..T) -> load, running maximum
+// and earliest argmax.  ITEMS consecutive bins per thread, wave scan, LDS
+// carry between waves, register carry between tiles.
+constexpr int SCAN_THREADS = 1024;
+constexpr int SCAN_ITEMS = 4;
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_peak(uint32_t T, const uint64_t *__restrict__ delta,
+                                                            uint64_t *__restrict__ load,
+                                                            uint64_t *__restrict__ peak, uint32_t *__restrict__ t_peak)
+{
+    __shared__ uint64_t wsum[SCAN_THREADS / WAVE];
+    __shared__ uint64_t wmax[SCAN_THREADS / WAVE];
+    __shared__ uint32_t warg[SCAN_THREADS / WAVE];
+    const int tid = threadIdx.x, l = tid & (WAVE - 1), w = tid / WAVE;
+    uint64_t carry = 0, best = 0;
+    uint32_t best_t = 0;
+    bool have = false;
+    for (uint32_t base = 0; base < T; base += SCAN_THREADS * SCAN_ITEMS) {
+        const uint32_t t0 = base + tid * SCAN_ITEMS;
+        uint64_t v[SCAN_ITEMS];
+        uint64_t sum = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            v[k] = (t0 + k < T) ? delta[t0 + k] : 0;
+            sum += v[k];
+        }
+        const uint64_t incl = wave_scan_add(sum);
+        if (l == WAVE - 1) wsum[w] = incl;
+        __syncthreads();
+        uint64_t pre = carry;
+        for (int k = 0; k < w; ++k) pre += wsum[k];
+        uint64_t total = 0;
+        for (int k = 0; k < SCAN_THREADS / WAVE; ++k) total += wsum[k];
+        uint64_t run = pre + incl - sum;
+#pragma unroll
+        for (int k = 0; k < SCAN_ITEMS; ++k) {
+            run += v[k];
+            if (t0 + k < T) {
+                load[t0 + k] = run;
+                if (!have || run > best) { best = run; best_t = t0 + k; have = true; }
+            }
+        }
+        carry += total;
+        __syncthreads();
+    }
+    // (value, earliest step) reduction
+    if (!have) { best = 0; best_t = 0xFFFFFFFFu; }
+    for (int m = WAVE / 2; m > 0; m >>= 1) {
+        const uint64_t ov = shfl_xor64(best, m);
+        const uint32_t ot = (uint32_t)__shfl_xor(best_t, m, WAVE);
+        if (ov > best || (ov == best && ot < best_t)) { best = ov; best_t = ot; }
+    }
+    if (l == 0) { wmax[w] = best; warg[w] = best_t; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int k = 1; k < SCAN_THREADS / WAVE; ++k)
+            if (wmax[k] > best || (wmax[k] == best && warg[k] < best_t)) { best = wmax[k]; best_t = warg[k]; }
+        *peak = best;
+        *t_peak = best_t;
+    }
+}
+
+// Trace content checks (flags[0] = trace error, flags[1] = a size >= 2^53),
+// and the sums the range checks need: sizes split in 32-bit halves so that
+// neither partial sum can overflow, max size, and the same for step_ns.
+__global__ __launch_bounds__(256) void k_validate(uint32_t n, uint32_t T, const uint64_t *__restrict__ size,
+                                                  const uint32_t *__restrict__ alloc,
+                                                  const uint32_t *__restrict__ free_,
+                                                  const uint32_t *__restrict__ gap_lo,
+                                                  const uint32_t *__restrict__ gap_hi,
+                                                  const uint64_t *__restrict__ step_ns,
+                                                  unsigned long long *out /* [8] zeroed */)
+{
+    const uint32_t stride = gridDim.x * blockDim.x;
+    const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned long long bad = 0, big = 0, lo = 0, hi = 0, mx = 0, nlo = 0, nhi = 0;
+    for (uint32_t i = g; i < n; i += stride) {
+        const uint64_t s = size[i];
+        const uint32_t a = alloc[i], f = free_[i];
+        if (s == 0 || a >= f || f > T) bad = 1;
+        if (gap_lo && (a < f) && (gap_lo[i] < a || gap_hi[i] > f - 1 || gap_lo[i] > gap_hi[i])) bad = 1;
+        if (s >= (1ull << 53)) big = 1;
+        lo += s & 0xFFFFFFFFull;
+        hi += s >> 32;
+        mx = s > mx ? s : mx;
+    }
+    if (step_ns)
+        for (uint32_t t = g; t < T; t += stride) {
+            const uint64_t ns = step_ns[t];
+            if (ns == 0) bad = 1;
+            if (ns >= (1ull << 53)) big = 1;
+            nlo += ns & 0xFFFFFFFFull;
+            nhi += ns >> 32;
+        }
+    if (bad) atomicOr(&out[0], 1ull);
+    if (big) atomicOr(&out[1], 1ull);
+    lo = wave_reduce_add(lo); hi = wave_reduce_add(hi); mx = wave_reduce_max(mx);
+    nlo = wave_reduce_add(nlo); nhi = wave_reduce_add(nhi);
+    if ((threadIdx.x & (WAVE - 1)) == 0) {
+        atomicAdd(&out[2], lo); atomicAdd(&out[3], hi); atomicMax(&out[4], mx);
+        atomicAdd(&out[5], nlo); atomicAdd(&out[6], nhi);
+    }
+}
+
+// ---------------------------------------------------------------------------
+
+hipError_t launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st)
+{
+    if (n == 0) return hipSuccess;
+    const int threads = 256;
+    const size_t want = (n + threads - 1) / threads;
+    const int blocks = (int)(want < 2048 ? want : 2048);
+    hipLaunchKernelGGL(k_fill_u64, dim3(blocks), dim3(threads), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_delta(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                        uint64_t *delta, hipStream_t st)
+{
+    const uint32_t nbins = T + 1;
+    constexpr uint32_t LDS_BINS = 8192;            // 64 KiB of u64 bins per workgroup
+    if (nbins <= LDS_BINS) {
+        uint32_t blocks = (n + 256 * 16 - 1) / (256 * 16);
+        blocks = blocks < 1 ? 1 : (blocks > 1024 ? 1024 : blocks);
+        hipLaunchKernelGGL(k_delta_lds, dim3(blocks), dim3(256), nbins * sizeof(uint64_t), st, n, nbins, size, alloc,
+                           free_, (unsigned long long *)delta);
+    } else {
+        const uint32_t per_block = 16384;
+        const uint32_t blocks = (n + per_block - 1) / per_block;
+        hipLaunchKernelGGL(k_delta_window, dim3(blocks), dim3(256), LDS_BINS * sizeof(uint64_t), st, n, per_block,
+                           LDS_BINS, size, alloc, free_, (unsigned long long *)delta);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_scan_peak(uint32_t T, const uint64_t *delta, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
+                            hipStream_t st)
+{
+    hipLaunchKernelGGL(k_scan_peak, dim3(1), dim3(SCAN_THREADS), 0, st, T, delta, load, peak, t_peak);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                           const uint32_t *gap_lo, const uint32_t *gap_hi, const uint64_t *step_ns, uint64_t *out8,
+                           hipStream_t st)
+{
+    uint32_t blocks = (n + 255) / 256;
+    blocks = blocks > 1024 ? 1024 : blocks;
+    hipLaunchKernelGGL(k_validate, dim3(blocks), dim3(256), 0, st, n, T, size, alloc, free_, gap_lo, gap_hi, step_ns,
+                       (unsigned long long *)out8);
+    return hipGetLastError();
+}
+
+}  // namespace lap

@@ -1,0 +1,131 @@
+// Placement orders (Section III-C sorts by size, largest first; the other
+// kinds are the extra heuristic orders evaluated in parallel).
+//
+// One wave per ordering produces perm[b][rank] = variable index: a stable
+// least-significant-digit radix sort (8-bit digits) of the indices 0..N-1 by a
+// 64-bit key.  The key is a pure function of (ordering, index) and is
+// recomputed from the trace on every pass, so only the 4-byte indices move.
+// Descending kinds sort the bitwise complement of the key; stability keeps
+// equal keys in ascending index order.  A pass whose digit is the same for
+// every variable is skipped.
+#include "lap_dev.h"
+#include "lap_kernels.h"
+
+namespace lap {
+
+__device__ __forceinline__ uint64_t order_key(uint32_t kind, uint64_t seed, uint32_t i,
+                                              const uint64_t *__restrict__ size,
+                                              const uint32_t *__restrict__ alloc,
+                                              const uint32_t *__restrict__ free_)
+{
+    switch (kind) {
+    case 0: return ~size[i];
+    case 1: return ~(uint64_t)(free_[i] - alloc[i]);
+    case 2: return ~(size[i] * (uint64_t)(free_[i] - alloc[i]));
+    case 3: return (uint64_t)alloc[i];
+    default: return mix64(seed, i);
+    }
+}
+
+__global__ __launch_bounds__(64) void k_sort_perm(uint32_t n, const uint64_t *__restrict__ size,
+                                                  const uint32_t *__restrict__ alloc,
+                                                  const uint32_t *__restrict__ free_,
+                                                  const uint32_t *__restrict__ kinds,
+                                                  const uint64_t *__restrict__ seeds,
+                                                  uint32_t *perm_all, uint32_t *tmp_all)
+{
+    __shared__ uint32_t hist[256];
+    const uint32_t b = blockIdx.x;
+    const int l = lane_id();
+    const uint32_t kind = kinds[b];
+    const uint64_t seed = seeds[b];
+    uint32_t *perm = perm_all + (size_t)b * n;
+    uint32_t *tmp = tmp_all + (size_t)b * n;
+
+    if (kind == 5) {
+        // caller-supplied permutation: copy.  Indices are clamped so that a malformed
+        // array can never cause an out-of-range access downstream.
+        const uint32_t *src = (const uint32_t *)(uintptr_t)seed;
+        for (uint32_t i = l; i < n; i += WAVE) perm[i] = min(src[i], n - 1);
+        return;
+    }
+
+    // cur == nullptr means the identity (no buffer read yet)
+    const uint32_t *cur = nullptr;
+    uint32_t *dst = perm;
+    const uint64_t lt_mask = (1ull << l) - 1ull;
+    for (int pass = 0; pass < 8; ++pass) {
+        const int shift = pass * 8;
+        for (int k = l; k < 256; k += WAVE) hist[k] = 0;
+        __syncthreads();
+        for (uint32_t base = 0; base < n; base += WAVE) {
+            const uint32_t r = base + l;
+            if (r < n) {
+                const uint32_t i = cur ? cur[r] : r;
+                const uint32_t d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
+                atomicAdd(&hist[d], 1u);
+            }
+        }
+        __syncthreads();
+        // exclusive scan of the 256 counts (4 per lane), and detection of a constant digit
+        uint32_t c[4], s = 0;
+        bool all_in_one = false;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { c[k] = hist[l * 4 + k]; s += c[k]; all_in_one |= (c[k] == n); }
+        const bool skip = ballot(all_in_one) != 0;
+        uint32_t incl = s;
+#pragma unroll
+        for (int dlt = 1; dlt < WAVE; dlt <<= 1) {
+            const uint32_t t = __shfl_up(incl, dlt, WAVE);
+            if (l >= dlt) incl += t;
+        }
+        uint32_t run = incl - s;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { hist[l * 4 + k] = run; run += c[k]; }
+        __syncthreads();
+        if (skip) continue;
+        // stable scatter, one tile of 64 ranks at a time
+        for (uint32_t base = 0; base < n; base += WAVE) {
+            const uint32_t r = base + l;
+            const bool act = r < n;
+            uint32_t i = 0, d = 0;
+            if (act) {
+                i = cur ? cur[r] : r;
+                d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
+            }
+            uint64_t same = ballot(act);
+#pragma unroll
+            for (int bit = 0; bit < 8; ++bit) {
+                const uint64_t m = ballot(act && ((d >> bit) & 1u));
+                same &= ((d >> bit) & 1u) ? m : ~m;
+            }
+            const uint32_t rank = (uint32_t)__popcll(same & lt_mask);
+            const uint32_t cnt = (uint32_t)__popcll(same);
+            uint32_t pos = 0;
+            if (act) pos = hist[d] + rank;
+            __syncthreads();
+            if (act && rank == 0) hist[d] += cnt;
+            __syncthreads();
+            if (act) dst[pos] = i;
+        }
+        __syncthreads();
+        cur = dst;
+        dst = (dst == perm) ? tmp : perm;
+    }
+    if (cur == nullptr) {
+        for (uint32_t i = l; i < n; i += WAVE) perm[i] = i;
+    } else if (cur != perm) {
+        for (uint32_t i = l; i < n; i += WAVE) perm[i] = tmp[i];
+    }
+}
+
+hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                            const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
+                            hipStream_t st)
+{
+    hipLaunchKernelGGL(k_sort_perm, dim3(B), dim3(WAVE), 0, st, n, size, alloc, free_, kinds, seeds, perm, tmp);
+    return hipGetLastError();
+}
+
+}  // namespace lap

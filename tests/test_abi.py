@@ -1,0 +1,105 @@
+"""Host-only checks of the C ABI: exported symbols, status strings, argument validation.
+
+None of these reaches a HIP call: every error below is detected before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lap():
+    import paper_1903_06631_amd as lap
+    if not os.path.exists(lap.lib_path()):
+        from paper_1903_06631_amd import build
+        build.build()
+    lap.load_library()
+    return lap
+
+
+def test_every_declared_symbol_is_exported(lap):
+    hdr = open(os.path.join(ROOT, "include", "lap.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(lap_[a-z_]+)\s*\(", hdr))
+    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_workspace_bytes",
+            "lap_validate_trace", "lap_status_string"} <= declared
+    lib = lap.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lap):
+    seen = {lap.status_string(s) for s in range(0, -9, -1)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert lap.status_string(-99) == "unknown status"
+
+
+def test_workspace_sizes(lap):
+    assert lap.workspace_bytes(0, 100, 22) >= 23 * 8
+    assert lap.workspace_bytes(1, 120, 22, 16) >= 16 * 120 * (4 + 8)
+    assert lap.workspace_bytes(2, 120, 22) >= 6 * 23 * 8
+    assert lap.workspace_bytes(3, 1, 1) > 0
+    assert lap.workspace_bytes(42, 1, 1) == 0
+    assert lap.workspace_bytes(1, 120, 22, 32) > lap.workspace_bytes(1, 120, 22, 16)
+
+
+def test_argument_errors(lap):
+    from paper_1903_06631_amd.binding import _Ordering, _Trace
+    lib = lap.load_library()
+    fake = 0x1000   # never dereferenced: all of these fail in the host-side checks
+    good = _Trace(4, 3, fake, fake, fake, None, None, None)
+    ords = (_Ordering * 2)()
+    ords[0].kind, ords[1].kind = 0, 4
+
+    # NULL pointers
+    assert lib.lap_load_profile(None, fake, fake, fake, fake, 1 << 20, None) == -1
+    assert lib.lap_load_profile(C.byref(good), None, fake, fake, fake, 1 << 20, None) == -1
+    assert lib.lap_load_profile(C.byref(_Trace(4, 3, None, fake, fake, None, None, None)),
+                                fake, fake, fake, fake, 1 << 20, None) == -1
+    assert lib.lap_load_profile(C.byref(_Trace(4, 3, fake, fake, fake, fake, None, None)),
+                                fake, fake, fake, fake, 1 << 20, None) == -1   # only one of the gap arrays
+    assert lib.lap_plan_pool(C.byref(good), None, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -1
+    assert lib.lap_plan_pool(C.byref(good), ords, 2, None, fake, fake, None, None, fake, 1 << 30, None) == -1
+    assert lib.lap_score_swaps(C.byref(good), 64.0, 1, None, None, fake, fake, fake, fake, fake, 1 << 20, None) == -1
+    # sizes
+    assert lib.lap_load_profile(C.byref(_Trace(0, 3, fake, fake, fake, None, None, None)),
+                                fake, fake, fake, fake, 1 << 20, None) == -2
+    assert lib.lap_load_profile(C.byref(_Trace(4, 0, fake, fake, fake, None, None, None)),
+                                fake, fake, fake, fake, 1 << 20, None) == -2
+    assert lib.lap_plan_pool(C.byref(good), ords, 0, fake, fake, fake, None, None, fake, 1 << 30, None) == -2
+    # workspace: NULL, misaligned, too small
+    assert lib.lap_load_profile(C.byref(good), fake, fake, fake, None, 1 << 20, None) == -3
+    assert lib.lap_load_profile(C.byref(good), fake, fake, fake, fake + 8, 1 << 20, None) == -3
+    assert lib.lap_load_profile(C.byref(good), fake, fake, fake, fake, 8, None) == -3
+    need = lap.workspace_bytes(1, 4, 3, 2)
+    assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, need - 1, None) == -3
+    # orderings
+    ords[1].kind = 6
+    assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -4
+    ords[1].kind, ords[1].seed = 5, 0
+    assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -4
+    # link
+    for link in (0.0, -3.0, float("nan"), float("inf"), 1e-9):
+        assert lib.lap_score_swaps(C.byref(good), link, 1, None, fake, fake, fake, fake, fake,
+                                   fake, 1 << 20, None) == -5
+
+
+def test_no_cpu_fallback(lap, monkeypatch, tmp_path):
+    """A missing library is an import-time error, never a silent CPU path."""
+    from paper_1903_06631_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()
+
+
+def test_product_never_imports_oracle():
+    pkg = os.path.join(ROOT, "paper_1903_06631_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                txt = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in txt.lower() or f == "__init__.py" and "oracle" not in txt, (dirpath, f)

@@ -1,0 +1,173 @@
+"""HIP path vs the CPU oracle, element by element, through the C ABI.  Integer results are
+bit-exact; AOA (one binary64 multiply or divide) is compared bit for bit as well."""
+import numpy as np
+import pytest
+
+from gpu_util import oracle_all_orderings, u64
+from helpers import mk_trace
+from traces import make_config, make_orderings, random_trace, tile_in_time
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lap():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_1903_06631_amd as lap
+    lap.load_library()
+    return lap
+
+
+def _check_load(lap, oracle, tr):
+    dt = lap.DeviceTrace(tr)
+    got = lap.load_profile(dt)
+    load, peak, tpk = oracle.load_profile(tr)
+    assert np.array_equal(u64(got["load"]), load)
+    assert int(u64(got["peak"])[0]) == peak
+    assert int(got["t_peak"].item()) == tpk
+    return dt, got
+
+
+@pytest.mark.parametrize("seed,n,T", [(0, 1, 1), (1, 7, 3), (2, 1000, 64), (3, 5000, 257), (4, 70001, 4099),
+                                      (5, 30000, 9000), (6, 200000, 20000), (7, 63, 8192), (8, 65, 8191)])
+def test_load_profile_random(lap, oracle_mod, seed, n, T):
+    tr = random_trace(seed, n, T, size_choices=[1, 2, 3, 1000, 77777] if seed % 2 else None)
+    _check_load(lap, oracle_mod, tr)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_load_profile_configs(lap, oracle_mod, cfg):
+    _check_load(lap, oracle_mod, make_config(cfg))
+
+
+def test_load_profile_tiled_long_timeline(lap, oracle_mod):
+    # many iterations back to back: long time line, time-local chunks (the stress layout)
+    tr = tile_in_time(make_config(3), 40)
+    _check_load(lap, oracle_mod, tr)
+
+
+def test_load_profile_peak_ties_and_extremes(lap, oracle_mod):
+    tr = mk_trace([512, 512, 512], [0, 2, 4], [1, 3, 5], T=6)          # three equal peaks -> earliest
+    _check_load(lap, oracle_mod, tr)
+    tr = mk_trace([(1 << 53) - 1, (1 << 53) - 1, 1], [0, 0, 1], [2, 1, 2], T=2)   # largest legal sizes
+    _check_load(lap, oracle_mod, tr)
+
+
+def _check_plan(lap, oracle, tr, kinds, seeds, explicit_np=None, which=None):
+    import torch
+    dt = lap.DeviceTrace(tr)
+    explicit = None
+    if explicit_np:
+        explicit = {b: torch.from_numpy(p.astype(np.uint32).view(np.int32)).to(dt.device)
+                    for b, p in explicit_np.items()}
+    got = lap.plan_pool(dt, kinds, seeds, explicit=explicit)
+    ref = oracle_all_orderings(oracle, tr, kinds, seeds, explicit_np, which)
+    all_off = u64(got["all_offsets"])
+    fps = u64(got["footprints"])
+    for b, (_, off, fp) in ref.items():
+        assert np.array_equal(all_off[b], off), f"ordering {b} kind {kinds[b]}"
+        assert fps[b] == fp, f"ordering {b}"
+    # properties that hold for every ordering, whatever was sampled
+    assert np.array_equal(fps, (all_off + tr.size[None, :]).max(axis=1))
+    best = int(got["best_ordering"].item())
+    assert best == int(np.argmin(fps)) and int(u64(got["best_footprint"])[0]) == int(fps.min())
+    assert np.array_equal(u64(got["best_offsets"]), all_off[best])
+    _, peak, _ = oracle.load_profile(tr)
+    assert (fps >= peak).all()
+    return got
+
+
+@pytest.mark.parametrize("seed,n,T", [(0, 1, 1), (1, 2, 2), (2, 64, 5), (3, 65, 9), (4, 300, 12), (5, 511, 30),
+                                      (6, 512, 30), (7, 513, 7), (8, 1500, 40), (9, 2600, 90)])
+def test_plan_pool_random(lap, oracle_mod, seed, n, T):
+    # coarse steps and repeated sizes force ties in every key; n spans the 512-entry
+    # recent list and several merges
+    tr = random_trace(50 + seed, n, T, size_choices=[1, 1, 2, 3, 5, 8, 13, 64])
+    kinds, seeds = make_orderings(24)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds)
+
+
+def test_plan_pool_wide_sizes(lap, oracle_mod):
+    tr = random_trace(99, 1200, 50, granule=1)          # byte-granular sizes 2^9 .. 2^23
+    kinds, seeds = make_orderings(16)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds)
+
+
+def test_plan_pool_explicit_permutations(lap, oracle_mod):
+    tr = random_trace(7, 700, 20, size_choices=[1, 2, 3, 4])
+    rng = np.random.default_rng(5)
+    explicit = {0: rng.permutation(700).astype(np.uint32), 2: np.arange(700, dtype=np.uint32)[::-1].copy()}
+    kinds = np.array([5, 0, 5, 4], np.uint32)
+    seeds = np.array([0, 0, 0, 99], np.uint64)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds, explicit_np=explicit)
+
+
+def test_plan_pool_special_cases(lap, oracle_mod):
+    kinds, seeds = make_orderings(8)
+    # identical lifetimes: blocks stack, footprint = sum of sizes
+    tr = mk_trace([512 * (1 + k % 7) for k in range(600)], [1] * 600, [4] * 600, T=5)
+    got = _check_plan(lap, oracle_mod, tr, kinds, seeds)
+    assert (u64(got["footprints"]) == int(tr.size.sum())).all()
+    # disjoint lifetimes: every offset 0
+    tr = mk_trace([512 * (1 + k % 5) for k in range(300)], list(range(300)), list(range(1, 301)))
+    got = _check_plan(lap, oracle_mod, tr, kinds, seeds)
+    assert not u64(got["all_offsets"]).any()
+    # largest legal sizes
+    tr = mk_trace([(1 << 53) - 1, 1 << 52, 12345], [0, 0, 0], [1, 1, 1])
+    _check_plan(lap, oracle_mod, tr, kinds, seeds)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_plan_pool_configs(lap, oracle_mod, cfg):
+    tr = make_config(cfg)
+    kinds, seeds = make_orderings(tr.meta["B"])
+    _check_plan(lap, oracle_mod, tr, kinds, seeds)
+
+
+def _check_scores(lap, oracle, tr, link, min_bytes, use_gaps=True, pass_load=True):
+    dt = lap.DeviceTrace(tr, use_gaps=use_gaps)
+    load = lap.load_profile(dt)["load"] if pass_load else None
+    got = lap.score_swaps(dt, link, min_bytes, load=load)
+    ref = oracle.score_swaps(tr, link, min_bytes, use_gaps=use_gaps)
+    assert np.array_equal(got["candidate"].cpu().numpy(), ref["candidate"])
+    assert np.array_equal(got["doa_ns"].cpu().numpy(), ref["doa_ns"])
+    assert np.array_equal(got["aoa"].cpu().numpy().view(np.uint64), ref["aoa"].view(np.uint64))
+    assert np.array_equal(u64(got["wdoa"]), ref["wdoa"])
+    assert np.array_equal(u64(got["peak_cut"]), ref["peak_cut"])
+
+
+@pytest.mark.parametrize("seed,n,T,link", [(0, 1, 1, 64.0), (1, 5, 2, 64.0), (2, 300, 17, 64.0), (3, 5000, 300, 0.5),
+                                           (4, 20000, 1025, 12.345), (5, 3000, 5000, 900.0), (6, 777, 33, 1e-3)])
+def test_score_swaps_random(lap, oracle_mod, seed, n, T, link):
+    tr = random_trace(700 + seed, n, T, with_step_ns=(seed % 2 == 0))
+    _check_scores(lap, oracle_mod, tr, link, 1 << 14, use_gaps=True, pass_load=(seed % 3 != 0))
+    _check_scores(lap, oracle_mod, tr, link, 1 << 14, use_gaps=False)
+
+
+@pytest.mark.parametrize("cfg", [1, 3, 5])
+def test_score_swaps_configs(lap, oracle_mod, cfg):
+    tr = make_config(cfg)
+    _check_scores(lap, oracle_mod, tr, tr.meta["link_GBps"], tr.meta["min_bytes"])
+
+
+def test_validate_trace(lap, oracle_mod):
+    tr = random_trace(3, 1000, 40, with_step_ns=True)
+    assert lap.validate_trace(lap.DeviceTrace(tr)) == 0 == oracle_mod.validate_trace(tr)
+
+    def broken(**kw):
+        t = random_trace(3, 1000, 40, with_step_ns=True)
+        for k, (i, v) in kw.items():
+            getattr(t, k)[i] = v
+        return t
+    cases = [broken(size=(5, 0)), broken(free=(7, 41)), broken(alloc=(9, 40)), broken(step_ns=(3, 0)),
+             broken(size=(11, 1 << 53)), broken(step_ns=(2, 1 << 53))]
+    t = random_trace(3, 1000, 40); t.gap_lo[4] = t.gap_hi[4] + 1; cases.append(t)
+    t = random_trace(3, 1000, 40); t.gap_hi[4] = t.free[4]; cases.append(t)
+    t = random_trace(3, 1000, 40); t.size[:] = (1 << 53) - 1; t.size = np.tile(t.size, 2)[:1025]
+    t.alloc = np.tile(t.alloc, 2)[:1025]; t.free = np.tile(t.free, 2)[:1025]
+    t.gap_lo = t.alloc.copy(); t.gap_hi = (t.free - 1).astype(np.uint32); cases.append(t)   # sum >= 2^63
+    for t in cases:
+        want = oracle_mod.validate_trace(t)
+        assert want in (-6, -7)
+        assert lap.validate_trace(lap.DeviceTrace(t)) == want
