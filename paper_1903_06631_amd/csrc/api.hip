@@ -33,14 +33,25 @@ inline uint32_t table_levels(uint32_t T)
 
 size_t ws_load(uint32_t T) { return up(((size_t)T + 1) * 8); }
 
-size_t ws_plan(uint32_t n, uint32_t B)
+// block lists of the placement kernels: the 64-bit path needs off/end/life per ordering, the
+// packed 32-bit path a packed main list with lifetimes, the per-step lists and their counters
+size_t ws_plan_lists(uint32_t n, uint32_t T, uint32_t B)
 {
     const size_t bn = (size_t)B * n;
-    return up((size_t)B * 4) + up((size_t)B * 8)      // kinds, seeds
-           + 2 * up(bn * 4)                            // perm, sort scratch
-           + up((size_t)B * 8)                         // footprints
-           + up(bn * 8)                                // offsets of every ordering
-           + 3 * up(bn * 8);                           // sorted block lists: off, end, life
+    const size_t wide = 3 * up(bn * 8);
+    const size_t fast = 2 * up(bn * 8) + up(bn * lap::PLAN_CL * 8) + 2 * up((size_t)B * T * 4);
+    return wide > fast ? wide : fast;
+}
+
+size_t ws_plan(uint32_t n, uint32_t T, uint32_t B)
+{
+    const size_t bn = (size_t)B * n;
+    return up(sizeof(lap::PlanHeader)) + 2 * up(((size_t)T + 2) * 4)   // header, step counts, list starts
+           + up((size_t)B * 4) + up((size_t)B * 8)                    // kinds, seeds
+           + 2 * up(bn * 4)                                            // perm, sort scratch
+           + up((size_t)B * 8)                                         // footprints
+           + up(bn * 8)                                                // offsets of every ordering
+           + ws_plan_lists(n, T, B);
 }
 
 size_t ws_score(uint32_t T)
@@ -125,7 +136,7 @@ size_t lap_workspace_bytes(int which, uint32_t n_vars, uint32_t n_steps, uint32_
 {
     switch (which) {
     case LAP_WS_LOAD_PROFILE: return ws_load(n_steps);
-    case LAP_WS_PLAN_POOL: return ws_plan(n_vars, B);
+    case LAP_WS_PLAN_POOL: return ws_plan(n_vars, n_steps, B);
     case LAP_WS_SCORE_SWAPS: return ws_score(n_steps);
     case LAP_WS_VALIDATE: return ws_validate();
     default: return 0;
@@ -188,21 +199,33 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
         if (ords[b].kind > LAP_ORD_EXPLICIT) return LAP_E_ORDERING;
         if (ords[b].kind == LAP_ORD_EXPLICIT && ords[b].seed == 0) return LAP_E_ORDERING;
     }
-    const uint32_t n = tr->n_vars;
-    rc = check_ws(ws, ws_bytes, ws_plan(n, B));
+    const uint32_t n = tr->n_vars, T = tr->n_steps;
+    if ((uint64_t)n * lap::PLAN_CL >= (1ull << 32)) return LAP_E_SIZE;
+    rc = check_ws(ws, ws_bytes, ws_plan(n, T, B));
     if (rc) return rc;
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t bn = (size_t)B * n;
     Carver c(ws);
+    lap::PlanHeader *hdr = c.take<lap::PlanHeader>(1);
+    uint32_t *cntd = c.take<uint32_t>((size_t)T + 2);
+    uint32_t *lstart = c.take<uint32_t>((size_t)T + 2);
     uint32_t *kinds = c.take<uint32_t>(B);
     uint64_t *seeds = c.take<uint64_t>(B);
     uint32_t *perm = c.take<uint32_t>(bn);
     uint32_t *tmp = c.take<uint32_t>(bn);
     uint64_t *fps_ws = c.take<uint64_t>(B);
     uint64_t *offs_ws = c.take<uint64_t>(bn);
-    uint64_t *m_off = c.take<uint64_t>(bn);
-    uint64_t *m_end = c.take<uint64_t>(bn);
-    uint64_t *m_life = c.take<uint64_t>(bn);
+    // the two placement kernels never both run: their lists share one region
+    Carver cw((char *)ws + c.used), cf((char *)ws + c.used);
+    uint64_t *m_off = cw.take<uint64_t>(bn);
+    uint64_t *m_end = cw.take<uint64_t>(bn);
+    uint64_t *m_life = cw.take<uint64_t>(bn);
+    uint64_t *f_oe = cf.take<uint64_t>(bn);
+    uint64_t *f_life = cf.take<uint64_t>(bn);
+    const uint64_t capL = (uint64_t)n * lap::PLAN_CL;
+    uint64_t *f_L = cf.take<uint64_t>((size_t)B * capL);
+    uint32_t *l_ns = cf.take<uint32_t>((size_t)B * T);
+    uint32_t *l_nu = cf.take<uint32_t>((size_t)B * T);
 
     // The descriptors are split into two arrays and copied from pageable host memory: the
     // runtime stages such a copy before it returns.  The staging vectors live for the
@@ -221,9 +244,19 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
         ProfScope p(LAP_K_SORT, st);
         LAP_HIP(lap::launch_sort_perm(n, B, tr->size, tr->alloc, tr->free_, kinds, seeds, perm, tmp, st));
     }
+    static_assert(sizeof(lap::PlanHeader) % 8 == 0, "header is cleared in 64-bit words");
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)hdr, sizeof(lap::PlanHeader) / 8, 0, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)cntd, ((size_t)T + 2) / 2, 0, st));
+    LAP_HIP(lap::launch_plan_prep(n, T, tr->size, tr->alloc, tr->free_, cntd, lstart, hdr, st));
+    // per-step entry counts start at zero (cleared as 64-bit words, the regions are padded)
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)l_ns, ((size_t)B * T + 1) / 2, 0, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)l_nu, ((size_t)B * T + 1) / 2, 0, st));
     {
         ProfScope p(LAP_K_PLACE, st);
-        LAP_HIP(lap::launch_place(n, B, tr->size, tr->alloc, tr->free_, perm, m_off, m_end, m_life, offs, fps, st));
+        LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, hdr, lstart, f_oe, f_life, f_L,
+                                       capL, l_ns, l_nu, offs, fps, st));
+        LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, hdr, m_off, m_end, m_life, offs,
+                                       fps, st));
     }
     LAP_HIP(lap::launch_select(n, B, fps, offs, best_footprint, best_ordering, best_offsets, st));
     return LAP_OK;

@@ -5,6 +5,17 @@
 
 namespace lap {
 
+// Per-call facts about the trace, computed on the device before placement.
+struct PlanHeader {
+    unsigned long long or_sizes;   // bitwise OR of all sizes
+    unsigned long long sum_sizes;  // sum of all sizes (bytes)
+    uint32_t n_multi;              // variables that live for more than one step
+    uint32_t shift;                // log2 of the offset granule: ctz(or_sizes)
+    uint32_t fast;                 // 1: sum_sizes >> shift fits 32 bits -> packed 32-bit path
+    uint32_t mode1;                // 1: per-step lists are in use (sum of lifetimes <= PLAN_CL * N)
+};
+constexpr uint32_t PLAN_CL = 6;
+
 hipError_t launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st);
 hipError_t launch_delta(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                         uint64_t *delta, hipStream_t st);
@@ -17,9 +28,15 @@ hipError_t launch_validate(uint32_t n, uint32_t T, const uint64_t *size, const u
 hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                             const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
                             hipStream_t st);
-hipError_t launch_place(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
-                        const uint32_t *perm, uint64_t *m_off, uint64_t *m_end, uint64_t *m_life, uint64_t *offs,
-                        uint64_t *fps, hipStream_t st);
+hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                            const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st);
+hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
+                             const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr,
+                             const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *L, uint64_t capL,
+                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st);
+hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc,
+                             const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr, uint64_t *m_off,
+                             uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st);
 hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs, uint64_t *best_fp,
                          uint32_t *best_idx, uint64_t *best_offsets, hipStream_t st);
 

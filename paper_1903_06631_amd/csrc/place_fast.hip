@@ -1,0 +1,616 @@
+// First-fit placement of every variable under many orderings (Section III-C):
+// the 32-bit granule path.
+//
+// Offsets are multiples of g = 2^shift, the largest power of two dividing every
+// size (an offset is a sum of sizes).  When sum(size)/g < 2^32 every offset and
+// block end fits 32 bits and a placed block packs into one 64-bit word
+// (off << 32 | end), so sorting words sorts by offset.
+//
+// One workgroup of PW waves per ordering.  Placed blocks are kept sorted by
+// offset in two families of lists:
+//
+//   ALL    every placed block, with its lifetime: `main` (global, sorted),
+//          `recent` (LDS, sorted) and `pending` (LDS, unsorted, the newest).
+//          Queried by variables that live for more than one step: the sorted
+//          lists are swept alternately, 64 entries per wave step -- blocks that
+//          do not overlap the variable in time are masked, a wave prefix-max of
+//          the remaining ends gives the highest occupied address so far, and
+//          the first entry whose offset leaves a hole of at least `size` above
+//          it ends the sweep ("the first hole that the variable can fit in").
+//   L[t]   (only when the sum of all lifetimes is at most CL*N steps) the
+//          blocks live at step t: a sorted prefix plus an unsorted tail.  A
+//          variable that lives for exactly one step t only meets blocks live
+//          at t, so its query is one sweep over L[t] held in registers.
+//          Multi-step blocks are appended to the tails of every step they
+//          cover and merged into the prefix by the next query of that step.
+//
+// One-step variables of different steps never interact, so between two
+// multi-step variables of the rank order the waves work in parallel: wave w
+// owns the steps t with t % PW == w.  Multi-step variables are handled by
+// wave 0 between workgroup barriers.  The result is identical to placing the
+// variables one by one in rank order.
+#include "lap_dev.h"
+#include "lap_kernels.h"
+
+namespace lap {
+
+constexpr int PW = 4;               // waves per ordering
+constexpr uint32_t PEND = 256;      // pending (unsorted) entries in LDS
+constexpr uint32_t REC = 512;       // recent (sorted) entries in LDS
+constexpr int LCH = 20;             // chunks of a per-step list held in registers
+constexpr uint32_t LREG = LCH * WAVE;
+constexpr uint32_t CL = PLAN_CL;    // per-step lists need sum of lifetimes <= CL * N
+constexpr int UNROLL = 4;           // chunks loaded ahead by a sweep
+
+// orders this wave's earlier LDS / global accesses before its later ones (no barrier)
+__device__ __forceinline__ void wave_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
+
+__device__ __forceinline__ uint64_t pk(uint32_t off, uint32_t end) { return ((uint64_t)off << 32) | end; }
+
+__device__ __forceinline__ uint32_t wave_scan_max32(uint32_t v)
+{
+    const int l = lane_id();
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        const uint32_t t = __shfl_up(v, d, WAVE);
+        if (l >= d) v = max(v, t);
+    }
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// preparation: granule shift, lifetime statistics, per-step list layout
+// ---------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void k_plan_prep1(uint32_t n, const uint64_t *__restrict__ size,
+                                                    const uint32_t *__restrict__ alloc,
+                                                    const uint32_t *__restrict__ free_, uint32_t *cntd,
+                                                    PlanHeader *hdr)
+{
+    const uint32_t stride = gridDim.x * blockDim.x;
+    unsigned long long orv = 0, sum = 0;
+    uint32_t multi = 0;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint64_t s = size[i];
+        const uint32_t a = alloc[i], f = free_[i];
+        orv |= s;
+        sum += s;
+        multi += (f - a > 1) ? 1u : 0u;
+        atomicAdd(&cntd[a], 1u);
+        atomicAdd(&cntd[f], 0xFFFFFFFFu);          // -1 modulo 2^32
+    }
+    for (int m = WAVE / 2; m > 0; m >>= 1) orv |= shfl_xor64(orv, m);
+    sum = wave_reduce_add(sum);
+    multi = wave_reduce_add32(multi);
+    if ((threadIdx.x & (WAVE - 1)) == 0) {
+        atomicOr((unsigned long long *)&hdr->or_sizes, orv);
+        atomicAdd((unsigned long long *)&hdr->sum_sizes, sum);
+        atomicAdd(&hdr->n_multi, multi);
+    }
+}
+
+constexpr int PREP_THREADS = 1024;
+
+__device__ __forceinline__ uint64_t prep_block_scan(uint64_t v, uint64_t *wtmp, uint64_t &total)
+{
+    const int tid = threadIdx.x, l = tid & (WAVE - 1), w = tid / WAVE;
+    const uint64_t incl = wave_scan_add(v);
+    if (l == WAVE - 1) wtmp[w] = incl;
+    __syncthreads();
+    uint64_t pre = 0, tot = 0;
+    for (int k = 0; k < PREP_THREADS / WAVE; ++k) {
+        const uint64_t x = wtmp[k];
+        if (k < w) pre += x;
+        tot += x;
+    }
+    __syncthreads();
+    total = tot;
+    return pre + incl;
+}
+
+// live[t] = number of variables live at step t; lstart = exclusive prefix sum of live
+__global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_t T,
+                                                             const uint32_t *__restrict__ cntd,
+                                                             uint32_t *__restrict__ lstart, PlanHeader *hdr)
+{
+    __shared__ uint64_t wtmp[PREP_THREADS / WAVE];
+    const uint32_t tid = threadIdx.x;
+    uint64_t c1 = 0, c2 = 0, tot;
+    for (uint32_t base = 0; base < T; base += PREP_THREADS) {
+        const uint32_t t = base + tid;
+        const bool in = t < T;
+        const uint64_t d = in ? (uint64_t)(int64_t)(int32_t)cntd[t] : 0;     // signed delta
+        const uint64_t live = c1 + prep_block_scan(d, wtmp, tot); c1 += tot;
+        const uint64_t lv = in ? live : 0;
+        const uint64_t incl = c2 + prep_block_scan(lv, wtmp, tot);
+        if (in) lstart[t] = (uint32_t)(incl - lv);
+        c2 += tot;
+    }
+    if (tid == 0) {
+        lstart[T] = (uint32_t)c2;
+        const uint64_t orv = hdr->or_sizes, sum = hdr->sum_sizes;
+        const uint32_t shift = orv ? (uint32_t)__ffsll((unsigned long long)orv) - 1 : 0;
+        const bool fast = (sum >> shift) < (1ull << 32);
+        const bool lists = fast && c2 <= (uint64_t)CL * n;
+        hdr->shift = shift;
+        hdr->fast = fast ? 1u : 0u;
+        hdr->mode1 = lists ? 1u : 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// sorted lists of packed blocks (global memory or LDS), one wave
+// ---------------------------------------------------------------------------
+
+// Lowest offset >= P at which `s` granules are free with respect to the entries of one
+// sorted list that overlap [a, f) in time (all entries when LIFE is false).  `cursor`:
+// where to start and where the sweep stopped; time-overlapping entries before it end at
+// or below the returned offset, so a later call with a larger P may resume there.
+template <bool LIFE>
+__device__ __forceinline__ uint32_t sweep32(const uint64_t *oe, const uint64_t *life, uint32_t n, uint32_t &cursor,
+                                            uint32_t P, uint32_t s, uint32_t a, uint32_t f)
+{
+    const int l = lane_id();
+    uint32_t i = cursor;
+    for (;;) {
+        uint64_t x[UNROLL], lf[UNROLL];
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const uint32_t idx = i + k * WAVE + l;
+            x[k] = 0; lf[k] = 0;
+            if (idx < n) {
+                x[k] = oe[idx];
+                if (LIFE) lf[k] = life[idx];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const uint32_t idx = i + k * WAVE + l;
+            const bool valid = idx < n;
+            const uint32_t o = (uint32_t)(x[k] >> 32);
+            uint32_t e = (uint32_t)x[k];
+            if (LIFE) {
+                const uint32_t ea = (uint32_t)(lf[k] >> 32), ef = (uint32_t)lf[k];
+                if (!(ea < f && a < ef)) e = 0;
+            }
+            if (!valid) e = 0;
+            const uint32_t incl = wave_scan_max32(e);
+            uint32_t excl = __shfl_up(incl, 1, WAVE);
+            if (l == 0) excl = 0;
+            const uint32_t before = max(P, excl);
+            const uint64_t hole = ballot(!valid || (o >= before && o - before >= s));
+            if (hole) {
+                const int first = __ffsll((unsigned long long)hole) - 1;
+                cursor = i + k * WAVE + first;
+                return __shfl(before, first, WAVE);
+            }
+            P = max(P, (uint32_t)__shfl(incl, WAVE - 1, WAVE));
+        }
+        i += UNROLL * WAVE;
+    }
+}
+
+// number of the first n entries that are < key
+__device__ __forceinline__ uint32_t count_below32(const uint64_t *oe, uint32_t n, uint64_t key)
+{
+    const int l = lane_id();
+    uint32_t p = 0;
+    for (uint32_t base = 0; base < n; base += WAVE) {
+        const uint32_t idx = base + l;
+        const uint64_t m = ballot(idx < n && oe[idx] < key);
+        p += (uint32_t)__popcll(m);
+        if (m != ~0ull) break;
+    }
+    return p;
+}
+
+// insert (x, lf) at position p of a sorted list of n entries; `life` may be null
+__device__ __forceinline__ void insert_at32(uint64_t *oe, uint64_t *life, uint32_t n, uint32_t p, uint64_t x,
+                                            uint64_t lf)
+{
+    const int l = lane_id();
+    uint32_t hi = n;
+    while (hi > p) {
+        const uint32_t lo = (hi - p > (uint32_t)WAVE) ? hi - WAVE : p;
+        const uint32_t idx = lo + l;
+        const bool act = idx < hi;
+        uint64_t y = 0, z = 0;
+        if (act) { y = oe[idx]; if (life) z = life[idx]; }
+        wave_fence();
+        if (act) { oe[idx + 1] = y; if (life) life[idx + 1] = z; }
+        wave_fence();
+        hi = lo;
+    }
+    if (l == 0) { oe[p] = x; if (life) life[p] = lf; }
+    wave_fence();
+}
+
+// Merge a sorted source list (ns entries, ns <= 64*PER) into a sorted destination list
+// (nd entries, capacity >= nd + ns), in place.  Equal keys: destination entries first.
+template <int PER>
+__device__ __forceinline__ void merge_into(uint64_t *d_oe, uint64_t *d_life, uint32_t nd, const uint64_t *s_oe,
+                                           const uint64_t *s_life, uint32_t ns)
+{
+    const int l = lane_id();
+    uint32_t pos[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const uint32_t j = k * WAVE + l;
+        pos[k] = 0;
+        if (j < ns) {
+            const uint64_t key = s_oe[j];
+            uint32_t lo = 0, hi = nd;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (d_oe[mid] <= key) lo = mid + 1; else hi = mid;
+            }
+            pos[k] = lo + j;
+        }
+    }
+    wave_fence();
+    uint32_t hi = nd;
+    while (hi > 0) {
+        const uint32_t lo = hi > (uint32_t)WAVE ? hi - WAVE : 0;
+        const uint32_t idx = lo + l;
+        const bool act = idx < hi;
+        uint64_t y = 0, z = 0;
+        uint32_t sh = 0;
+        if (act) {
+            y = d_oe[idx]; z = d_life[idx];
+            uint32_t a = 0, b = ns;
+            while (a < b) {
+                const uint32_t mid = (a + b) >> 1;
+                if (s_oe[mid] < y) a = mid + 1; else b = mid;
+            }
+            sh = a;
+        }
+        wave_fence();
+        if (act && sh) { d_oe[idx + sh] = y; d_life[idx + sh] = z; }
+        wave_fence();
+        if (ballot(act && sh) == 0) break;        // sorted: nothing below moves either
+        hi = lo;
+    }
+    wave_fence();
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const uint32_t j = k * WAVE + l;
+        if (j < ns) { d_oe[pos[k]] = s_oe[j]; d_life[pos[k]] = s_life[j]; }
+    }
+    wave_fence();
+}
+
+// bitonic sort of m (power of two, >= 64) packed entries with their lifetimes, in LDS, one wave
+__device__ __forceinline__ void bitonic_sort(uint64_t *oe, uint64_t *life, uint32_t m)
+{
+    const int l = lane_id();
+    for (uint32_t k = 2; k <= m; k <<= 1) {
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            for (uint32_t i = l; i < m / 2; i += WAVE) {
+                const uint32_t lo = ((i / j) * (j << 1)) + (i % j);
+                const uint32_t hi = lo + j;
+                const bool up = (lo & k) == 0;
+                const uint64_t x = oe[lo], y = oe[hi];
+                if ((x > y) == up) {
+                    oe[lo] = y; oe[hi] = x;
+                    const uint64_t u = life[lo], v = life[hi];
+                    life[lo] = v; life[hi] = u;
+                }
+            }
+            wave_fence();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// a per-step list held in registers: entry c*64+lane lives in e[c]
+// ---------------------------------------------------------------------------
+
+__device__ __forceinline__ uint32_t reg_count_below(const uint64_t (&e)[LCH], uint32_t cnt, uint64_t key)
+{
+    const int l = lane_id();
+    uint32_t p = 0;
+#pragma unroll
+    for (int c = 0; c < LCH; ++c) {
+        if ((uint32_t)c * WAVE < cnt) {
+            const uint32_t idx = c * WAVE + l;
+            p += (uint32_t)__popcll(ballot(idx < cnt && e[c] < key));
+        }
+    }
+    return p;
+}
+
+// entries [p, cnt) move up by one, x goes to position p  (cnt < LREG)
+__device__ __forceinline__ void reg_insert(uint64_t (&e)[LCH], uint32_t cnt, uint32_t p, uint64_t x)
+{
+    const int l = lane_id();
+#pragma unroll
+    for (int c = LCH - 1; c >= 0; --c) {
+        if ((uint32_t)c * WAVE <= cnt && (uint32_t)c * WAVE + WAVE > p) {
+            const uint32_t idx = c * WAVE + l;
+            uint64_t prev = shfl_up64(e[c], 1);
+            if (c > 0) {
+                const uint64_t carry = shfl64(e[c - 1], WAVE - 1);
+                if (l == 0) prev = carry;
+            }
+            if (idx > p && idx <= cnt) e[c] = prev;
+            else if (idx == p) e[c] = x;
+        }
+    }
+}
+
+__device__ __forceinline__ uint64_t reg_extract(const uint64_t (&e)[LCH], uint32_t j)
+{
+    uint64_t x = 0;
+#pragma unroll
+    for (int c = 0; c < LCH; ++c)
+        if ((uint32_t)c == (j >> 6)) x = shfl64(e[c], (int)(j & 63));
+    return x;
+}
+
+// first-fit over the cnt sorted entries (all of them are neighbours); pos = where the block goes
+__device__ __forceinline__ uint32_t reg_sweep(const uint64_t (&e)[LCH], uint32_t cnt, uint32_t s, uint32_t &pos)
+{
+    const int l = lane_id();
+    uint32_t P = 0;
+#pragma unroll
+    for (int c = 0; c < LCH; ++c) {
+        if ((uint32_t)c * WAVE <= cnt) {
+            const uint32_t idx = c * WAVE + l;
+            const bool valid = idx < cnt;
+            const uint32_t o = (uint32_t)(e[c] >> 32);
+            const uint32_t en = valid ? (uint32_t)e[c] : 0;
+            const uint32_t incl = wave_scan_max32(en);
+            uint32_t excl = __shfl_up(incl, 1, WAVE);
+            if (l == 0) excl = 0;
+            const uint32_t before = max(P, excl);
+            const uint64_t hole = ballot(!valid || (o >= before && o - before >= s));
+            if (hole) {
+                const int first = __ffsll((unsigned long long)hole) - 1;
+                pos = c * WAVE + first;
+                return __shfl(before, first, WAVE);
+            }
+            P = max(P, (uint32_t)__shfl(incl, WAVE - 1, WAVE));
+        }
+    }
+    pos = cnt;
+    return P;
+}
+
+// ---------------------------------------------------------------------------
+// the placement kernel
+// ---------------------------------------------------------------------------
+
+struct FastArgs {
+    uint32_t n, T;
+    const uint64_t *size;
+    const uint32_t *alloc, *free_;
+    const uint32_t *perm;        // [B][n]
+    const PlanHeader *hdr;
+    const uint32_t *lstart;      // [T+1]
+    uint64_t *m_oe, *m_life;     // [B][n]      ALL main list
+    uint64_t *L;                 // [B][capL]   per-step lists, packed blocks
+    uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts
+    uint64_t capL;
+    uint64_t *offs;              // [B][n]
+    uint64_t *fps;               // [B]
+};
+
+struct AllState {                // owned by wave 0
+    uint32_t nm, nr;
+};
+
+__device__ __forceinline__ void flush_pending(uint64_t *p_oe, uint64_t *p_life, uint32_t np, uint64_t *r_oe,
+                                              uint64_t *r_life, uint64_t *m_oe, uint64_t *m_life, AllState &st)
+{
+    const int l = lane_id();
+    if (np == 0) return;
+    uint32_t m = WAVE;
+    while (m < np) m <<= 1;
+    for (uint32_t i = np + l; i < m; i += WAVE) { p_oe[i] = U64_MAX; p_life[i] = 0; }
+    wave_fence();
+    bitonic_sort(p_oe, p_life, m);
+    if (st.nr + np > REC) {
+        merge_into<REC / WAVE>(m_oe, m_life, st.nm, r_oe, r_life, st.nr);
+        st.nm += st.nr;
+        st.nr = 0;
+    }
+    merge_into<PEND / WAVE>(r_oe, r_life, st.nr, p_oe, p_life, np);
+    st.nr += np;
+}
+
+__global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
+{
+    __shared__ uint64_t p_oe[PEND], p_life[PEND];
+    __shared__ uint64_t r_oe[REC], r_life[REC];
+    __shared__ uint32_t s_np;
+    __shared__ uint32_t s_fp[PW];
+
+    if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
+    const bool mode1 = A.hdr->mode1 != 0;
+    const uint32_t sh = A.hdr->shift;
+    const uint32_t b = blockIdx.x;
+    const int l = lane_id();
+    const uint32_t wave = threadIdx.x / WAVE;
+    if (!mode1 && wave != 0) return;        // without per-step lists every query is wave 0's
+
+    const uint32_t n = A.n, T = A.T;
+    const uint32_t *perm = A.perm + (size_t)b * n;
+    uint64_t *m_oe = A.m_oe + (size_t)b * n;
+    uint64_t *m_life = A.m_life + (size_t)b * n;
+    uint64_t *L = A.L + (size_t)b * A.capL;
+    uint32_t *l_ns = A.l_ns + (size_t)b * T;
+    uint32_t *l_nu = A.l_nu + (size_t)b * T;
+    uint64_t *offs = A.offs + (size_t)b * n;
+
+    // variables that will still query ALL: every one without per-step lists
+    uint32_t multi_left = mode1 ? A.hdr->n_multi : n;
+    AllState st{0, 0};
+    uint32_t fp = 0;
+    if (threadIdx.x == 0) s_np = 0;
+    __syncthreads();
+
+    for (uint32_t r0 = 0; r0 < n; r0 += WAVE) {
+        const uint32_t ridx = r0 + l;
+        const bool in = ridx < n;
+        uint32_t v = 0, a = 0, f = 1, s = 0;
+        if (in) {
+            v = perm[ridx];
+            a = A.alloc[v];
+            f = A.free_[v];
+            s = (uint32_t)(A.size[v] >> sh);
+        }
+        const uint64_t im = ballot(in);
+        const uint64_t mm = ballot(in && (!mode1 || f - a > 1));
+        const uint32_t wn = (uint32_t)__popcll(im);
+        uint32_t p = 0;
+        bool dirty = false;
+        while (p < wn) {
+            if ((mm >> p) & 1ull) {
+                // ---- a variable that queries ALL: wave 0, alone --------------------------
+                if (dirty) { __syncthreads(); dirty = false; }
+                if (wave == 0) {
+                    const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
+                    const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
+                    flush_pending(p_oe, p_life, s_np, r_oe, r_life, m_oe, m_life, st);
+                    uint32_t o = 0, cm = 0, cr = 0;
+                    for (;;) {
+                        const uint32_t o1 = sweep32<true>(m_oe, m_life, st.nm, cm, o, vs, va, vf);
+                        const uint32_t o2 = st.nr ? sweep32<true>(r_oe, r_life, st.nr, cr, o1, vs, va, vf) : o1;
+                        o = o2;
+                        if (o2 == o1) break;
+                    }
+                    const uint32_t e = o + vs;
+                    fp = max(fp, e);
+                    if (l == 0) {
+                        offs[vv] = (uint64_t)o << sh;
+                        uint32_t np = 0;
+                        if (multi_left > 1) {           // someone will still query ALL
+                            p_oe[0] = pk(o, e);
+                            p_life[0] = ((uint64_t)va << 32) | vf;
+                            np = 1;
+                        }
+                        s_np = np;
+                    }
+                    if (mode1) {
+                        const uint64_t x = pk(o, e);
+                        for (uint32_t t = va + l; t < vf; t += WAVE) {
+                            const uint32_t k = l_ns[t] + l_nu[t];
+                            L[A.lstart[t] + k] = x;
+                            l_nu[t] = l_nu[t] + 1;
+                        }
+                    }
+                }
+                --multi_left;
+                __syncthreads();
+                ++p;
+            } else {
+                // ---- a run of one-step variables: each wave takes the steps it owns --------
+                const uint64_t rest = (~mm & im) >> p;
+                const uint32_t run = (~rest == 0ull) ? 64u : (uint32_t)(__ffsll((unsigned long long)~rest) - 1);
+                const uint32_t q = p + run;
+                uint64_t mine = ballot((uint32_t)l >= p && (uint32_t)l < q && (a % PW) == wave);
+                while (mine) {
+                    const int j = __ffsll((unsigned long long)mine) - 1;
+                    mine &= mine - 1;
+                    const uint32_t vv = __shfl(v, j, WAVE), t = __shfl(a, j, WAVE), vs = __shfl(s, j, WAVE);
+                    const uint32_t base = A.lstart[t];
+                    uint64_t *Lt = L + base;
+                    const uint32_t ns = l_ns[t], nu = l_nu[t], tot = ns + nu;
+                    uint32_t o;
+                    if (tot + 1 <= LREG) {
+                        uint64_t e[LCH];
+#pragma unroll
+                        for (int c = 0; c < LCH; ++c) {
+                            const uint32_t idx = c * WAVE + l;
+                            e[c] = U64_MAX;
+                            if ((uint32_t)c * WAVE < tot && idx < tot) e[c] = Lt[idx];
+                        }
+                        uint32_t minp = tot;
+                        for (uint32_t jj = ns; jj < tot; ++jj) {      // merge the unsorted tail
+                            const uint64_t x = reg_extract(e, jj);
+                            const uint32_t pp = reg_count_below(e, jj, x);
+                            reg_insert(e, jj, pp, x);
+                            minp = min(minp, pp);
+                        }
+                        uint32_t pos;
+                        o = reg_sweep(e, tot, vs, pos);
+                        reg_insert(e, tot, pos, pk(o, o + vs));
+                        minp = min(minp, pos);
+#pragma unroll
+                        for (int c = 0; c < LCH; ++c) {
+                            const uint32_t idx = c * WAVE + l;
+                            if ((uint32_t)c * WAVE <= tot && idx >= minp && idx <= tot) Lt[idx] = e[c];
+                        }
+                    } else {
+                        // list too long for registers: same steps directly in global memory
+                        for (uint32_t jj = ns; jj < tot; ++jj) {
+                            const uint64_t x = Lt[jj];
+                            wave_fence();
+                            const uint32_t pp = count_below32(Lt, jj, x);
+                            insert_at32(Lt, nullptr, jj, pp, x, 0);
+                        }
+                        uint32_t pos = 0;
+                        o = sweep32<false>(Lt, nullptr, tot, pos, 0, vs, 0, 0);
+                        insert_at32(Lt, nullptr, tot, pos, pk(o, o + vs), 0);
+                    }
+                    fp = max(fp, o + vs);
+                    if (l == 0) {
+                        l_ns[t] = tot + 1;
+                        l_nu[t] = 0;
+                        offs[vv] = (uint64_t)o << sh;
+                        if (multi_left > 0) {
+                            const uint32_t slot = atomicAdd(&s_np, 1u);
+                            p_oe[slot] = pk(o, o + vs);
+                            p_life[slot] = ((uint64_t)t << 32) | (t + 1);
+                        }
+                    }
+                    wave_fence();
+                }
+                dirty = true;
+                p = q;
+            }
+        }
+        __syncthreads();
+        // keep room for the next window's placements (every wave reads the count before
+        // wave 0 may reset it)
+        const uint32_t np_now = s_np;
+        __syncthreads();
+        if (np_now + WAVE > PEND) {
+            if (wave == 0) {
+                flush_pending(p_oe, p_life, np_now, r_oe, r_life, m_oe, m_life, st);
+                if (l == 0) s_np = 0;
+            }
+            __syncthreads();
+        }
+    }
+    if (l == 0) s_fp[wave] = fp;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t m = s_fp[0];
+        if (mode1)
+            for (int w = 1; w < PW; ++w) m = max(m, s_fp[w]);
+        A.fps[b] = (uint64_t)m << sh;
+    }
+}
+
+hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                            const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st)
+{
+    uint32_t blocks = (n + 255) / 256;
+    blocks = blocks > 1024 ? 1024 : blocks;
+    hipLaunchKernelGGL(k_plan_prep1, dim3(blocks), dim3(256), 0, st, n, size, alloc, free_, cntd, hdr);
+    hipLaunchKernelGGL(k_plan_prep2, dim3(1), dim3(PREP_THREADS), 0, st, n, T, cntd, lstart, hdr);
+    return hipGetLastError();
+}
+
+hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
+                             const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr,
+                             const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *L, uint64_t capL,
+                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st)
+{
+    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, m_oe, m_life, L, l_ns, l_nu, capL, offs, fps};
+    hipLaunchKernelGGL(k_place_fast, dim3(B), dim3(PW * WAVE), 0, st, A);
+    return hipGetLastError();
+}
+
+}  // namespace lap

@@ -1,4 +1,6 @@
-// First-fit placement of every variable under many orderings (Section III-C).
+// First-fit placement of every variable under many orderings (Section III-C):
+// the 64-bit path, used when byte offsets do not fit 32-bit granules (see
+// place_fast.hip for the common case).
 //
 // One wave (one 64-thread workgroup) per ordering.  Variables are taken in
 // the ordering's rank order; each gets the lowest offset at which its block
@@ -148,14 +150,16 @@ __device__ __forceinline__ void merge_recent(uint64_t *m_off, uint64_t *m_end, u
     __syncthreads();
 }
 
-__global__ __launch_bounds__(64) void k_place(uint32_t n, const uint64_t *__restrict__ size,
+__global__ __launch_bounds__(64) void k_place_wide(uint32_t n, const uint64_t *__restrict__ size,
                                               const uint32_t *__restrict__ alloc,
                                               const uint32_t *__restrict__ free_,
                                               const uint32_t *__restrict__ perm_all,
+                                              const PlanHeader *__restrict__ hdr,
                                               uint64_t *m_off_all, uint64_t *m_end_all, uint64_t *m_life_all,
                                               uint64_t *__restrict__ offs_all, uint64_t *__restrict__ fps)
 {
     __shared__ uint64_t r_off[RECENT], r_end[RECENT], r_life[RECENT];
+    if (hdr->fast) return;                 // the 32-bit granule kernel handles this trace
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
     const uint32_t *perm = perm_all + (size_t)b * n;
@@ -231,12 +235,12 @@ __global__ __launch_bounds__(256) void k_copy_best(uint32_t n, const uint64_t *_
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) best_offsets[i] = src[i];
 }
 
-hipError_t launch_place(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
-                        const uint32_t *perm, uint64_t *m_off, uint64_t *m_end, uint64_t *m_life, uint64_t *offs,
-                        uint64_t *fps, hipStream_t st)
+hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                        const uint32_t *perm, const PlanHeader *hdr, uint64_t *m_off, uint64_t *m_end,
+                        uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_place, dim3(B), dim3(WAVE), 0, st, n, size, alloc, free_, perm, m_off, m_end, m_life, offs,
-                       fps);
+    hipLaunchKernelGGL(k_place_wide, dim3(B), dim3(WAVE), 0, st, n, size, alloc, free_, perm, hdr, m_off, m_end,
+                       m_life, offs, fps);
     return hipGetLastError();
 }
 

@@ -88,6 +88,32 @@ def test_plan_pool_random(lap, oracle_mod, seed, n, T):
     _check_plan(lap, oracle_mod, tr, kinds, seeds)
 
 
+@pytest.mark.parametrize("seed,n,T,frac,max_life", [
+    (0, 3000, 40, 0.97, 40),      # per-step lists, tails of a few entries
+    (1, 5000, 64, 0.90, 8),       # many short multi-step variables
+    (2, 4000, 2, 0.80, 2),        # ~2000 blocks per step: lists too long for registers
+    (3, 2000, 7, 1.00, 1),        # one-step variables only
+    (4, 6000, 300, 0.99, 300),    # few long-lived among many temporaries (transformer-like)
+    (5, 1400, 1, 1.00, 1),        # a single step: one list of 1400 entries crosses the register limit
+])
+def test_plan_pool_per_step_lists(lap, oracle_mod, seed, n, T, frac, max_life):
+    """Traces whose lifetimes sum to at most 6N steps take the per-step-list path."""
+    tr = random_trace(1000 + seed, n, T, size_choices=[1, 1, 2, 3, 5, 8, 13, 64], one_step_frac=frac,
+                      max_life=max_life)
+    assert int((tr.free - tr.alloc).sum()) <= 6 * n
+    kinds, seeds = make_orderings(20)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds)
+
+
+def test_plan_pool_64bit_offsets(lap, oracle_mod):
+    """Sizes whose sum does not fit 2^32 granules take the 64-bit path."""
+    tr = random_trace(31, 900, 25, granule=1)
+    tr.size = tr.size * np.uint64(1 << 20) + np.uint64(1)        # odd sizes: granule 1 byte, sum ~ 2^42
+    assert int(tr.size.sum()) >= 1 << 32
+    kinds, seeds = make_orderings(12)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds)
+
+
 def test_plan_pool_wide_sizes(lap, oracle_mod):
     tr = random_trace(99, 1200, 50, granule=1)          # byte-granular sizes 2^9 .. 2^23
     kinds, seeds = make_orderings(16)
