@@ -35,9 +35,9 @@
 namespace lap {
 
 constexpr int PW = 4;               // waves per ordering
-constexpr uint32_t PEND = 256;      // pending (unsorted) entries in LDS
-constexpr uint32_t REC = 512;       // recent (sorted) entries in LDS
-constexpr int LCH = 20;             // chunks of a per-step list held in registers
+constexpr uint32_t PEND = 512;      // pending (unsorted) entries in LDS
+constexpr uint32_t REC = 1536;      // recent (sorted) entries in LDS
+constexpr int LCH = 18;             // chunks of a per-step list held in registers
 constexpr uint32_t LREG = LCH * WAVE;
 constexpr uint32_t CL = PLAN_CL;    // per-step lists need sum of lifetimes <= CL * N
 constexpr int UNROLL = 4;           // chunks loaded ahead by a sweep
@@ -47,16 +47,7 @@ __device__ __forceinline__ void wave_fence() { __builtin_amdgcn_fence(__ATOMIC_S
 
 __device__ __forceinline__ uint64_t pk(uint32_t off, uint32_t end) { return ((uint64_t)off << 32) | end; }
 
-__device__ __forceinline__ uint32_t wave_scan_max32(uint32_t v)
-{
-    const int l = lane_id();
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        const uint32_t t = __shfl_up(v, d, WAVE);
-        if (l >= d) v = max(v, t);
-    }
-    return v;
-}
+__device__ __forceinline__ uint32_t wave_scan_max32(uint32_t v) { return wave_scan_max_u32(v); }
 
 // ---------------------------------------------------------------------------
 // preparation: granule shift, lifetime statistics, per-step list layout
@@ -175,16 +166,15 @@ __device__ __forceinline__ uint32_t sweep32(const uint64_t *oe, const uint64_t *
             }
             if (!valid) e = 0;
             const uint32_t incl = wave_scan_max32(e);
-            uint32_t excl = __shfl_up(incl, 1, WAVE);
-            if (l == 0) excl = 0;
+            const uint32_t excl = lane_shift_up(incl, 0u);
             const uint32_t before = max(P, excl);
             const uint64_t hole = ballot(!valid || (o >= before && o - before >= s));
             if (hole) {
                 const int first = __ffsll((unsigned long long)hole) - 1;
                 cursor = i + k * WAVE + first;
-                return __shfl(before, first, WAVE);
+                return read_lane(before, first);
             }
-            P = max(P, (uint32_t)__shfl(incl, WAVE - 1, WAVE));
+            P = max(P, read_lane(incl, WAVE - 1));
         }
         i += UNROLL * WAVE;
     }
@@ -225,29 +215,26 @@ __device__ __forceinline__ void insert_at32(uint64_t *oe, uint64_t *life, uint32
     wave_fence();
 }
 
-// Merge a sorted source list (ns entries, ns <= 64*PER) into a sorted destination list
-// (nd entries, capacity >= nd + ns), in place.  Equal keys: destination entries first.
-template <int PER>
+// Merge a sorted source list (ns entries) into a sorted destination list (nd entries,
+// capacity >= nd + ns), in place.  Equal keys: destination entries first.  `pos` is LDS
+// scratch for ns final positions.
 __device__ __forceinline__ void merge_into(uint64_t *d_oe, uint64_t *d_life, uint32_t nd, const uint64_t *s_oe,
-                                           const uint64_t *s_life, uint32_t ns)
+                                           const uint64_t *s_life, uint32_t ns, uint32_t *pos)
 {
     const int l = lane_id();
-    uint32_t pos[PER];
-#pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        const uint32_t j = k * WAVE + l;
-        pos[k] = 0;
-        if (j < ns) {
-            const uint64_t key = s_oe[j];
-            uint32_t lo = 0, hi = nd;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi) >> 1;
-                if (d_oe[mid] <= key) lo = mid + 1; else hi = mid;
-            }
-            pos[k] = lo + j;
+    // final position of source entry j: j + number of destination entries with key <= its key
+    for (uint32_t j = l; j < ns; j += WAVE) {
+        const uint64_t key = s_oe[j];
+        uint32_t lo = 0, hi = nd;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (d_oe[mid] <= key) lo = mid + 1; else hi = mid;
         }
+        pos[j] = lo + j;
     }
     wave_fence();
+    // destination entries move up by the number of source entries strictly below them, top
+    // chunk first
     uint32_t hi = nd;
     while (hi > 0) {
         const uint32_t lo = hi > (uint32_t)WAVE ? hi - WAVE : 0;
@@ -264,17 +251,16 @@ __device__ __forceinline__ void merge_into(uint64_t *d_oe, uint64_t *d_life, uin
             }
             sh = a;
         }
-        wave_fence();
+        // stores of this chunk land at or above its own lowest index; the chunks still to be
+        // read lie strictly below, so no fence is needed between iterations
         if (act && sh) { d_oe[idx + sh] = y; d_life[idx + sh] = z; }
-        wave_fence();
         if (ballot(act && sh) == 0) break;        // sorted: nothing below moves either
         hi = lo;
     }
     wave_fence();
-#pragma unroll
-    for (int k = 0; k < PER; ++k) {
-        const uint32_t j = k * WAVE + l;
-        if (j < ns) { d_oe[pos[k]] = s_oe[j]; d_life[pos[k]] = s_life[j]; }
+    for (uint32_t j = l; j < ns; j += WAVE) {
+        const uint32_t q = pos[j];
+        d_oe[q] = s_oe[j]; d_life[q] = s_life[j];
     }
     wave_fence();
 }
@@ -327,11 +313,8 @@ __device__ __forceinline__ void reg_insert(uint64_t (&e)[LCH], uint32_t cnt, uin
     for (int c = LCH - 1; c >= 0; --c) {
         if ((uint32_t)c * WAVE <= cnt && (uint32_t)c * WAVE + WAVE > p) {
             const uint32_t idx = c * WAVE + l;
-            uint64_t prev = shfl_up64(e[c], 1);
-            if (c > 0) {
-                const uint64_t carry = shfl64(e[c - 1], WAVE - 1);
-                if (l == 0) prev = carry;
-            }
+            const uint64_t carry = c > 0 ? read_lane64(e[c > 0 ? c - 1 : 0], WAVE - 1) : 0;
+            const uint64_t prev = lane_shift_up64(e[c], carry);
             if (idx > p && idx <= cnt) e[c] = prev;
             else if (idx == p) e[c] = x;
         }
@@ -343,37 +326,33 @@ __device__ __forceinline__ uint64_t reg_extract(const uint64_t (&e)[LCH], uint32
     uint64_t x = 0;
 #pragma unroll
     for (int c = 0; c < LCH; ++c)
-        if ((uint32_t)c == (j >> 6)) x = shfl64(e[c], (int)(j & 63));
+        if ((uint32_t)c == (j >> 6)) x = read_lane64(e[c], (int)(j & 63));
     return x;
 }
 
-// first-fit over the cnt sorted entries (all of them are neighbours); pos = where the block goes
+// First-fit over the cnt sorted entries of a per-step list.  All of them are live at the
+// same step, hence pairwise disjoint in address: ends ascend with offsets and the highest
+// occupied address below entry i is simply the end of entry i-1.  pos = where the block goes.
 __device__ __forceinline__ uint32_t reg_sweep(const uint64_t (&e)[LCH], uint32_t cnt, uint32_t s, uint32_t &pos)
 {
     const int l = lane_id();
-    uint32_t P = 0;
 #pragma unroll
     for (int c = 0; c < LCH; ++c) {
         if ((uint32_t)c * WAVE <= cnt) {
             const uint32_t idx = c * WAVE + l;
-            const bool valid = idx < cnt;
+            const uint32_t carry = c > 0 ? read_lane((uint32_t)e[c > 0 ? c - 1 : 0], WAVE - 1) : 0u;
+            const uint32_t prev = lane_shift_up((uint32_t)e[c], carry);
             const uint32_t o = (uint32_t)(e[c] >> 32);
-            const uint32_t en = valid ? (uint32_t)e[c] : 0;
-            const uint32_t incl = wave_scan_max32(en);
-            uint32_t excl = __shfl_up(incl, 1, WAVE);
-            if (l == 0) excl = 0;
-            const uint32_t before = max(P, excl);
-            const uint64_t hole = ballot(!valid || (o >= before && o - before >= s));
+            const uint64_t hole = ballot(idx >= cnt || (o >= prev && o - prev >= s));
             if (hole) {
                 const int first = __ffsll((unsigned long long)hole) - 1;
                 pos = c * WAVE + first;
-                return __shfl(before, first, WAVE);
+                return read_lane(prev, first);
             }
-            P = max(P, (uint32_t)__shfl(incl, WAVE - 1, WAVE));
         }
     }
     pos = cnt;
-    return P;
+    return 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -400,7 +379,8 @@ struct AllState {                // owned by wave 0
 };
 
 __device__ __forceinline__ void flush_pending(uint64_t *p_oe, uint64_t *p_life, uint32_t np, uint64_t *r_oe,
-                                              uint64_t *r_life, uint64_t *m_oe, uint64_t *m_life, AllState &st)
+                                              uint64_t *r_life, uint64_t *m_oe, uint64_t *m_life, AllState &st,
+                                              uint32_t *s_pos)
 {
     const int l = lane_id();
     if (np == 0) return;
@@ -410,20 +390,92 @@ __device__ __forceinline__ void flush_pending(uint64_t *p_oe, uint64_t *p_life, 
     wave_fence();
     bitonic_sort(p_oe, p_life, m);
     if (st.nr + np > REC) {
-        merge_into<REC / WAVE>(m_oe, m_life, st.nm, r_oe, r_life, st.nr);
+        merge_into(m_oe, m_life, st.nm, r_oe, r_life, st.nr, s_pos);
         st.nm += st.nr;
         st.nr = 0;
     }
-    merge_into<PEND / WAVE>(r_oe, r_life, st.nr, p_oe, p_life, np);
+    merge_into(r_oe, r_life, st.nr, p_oe, p_life, np, s_pos);
     st.nr += np;
 }
 
-__global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
+constexpr int COOP_U = 4;                    // chunks per wave in one cooperative round
+constexpr int ROUND_CH = PW * COOP_U;        // chunks per round
+constexpr uint32_t NONE32 = 0xFFFFFFFFu;
+
+// sweep32 over a long global list with all PW waves: chunk q of a round belongs to wave
+// q % PW.  Every wave scans its chunks, the chunk maxima are exchanged through LDS, each
+// wave then tests its chunks for the first hole with the right carry, and the lowest hole
+// of the round wins.  Two workgroup barriers per round.  All waves pass the same arguments
+// and get the same result.
+__device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_t *life, uint32_t n,
+                                               uint32_t &cursor, uint32_t P, uint32_t s, uint32_t a, uint32_t f,
+                                               uint32_t wave, uint32_t *s_cmax, uint32_t *s_hq, uint32_t *s_hans)
+{
+    const int l = lane_id();
+    uint32_t i = cursor;
+    for (;;) {
+        uint64_t x[COOP_U], lf[COOP_U];
+#pragma unroll
+        for (int k = 0; k < COOP_U; ++k) {
+            const uint32_t idx = i + (k * PW + wave) * WAVE + l;
+            x[k] = 0; lf[k] = 0;
+            if (idx < n) { x[k] = oe[idx]; lf[k] = life[idx]; }
+        }
+        uint32_t incl[COOP_U];
+#pragma unroll
+        for (int k = 0; k < COOP_U; ++k) {
+            const uint32_t idx = i + (k * PW + wave) * WAVE + l;
+            uint32_t e = (uint32_t)x[k];
+            const uint32_t ea = (uint32_t)(lf[k] >> 32), ef = (uint32_t)lf[k];
+            if (idx >= n || !(ea < f && a < ef)) e = 0;
+            incl[k] = wave_scan_max32(e);
+            if (l == WAVE - 1) s_cmax[k * PW + wave] = incl[k];
+        }
+        __syncthreads();
+        const uint32_t cm = (l < ROUND_CH) ? s_cmax[l] : 0;
+        const uint32_t pin = wave_scan_max32(cm);
+        const uint32_t total = __shfl(pin, ROUND_CH - 1, WAVE);
+        uint32_t best_q = NONE32, best_ans = 0;
+#pragma unroll
+        for (int k = 0; k < COOP_U; ++k) {
+            const uint32_t q = k * PW + wave;
+            const uint32_t idx = i + q * WAVE + l;
+            const uint32_t carry = max(P, q ? (uint32_t)__shfl(pin, (int)q - 1, WAVE) : 0u);
+            const uint32_t excl = lane_shift_up(incl[k], 0u);
+            const uint32_t before = max(carry, excl);
+            const uint32_t o = (uint32_t)(x[k] >> 32);
+            const uint64_t hole = ballot(idx >= n || (o >= before && o - before >= s));
+            if (hole && best_q == NONE32) {
+                const int first = __ffsll((unsigned long long)hole) - 1;
+                best_q = q * WAVE + first;
+                best_ans = read_lane(before, first);
+            }
+        }
+        if (l == 0) { s_hq[wave] = best_q; s_hans[wave] = best_ans; }
+        __syncthreads();
+        uint32_t hq = NONE32, ha = 0;
+#pragma unroll
+        for (int w = 0; w < PW; ++w) {
+            const uint32_t q = s_hq[w];
+            if (q < hq) { hq = q; ha = s_hans[w]; }
+        }
+        if (hq != NONE32) {
+            cursor = i + hq;
+            return ha;
+        }
+        P = max(P, total);
+        i += ROUND_CH * WAVE;
+    }
+}
+
+__global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
     __shared__ uint64_t p_oe[PEND], p_life[PEND];
     __shared__ uint64_t r_oe[REC], r_life[REC];
-    __shared__ uint32_t s_np;
-    __shared__ uint32_t s_fp[PW];
+    __shared__ uint32_t s_np, s_nm, s_bc;
+    __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
+    __shared__ uint32_t s_cmax[ROUND_CH];
+    __shared__ uint32_t s_pos[REC];
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
     const bool mode1 = A.hdr->mode1 != 0;
@@ -431,7 +483,6 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
     const uint32_t wave = threadIdx.x / WAVE;
-    if (!mode1 && wave != 0) return;        // without per-step lists every query is wave 0's
 
     const uint32_t n = A.n, T = A.T;
     const uint32_t *perm = A.perm + (size_t)b * n;
@@ -442,12 +493,34 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
     uint32_t *l_nu = A.l_nu + (size_t)b * T;
     uint64_t *offs = A.offs + (size_t)b * n;
 
-    // variables that will still query ALL: every one without per-step lists
+    // variables that will still query ALL: every one when there are no per-step lists
     uint32_t multi_left = mode1 ? A.hdr->n_multi : n;
     AllState st{0, 0};
     uint32_t fp = 0;
     if (threadIdx.x == 0) s_np = 0;
     __syncthreads();
+
+    // this wave's register-resident per-step list: step, entries, count, first index not yet
+    // written back; wmask remembers (hashed) which lists were stored since the last fence
+    uint32_t cur_t = NONE32, cnt = 0, wb_from = NONE32;
+    uint64_t wmask = 0;
+    uint64_t e[LCH];
+#pragma unroll
+    for (int c = 0; c < LCH; ++c) e[c] = U64_MAX;
+
+    auto writeback = [&]() {
+        if (cur_t != NONE32 && wb_from != NONE32) {
+            uint64_t *Lt = L + A.lstart[cur_t];
+#pragma unroll
+            for (int c = 0; c < LCH; ++c) {
+                const uint32_t idx = c * WAVE + l;
+                if ((uint32_t)c * WAVE < cnt && idx >= wb_from && idx < cnt) Lt[idx] = e[c];
+            }
+            if (l == 0) { l_ns[cur_t] = cnt; l_nu[cur_t] = 0; }
+            wmask |= 1ull << ((cur_t / PW) & 63);
+        }
+        wb_from = NONE32;
+    };
 
     for (uint32_t r0 = 0; r0 < n; r0 += WAVE) {
         const uint32_t ridx = r0 + l;
@@ -463,41 +536,50 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
         const uint64_t mm = ballot(in && (!mode1 || f - a > 1));
         const uint32_t wn = (uint32_t)__popcll(im);
         uint32_t p = 0;
-        bool dirty = false;
         while (p < wn) {
             if ((mm >> p) & 1ull) {
-                // ---- a variable that queries ALL: wave 0, alone --------------------------
-                if (dirty) { __syncthreads(); dirty = false; }
+                // ---- a variable that queries ALL: every wave sweeps, wave 0 keeps the lists ----
+                if (cur_t != NONE32) { writeback(); cur_t = NONE32; }
+                __syncthreads();
+                const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
+                const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
                 if (wave == 0) {
-                    const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
-                    const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
-                    flush_pending(p_oe, p_life, s_np, r_oe, r_life, m_oe, m_life, st);
-                    uint32_t o = 0, cm = 0, cr = 0;
-                    for (;;) {
-                        const uint32_t o1 = sweep32<true>(m_oe, m_life, st.nm, cm, o, vs, va, vf);
+                    flush_pending(p_oe, p_life, s_np, r_oe, r_life, m_oe, m_life, st, s_pos);
+                    if (l == 0) { s_nm = st.nm; s_np = 0; }
+                }
+                __syncthreads();
+                const uint32_t nm = s_nm;
+                uint32_t o = 0, cm = 0, cr = 0;
+                for (;;) {
+                    const uint32_t o1 = coop_sweep(m_oe, m_life, nm, cm, o, vs, va, vf, wave, s_cmax, s_hq, s_hans);
+                    if (wave == 0) {
                         const uint32_t o2 = st.nr ? sweep32<true>(r_oe, r_life, st.nr, cr, o1, vs, va, vf) : o1;
-                        o = o2;
-                        if (o2 == o1) break;
+                        if (l == 0) s_bc = o2;
                     }
-                    const uint32_t e = o + vs;
-                    fp = max(fp, e);
-                    if (l == 0) {
-                        offs[vv] = (uint64_t)o << sh;
-                        uint32_t np = 0;
-                        if (multi_left > 1) {           // someone will still query ALL
-                            p_oe[0] = pk(o, e);
-                            p_life[0] = ((uint64_t)va << 32) | vf;
-                            np = 1;
-                        }
-                        s_np = np;
+                    __syncthreads();
+                    o = s_bc;
+                    if (o == o1) break;
+                }
+                const uint32_t en = o + vs;
+                fp = max(fp, en);
+                if (threadIdx.x == 0) offs[vv] = (uint64_t)o << sh;
+                if (wave == 0 && multi_left > 1) {      // someone will still query ALL
+                    if (st.nr == REC) {
+                        merge_into(m_oe, m_life, st.nm, r_oe, r_life, st.nr, s_pos);
+                        st.nm += st.nr;
+                        st.nr = 0;
                     }
-                    if (mode1) {
-                        const uint64_t x = pk(o, e);
-                        for (uint32_t t = va + l; t < vf; t += WAVE) {
-                            const uint32_t k = l_ns[t] + l_nu[t];
-                            L[A.lstart[t] + k] = x;
-                            l_nu[t] = l_nu[t] + 1;
-                        }
+                    const uint64_t x = pk(o, en);
+                    const uint32_t ip = count_below32(r_oe, st.nr, x);
+                    insert_at32(r_oe, r_life, st.nr, ip, x, ((uint64_t)va << 32) | vf);
+                    ++st.nr;
+                }
+                if (mode1) {
+                    const uint64_t x = pk(o, en);
+                    for (uint32_t t = va + wave * WAVE + l; t < vf; t += PW * WAVE) {
+                        const uint32_t k = l_ns[t] + l_nu[t];
+                        L[A.lstart[t] + k] = x;
+                        l_nu[t] = l_nu[t] + 1;
                     }
                 }
                 --multi_left;
@@ -513,36 +595,43 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
                     const int j = __ffsll((unsigned long long)mine) - 1;
                     mine &= mine - 1;
                     const uint32_t vv = __shfl(v, j, WAVE), t = __shfl(a, j, WAVE), vs = __shfl(s, j, WAVE);
-                    const uint32_t base = A.lstart[t];
-                    uint64_t *Lt = L + base;
-                    const uint32_t ns = l_ns[t], nu = l_nu[t], tot = ns + nu;
                     uint32_t o;
-                    if (tot + 1 <= LREG) {
-                        uint64_t e[LCH];
+                    if (t != cur_t) {
+                        writeback();
+                        cur_t = NONE32;
+                        const uint32_t base = A.lstart[t];
+                        const uint32_t cap = A.lstart[t + 1] - base;
+                        if (wmask & (1ull << ((t / PW) & 63))) { wave_fence(); wmask = 0; }
+                        if (cap <= LREG) {
+                            // counts and (speculatively, up to the list's capacity) entries in one go
+                            const uint64_t *Lt = L + base;
+                            const uint32_t ns = l_ns[t], nu = l_nu[t];
 #pragma unroll
-                        for (int c = 0; c < LCH; ++c) {
-                            const uint32_t idx = c * WAVE + l;
-                            e[c] = U64_MAX;
-                            if ((uint32_t)c * WAVE < tot && idx < tot) e[c] = Lt[idx];
+                            for (int c = 0; c < LCH; ++c) {
+                                const uint32_t idx = c * WAVE + l;
+                                if ((uint32_t)c * WAVE < cap && idx < cap) e[c] = Lt[idx];
+                            }
+                            const uint32_t tot = ns + nu;
+                            for (uint32_t jj = ns; jj < tot; ++jj) {      // merge the unsorted tail
+                                const uint64_t x = reg_extract(e, jj);
+                                const uint32_t pp = reg_count_below(e, jj, x);
+                                reg_insert(e, jj, pp, x);
+                                wb_from = min(wb_from, pp);
+                            }
+                            cur_t = t;
+                            cnt = tot;
                         }
-                        uint32_t minp = tot;
-                        for (uint32_t jj = ns; jj < tot; ++jj) {      // merge the unsorted tail
-                            const uint64_t x = reg_extract(e, jj);
-                            const uint32_t pp = reg_count_below(e, jj, x);
-                            reg_insert(e, jj, pp, x);
-                            minp = min(minp, pp);
-                        }
+                    }
+                    if (cur_t == t) {
                         uint32_t pos;
-                        o = reg_sweep(e, tot, vs, pos);
-                        reg_insert(e, tot, pos, pk(o, o + vs));
-                        minp = min(minp, pos);
-#pragma unroll
-                        for (int c = 0; c < LCH; ++c) {
-                            const uint32_t idx = c * WAVE + l;
-                            if ((uint32_t)c * WAVE <= tot && idx >= minp && idx <= tot) Lt[idx] = e[c];
-                        }
+                        o = reg_sweep(e, cnt, vs, pos);
+                        reg_insert(e, cnt, pos, pk(o, o + vs));
+                        wb_from = min(wb_from, pos);
+                        ++cnt;
                     } else {
                         // list too long for registers: same steps directly in global memory
+                        uint64_t *Lt = L + A.lstart[t];
+                        const uint32_t ns = l_ns[t], nu = l_nu[t], tot = ns + nu;
                         for (uint32_t jj = ns; jj < tot; ++jj) {
                             const uint64_t x = Lt[jj];
                             wave_fence();
@@ -552,11 +641,11 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
                         uint32_t pos = 0;
                         o = sweep32<false>(Lt, nullptr, tot, pos, 0, vs, 0, 0);
                         insert_at32(Lt, nullptr, tot, pos, pk(o, o + vs), 0);
+                        if (l == 0) { l_ns[t] = tot + 1; l_nu[t] = 0; }
+                        wave_fence();
                     }
                     fp = max(fp, o + vs);
                     if (l == 0) {
-                        l_ns[t] = tot + 1;
-                        l_nu[t] = 0;
                         offs[vv] = (uint64_t)o << sh;
                         if (multi_left > 0) {
                             const uint32_t slot = atomicAdd(&s_np, 1u);
@@ -564,9 +653,7 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
                             p_life[slot] = ((uint64_t)t << 32) | (t + 1);
                         }
                     }
-                    wave_fence();
                 }
-                dirty = true;
                 p = q;
             }
         }
@@ -577,7 +664,7 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
         __syncthreads();
         if (np_now + WAVE > PEND) {
             if (wave == 0) {
-                flush_pending(p_oe, p_life, np_now, r_oe, r_life, m_oe, m_life, st);
+                flush_pending(p_oe, p_life, np_now, r_oe, r_life, m_oe, m_life, st, s_pos);
                 if (l == 0) s_np = 0;
             }
             __syncthreads();
@@ -587,8 +674,7 @@ __global__ __launch_bounds__(PW *WAVE) void k_place_fast(FastArgs A)
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t m = s_fp[0];
-        if (mode1)
-            for (int w = 1; w < PW; ++w) m = max(m, s_fp[w]);
+        for (int w = 1; w < PW; ++w) m = max(m, s_fp[w]);
         A.fps[b] = (uint64_t)m << sh;
     }
 }
