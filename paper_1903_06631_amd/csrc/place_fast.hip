@@ -215,56 +215,6 @@ __device__ __forceinline__ void insert_at32(uint64_t *oe, uint64_t *life, uint32
     wave_fence();
 }
 
-// Merge a sorted source list (ns entries) into a sorted destination list (nd entries,
-// capacity >= nd + ns), in place.  Equal keys: destination entries first.  `pos` is LDS
-// scratch for ns final positions.
-__device__ __forceinline__ void merge_into(uint64_t *d_oe, uint64_t *d_life, uint32_t nd, const uint64_t *s_oe,
-                                           const uint64_t *s_life, uint32_t ns, uint32_t *pos)
-{
-    const int l = lane_id();
-    // final position of source entry j: j + number of destination entries with key <= its key
-    for (uint32_t j = l; j < ns; j += WAVE) {
-        const uint64_t key = s_oe[j];
-        uint32_t lo = 0, hi = nd;
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (d_oe[mid] <= key) lo = mid + 1; else hi = mid;
-        }
-        pos[j] = lo + j;
-    }
-    wave_fence();
-    // destination entries move up by the number of source entries strictly below them, top
-    // chunk first
-    uint32_t hi = nd;
-    while (hi > 0) {
-        const uint32_t lo = hi > (uint32_t)WAVE ? hi - WAVE : 0;
-        const uint32_t idx = lo + l;
-        const bool act = idx < hi;
-        uint64_t y = 0, z = 0;
-        uint32_t sh = 0;
-        if (act) {
-            y = d_oe[idx]; z = d_life[idx];
-            uint32_t a = 0, b = ns;
-            while (a < b) {
-                const uint32_t mid = (a + b) >> 1;
-                if (s_oe[mid] < y) a = mid + 1; else b = mid;
-            }
-            sh = a;
-        }
-        // stores of this chunk land at or above its own lowest index; the chunks still to be
-        // read lie strictly below, so no fence is needed between iterations
-        if (act && sh) { d_oe[idx + sh] = y; d_life[idx + sh] = z; }
-        if (ballot(act && sh) == 0) break;        // sorted: nothing below moves either
-        hi = lo;
-    }
-    wave_fence();
-    for (uint32_t j = l; j < ns; j += WAVE) {
-        const uint32_t q = pos[j];
-        d_oe[q] = s_oe[j]; d_life[q] = s_life[j];
-    }
-    wave_fence();
-}
-
 // bitonic sort of m (power of two, >= 64) packed entries with their lifetimes, in LDS, one wave
 __device__ __forceinline__ void bitonic_sort(uint64_t *oe, uint64_t *life, uint32_t m)
 {
@@ -366,7 +316,7 @@ struct FastArgs {
     const uint32_t *perm;        // [B][n]
     const PlanHeader *hdr;
     const uint32_t *lstart;      // [T+1]
-    uint64_t *m_oe, *m_life;     // [B][n]      ALL main list
+    uint64_t *m_oe[2], *m_life[2];  // [B][n] x 2  ALL main list, two buffers (merges ping-pong)
     uint64_t *L;                 // [B][capL]   per-step lists, packed blocks
     uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts
     uint64_t capL;
@@ -374,52 +324,133 @@ struct FastArgs {
     uint64_t *fps;               // [B]
 };
 
-struct AllState {                // owned by wave 0
-    uint32_t nm, nr;
-};
-
-__device__ __forceinline__ void flush_pending(uint64_t *p_oe, uint64_t *p_life, uint32_t np, uint64_t *r_oe,
-                                              uint64_t *r_life, uint64_t *m_oe, uint64_t *m_life, AllState &st,
-                                              uint32_t *s_pos)
-{
-    const int l = lane_id();
-    if (np == 0) return;
-    uint32_t m = WAVE;
-    while (m < np) m <<= 1;
-    for (uint32_t i = np + l; i < m; i += WAVE) { p_oe[i] = U64_MAX; p_life[i] = 0; }
-    wave_fence();
-    bitonic_sort(p_oe, p_life, m);
-    if (st.nr + np > REC) {
-        merge_into(m_oe, m_life, st.nm, r_oe, r_life, st.nr, s_pos);
-        st.nm += st.nr;
-        st.nr = 0;
-    }
-    merge_into(r_oe, r_life, st.nr, p_oe, p_life, np, s_pos);
-    st.nr += np;
-}
-
 constexpr int COOP_U = 4;                    // chunks per wave in one cooperative round
 constexpr int ROUND_CH = PW * COOP_U;        // chunks per round
 constexpr uint32_t NONE32 = 0xFFFFFFFFu;
 
+// Merge the sorted recent list (LDS, nr entries) and the sorted main list (global, nm
+// entries) into another global buffer, with all PW waves; chunk c of main belongs to wave
+// c % PW and chunks are independent.  A chunk moves its own entries up by the number of
+// recent entries below each, and writes the recent entries whose place is inside it (after
+// main entries of equal key).  No barrier inside; the caller synchronises before reading dst.
+__device__ __forceinline__ void coop_merge_main(const uint64_t *src_oe, const uint64_t *src_life, uint32_t nm,
+                                                const uint64_t *r_oe, const uint64_t *r_life, uint32_t nr,
+                                                uint64_t *dst_oe, uint64_t *dst_life, uint32_t wave)
+{
+    const int l = lane_id();
+    const uint32_t nch = nm ? (nm + WAVE - 1) / WAVE : 1;
+    uint32_t jp = 0;
+    for (uint32_t c0 = wave; c0 < nch; c0 += 2 * PW) {
+        uint64_t key[2], lf[2], prevlast[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t c = c0 + u * PW;
+            const uint32_t idx = c * WAVE + l;
+            key[u] = U64_MAX; lf[u] = 0; prevlast[u] = 0;
+            if (c < nch) {
+                if (idx < nm) { key[u] = src_oe[idx]; lf[u] = src_life[idx]; }
+                if (c) prevlast[u] = src_oe[c * WAVE - 1];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t c = c0 + u * PW;
+            if (c < nch) {
+                const uint32_t idx = c * WAVE + l;
+                const bool valid = idx < nm;
+                const bool last = c == nch - 1;
+                const uint64_t lastkey = read_lane64(key[u], WAVE - 1);
+                while (jp < nr && r_oe[jp] < prevlast[u]) ++jp;
+                uint32_t sh = jp, j = jp;
+                while (j < nr) {
+                    const uint64_t rk = r_oe[j];
+                    if (!last && !(rk < lastkey)) break;
+                    const uint32_t below = (uint32_t)__popcll(ballot(valid && key[u] <= rk));
+                    if (l == 0) {
+                        dst_oe[c * WAVE + below + j] = rk;
+                        dst_life[c * WAVE + below + j] = r_life[j];
+                    }
+                    sh += (valid && rk < key[u]) ? 1u : 0u;
+                    ++j;
+                }
+                if (valid) { dst_oe[idx + sh] = key[u]; dst_life[idx + sh] = lf[u]; }
+            }
+        }
+    }
+}
+
+// Merge a sorted source list (ns entries) into a sorted destination list (nd entries,
+// capacity >= nd + ns), both in LDS, in place, one wave.  Equal keys: destination first.
+__device__ __forceinline__ void merge_lds(uint64_t *d_oe, uint64_t *d_life, uint32_t nd, const uint64_t *s_oe,
+                                          const uint64_t *s_life, uint32_t ns, uint32_t *pos)
+{
+    const int l = lane_id();
+    for (uint32_t j = l; j < ns; j += WAVE) {
+        const uint64_t key = s_oe[j];
+        uint32_t lo = 0, hi = nd;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (d_oe[mid] <= key) lo = mid + 1; else hi = mid;
+        }
+        pos[j] = lo + j;
+    }
+    wave_fence();
+    uint32_t hi = nd;
+    while (hi > 0) {
+        const uint32_t lo = hi > (uint32_t)WAVE ? hi - WAVE : 0;
+        const uint32_t idx = lo + l;
+        const bool act = idx < hi;
+        uint64_t y = 0, z = 0;
+        uint32_t sh = 0;
+        if (act) {
+            y = d_oe[idx]; z = d_life[idx];
+            uint32_t a = 0, b = ns;
+            while (a < b) {
+                const uint32_t mid = (a + b) >> 1;
+                if (s_oe[mid] < y) a = mid + 1; else b = mid;
+            }
+            sh = a;
+        }
+        wave_fence();                         // every lane has read its entry
+        if (act && sh) { d_oe[idx + sh] = y; d_life[idx + sh] = z; }
+        if (ballot(act && sh) == 0) break;    // sorted: nothing below moves either
+        hi = lo;
+    }
+    wave_fence();
+    for (uint32_t j = l; j < ns; j += WAVE) {
+        const uint32_t q = pos[j];
+        d_oe[q] = s_oe[j]; d_life[q] = s_life[j];
+    }
+    wave_fence();
+}
+
 // sweep32 over a long global list with all PW waves: chunk q of a round belongs to wave
 // q % PW.  Every wave scans its chunks, the chunk maxima are exchanged through LDS, each
 // wave then tests its chunks for the first hole with the right carry, and the lowest hole
-// of the round wins.  Two workgroup barriers per round.  All waves pass the same arguments
-// and get the same result.
+// of the round wins.  Two workgroup barriers per round; the next round's loads are issued
+// before the current round is processed.  All waves pass the same arguments and get the
+// same result.
 __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_t *life, uint32_t n,
                                                uint32_t &cursor, uint32_t P, uint32_t s, uint32_t a, uint32_t f,
                                                uint32_t wave, uint32_t *s_cmax, uint32_t *s_hq, uint32_t *s_hans)
 {
     const int l = lane_id();
     uint32_t i = cursor;
+    uint64_t x[COOP_U], lf[COOP_U], nx[COOP_U], nlf[COOP_U];
+#pragma unroll
+    for (int k = 0; k < COOP_U; ++k) {
+        const uint32_t idx = i + (k * PW + wave) * WAVE + l;
+        nx[k] = 0; nlf[k] = 0;
+        if (idx < n) { nx[k] = oe[idx]; nlf[k] = life[idx]; }
+    }
     for (;;) {
-        uint64_t x[COOP_U], lf[COOP_U];
+#pragma unroll
+        for (int k = 0; k < COOP_U; ++k) { x[k] = nx[k]; lf[k] = nlf[k]; }
 #pragma unroll
         for (int k = 0; k < COOP_U; ++k) {
-            const uint32_t idx = i + (k * PW + wave) * WAVE + l;
-            x[k] = 0; lf[k] = 0;
-            if (idx < n) { x[k] = oe[idx]; lf[k] = life[idx]; }
+            const uint32_t idx = i + ROUND_CH * WAVE + (k * PW + wave) * WAVE + l;
+            nx[k] = 0; nlf[k] = 0;
+            if (idx < n) { nx[k] = oe[idx]; nlf[k] = life[idx]; }
         }
         uint32_t incl[COOP_U];
 #pragma unroll
@@ -434,7 +465,7 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_
         __syncthreads();
         const uint32_t cm = (l < ROUND_CH) ? s_cmax[l] : 0;
         const uint32_t pin = wave_scan_max32(cm);
-        const uint32_t total = __shfl(pin, ROUND_CH - 1, WAVE);
+        const uint32_t total = read_lane(pin, ROUND_CH - 1);
         uint32_t best_q = NONE32, best_ans = 0;
 #pragma unroll
         for (int k = 0; k < COOP_U; ++k) {
@@ -472,10 +503,10 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
     __shared__ uint64_t p_oe[PEND], p_life[PEND];
     __shared__ uint64_t r_oe[REC], r_life[REC];
-    __shared__ uint32_t s_np, s_nm, s_bc;
+    __shared__ uint32_t s_np, s_bc;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
-    __shared__ uint32_t s_pos[REC];
+    __shared__ uint32_t s_pos[PEND];
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
     const bool mode1 = A.hdr->mode1 != 0;
@@ -486,8 +517,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 
     const uint32_t n = A.n, T = A.T;
     const uint32_t *perm = A.perm + (size_t)b * n;
-    uint64_t *m_oe = A.m_oe + (size_t)b * n;
-    uint64_t *m_life = A.m_life + (size_t)b * n;
+    uint64_t *m_oe[2] = {A.m_oe[0] + (size_t)b * n, A.m_oe[1] + (size_t)b * n};
+    uint64_t *m_life[2] = {A.m_life[0] + (size_t)b * n, A.m_life[1] + (size_t)b * n};
     uint64_t *L = A.L + (size_t)b * A.capL;
     uint32_t *l_ns = A.l_ns + (size_t)b * T;
     uint32_t *l_nu = A.l_nu + (size_t)b * T;
@@ -495,7 +526,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 
     // variables that will still query ALL: every one when there are no per-step lists
     uint32_t multi_left = mode1 ? A.hdr->n_multi : n;
-    AllState st{0, 0};
+    // ALL list state, identical in every wave: main buffer in use, main / recent counts
+    uint32_t mb = 0, nm = 0, nr = 0;
     uint32_t fp = 0;
     if (threadIdx.x == 0) s_np = 0;
     __syncthreads();
@@ -507,8 +539,11 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     uint64_t e[LCH];
 #pragma unroll
     for (int c = 0; c < LCH; ++c) e[c] = U64_MAX;
+    // per lane, for the one-step variable of this lane's rank: list start, sorted and
+    // unsorted entry counts of its step (kept current by the code below)
+    uint32_t plb = 0, pns = 0, pnu = 0;
 
-    auto writeback = [&]() {
+    auto writeback = [&](uint32_t a_lane) {
         if (cur_t != NONE32 && wb_from != NONE32) {
             uint64_t *Lt = L + A.lstart[cur_t];
 #pragma unroll
@@ -519,7 +554,36 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
             if (l == 0) { l_ns[cur_t] = cnt; l_nu[cur_t] = 0; }
             wmask |= 1ull << ((cur_t / PW) & 63);
         }
+        if (cur_t != NONE32 && a_lane == cur_t) { pns = cnt; pnu = 0; }
         wb_from = NONE32;
+    };
+
+    // recent is full or cannot take `incoming` more entries: merge it into main (all waves)
+    auto make_room = [&](uint32_t incoming) {
+        if (nr + incoming > REC) {
+            coop_merge_main(m_oe[mb], m_life[mb], nm, r_oe, r_life, nr, m_oe[mb ^ 1], m_life[mb ^ 1], wave);
+            mb ^= 1;
+            nm += nr;
+            nr = 0;
+            __syncthreads();
+        }
+    };
+
+    // pending -> recent (all waves call it; wave 0 sorts and merges in LDS)
+    auto flush = [&](uint32_t np) {
+        if (np == 0) return;
+        make_room(np);
+        if (wave == 0) {
+            uint32_t m = WAVE;
+            while (m < np) m <<= 1;
+            for (uint32_t i = np + l; i < m; i += WAVE) { p_oe[i] = U64_MAX; p_life[i] = 0; }
+            wave_fence();
+            bitonic_sort(p_oe, p_life, m);
+            merge_lds(r_oe, r_life, nr, p_oe, p_life, np, s_pos);
+            if (l == 0) s_np = 0;
+        }
+        nr += np;
+        __syncthreads();
     };
 
     for (uint32_t r0 = 0; r0 < n; r0 += WAVE) {
@@ -535,25 +599,26 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         const uint64_t im = ballot(in);
         const uint64_t mm = ballot(in && (!mode1 || f - a > 1));
         const uint32_t wn = (uint32_t)__popcll(im);
+        const bool one_step = in && mode1 && f - a == 1;
+        if (one_step) { plb = A.lstart[a]; pns = l_ns[a]; pnu = l_nu[a]; }
+        if (cur_t != NONE32 && one_step && a == cur_t) { pns = cnt; pnu = 0; }   // the cached list is newer
         uint32_t p = 0;
         while (p < wn) {
             if ((mm >> p) & 1ull) {
-                // ---- a variable that queries ALL: every wave sweeps, wave 0 keeps the lists ----
-                if (cur_t != NONE32) { writeback(); cur_t = NONE32; }
+                // ---- a variable that queries ALL: every wave sweeps, wave 0 keeps recent ----
+                if (cur_t != NONE32) { writeback(one_step ? a : NONE32); cur_t = NONE32; }
                 __syncthreads();
                 const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
                 const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
-                if (wave == 0) {
-                    flush_pending(p_oe, p_life, s_np, r_oe, r_life, m_oe, m_life, st, s_pos);
-                    if (l == 0) { s_nm = st.nm; s_np = 0; }
-                }
+                const uint32_t np = s_np;
                 __syncthreads();
-                const uint32_t nm = s_nm;
+                flush(np);
                 uint32_t o = 0, cm = 0, cr = 0;
                 for (;;) {
-                    const uint32_t o1 = coop_sweep(m_oe, m_life, nm, cm, o, vs, va, vf, wave, s_cmax, s_hq, s_hans);
+                    const uint32_t o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax, s_hq,
+                                                   s_hans);
                     if (wave == 0) {
-                        const uint32_t o2 = st.nr ? sweep32<true>(r_oe, r_life, st.nr, cr, o1, vs, va, vf) : o1;
+                        const uint32_t o2 = nr ? sweep32<true>(r_oe, r_life, nr, cr, o1, vs, va, vf) : o1;
                         if (l == 0) s_bc = o2;
                     }
                     __syncthreads();
@@ -563,16 +628,14 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 const uint32_t en = o + vs;
                 fp = max(fp, en);
                 if (threadIdx.x == 0) offs[vv] = (uint64_t)o << sh;
-                if (wave == 0 && multi_left > 1) {      // someone will still query ALL
-                    if (st.nr == REC) {
-                        merge_into(m_oe, m_life, st.nm, r_oe, r_life, st.nr, s_pos);
-                        st.nm += st.nr;
-                        st.nr = 0;
+                if (multi_left > 1) {                   // someone will still query ALL
+                    make_room(1);
+                    if (wave == 0) {
+                        const uint64_t x = pk(o, en);
+                        const uint32_t ip = count_below32(r_oe, nr, x);
+                        insert_at32(r_oe, r_life, nr, ip, x, ((uint64_t)va << 32) | vf);
                     }
-                    const uint64_t x = pk(o, en);
-                    const uint32_t ip = count_below32(r_oe, st.nr, x);
-                    insert_at32(r_oe, r_life, st.nr, ip, x, ((uint64_t)va << 32) | vf);
-                    ++st.nr;
+                    ++nr;
                 }
                 if (mode1) {
                     const uint64_t x = pk(o, en);
@@ -584,6 +647,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 }
                 --multi_left;
                 __syncthreads();
+                // the tails of the steps it covers grew: refresh the counts of the ranks to come
+                if (one_step && (uint32_t)l > p && a >= va && a < vf) pnu = l_nu[a];
                 ++p;
             } else {
                 // ---- a run of one-step variables: each wave takes the steps it owns --------
@@ -594,24 +659,21 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 while (mine) {
                     const int j = __ffsll((unsigned long long)mine) - 1;
                     mine &= mine - 1;
-                    const uint32_t vv = __shfl(v, j, WAVE), t = __shfl(a, j, WAVE), vs = __shfl(s, j, WAVE);
+                    const uint32_t vv = read_lane(v, j), t = read_lane(a, j), vs = read_lane(s, j);
                     uint32_t o;
                     if (t != cur_t) {
-                        writeback();
+                        writeback(one_step ? a : NONE32);
                         cur_t = NONE32;
-                        const uint32_t base = A.lstart[t];
-                        const uint32_t cap = A.lstart[t + 1] - base;
+                        const uint32_t base = read_lane(plb, j);
+                        const uint32_t ns = read_lane(pns, j), nu = read_lane(pnu, j), tot = ns + nu;
                         if (wmask & (1ull << ((t / PW) & 63))) { wave_fence(); wmask = 0; }
-                        if (cap <= LREG) {
-                            // counts and (speculatively, up to the list's capacity) entries in one go
+                        if (tot + 1 <= LREG) {
                             const uint64_t *Lt = L + base;
-                            const uint32_t ns = l_ns[t], nu = l_nu[t];
 #pragma unroll
                             for (int c = 0; c < LCH; ++c) {
                                 const uint32_t idx = c * WAVE + l;
-                                if ((uint32_t)c * WAVE < cap && idx < cap) e[c] = Lt[idx];
+                                e[c] = ((uint32_t)c * WAVE < tot && idx < tot) ? Lt[idx] : U64_MAX;
                             }
-                            const uint32_t tot = ns + nu;
                             for (uint32_t jj = ns; jj < tot; ++jj) {      // merge the unsorted tail
                                 const uint64_t x = reg_extract(e, jj);
                                 const uint32_t pp = reg_count_below(e, jj, x);
@@ -622,7 +684,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                             cnt = tot;
                         }
                     }
-                    if (cur_t == t) {
+                    if (cur_t == t && cnt + 1 <= LREG) {
                         uint32_t pos;
                         o = reg_sweep(e, cnt, vs, pos);
                         reg_insert(e, cnt, pos, pk(o, o + vs));
@@ -630,6 +692,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         ++cnt;
                     } else {
                         // list too long for registers: same steps directly in global memory
+                        if (cur_t == t) { writeback(one_step ? a : NONE32); cur_t = NONE32; wave_fence(); wmask = 0; }
                         uint64_t *Lt = L + A.lstart[t];
                         const uint32_t ns = l_ns[t], nu = l_nu[t], tot = ns + nu;
                         for (uint32_t jj = ns; jj < tot; ++jj) {
@@ -643,6 +706,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         insert_at32(Lt, nullptr, tot, pos, pk(o, o + vs), 0);
                         if (l == 0) { l_ns[t] = tot + 1; l_nu[t] = 0; }
                         wave_fence();
+                        if (one_step && a == t) { pns = tot + 1; pnu = 0; }
                     }
                     fp = max(fp, o + vs);
                     if (l == 0) {
@@ -659,16 +723,10 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         }
         __syncthreads();
         // keep room for the next window's placements (every wave reads the count before
-        // wave 0 may reset it)
+        // it may be reset)
         const uint32_t np_now = s_np;
         __syncthreads();
-        if (np_now + WAVE > PEND) {
-            if (wave == 0) {
-                flush_pending(p_oe, p_life, np_now, r_oe, r_life, m_oe, m_life, st, s_pos);
-                if (l == 0) s_np = 0;
-            }
-            __syncthreads();
-        }
+        if (np_now + WAVE > PEND) flush(np_now);
     }
     if (l == 0) s_fp[wave] = fp;
     __syncthreads();
@@ -691,10 +749,12 @@ hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const 
 
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr,
-                             const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *L, uint64_t capL,
-                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st)
+                             const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
+                             uint64_t *m_life2, uint64_t *L, uint64_t capL, uint32_t *l_ns, uint32_t *l_nu,
+                             uint64_t *offs, uint64_t *fps, hipStream_t st)
 {
-    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, m_oe, m_life, L, l_ns, l_nu, capL, offs, fps};
+    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, L, l_ns, l_nu, capL,
+               offs, fps};
     hipLaunchKernelGGL(k_place_fast, dim3(B), dim3(PW * WAVE), 0, st, A);
     return hipGetLastError();
 }
