@@ -17,12 +17,15 @@
 //          the remaining ends gives the highest occupied address so far, and
 //          the first entry whose offset leaves a hole of at least `size` above
 //          it ends the sweep ("the first hole that the variable can fit in").
-//   L[t]   (only when the sum of all lifetimes is at most CL*N steps) the
-//          blocks live at step t: a sorted prefix plus an unsorted tail.  A
-//          variable that lives for exactly one step t only meets blocks live
-//          at t, so its query is one sweep over L[t] held in registers.
-//          Multi-step blocks are appended to the tails of every step they
-//          cover and merged into the prefix by the next query of that step.
+//   L[t]   (only when the sum of all lifetimes, plus one per step, is at most
+//          CL*N) the FREE address ranges ("holes") at step t, sorted by start,
+//          packed (start << 32 | size), the last one reaching to 2^32-1;
+//          followed by an unsorted tail of multi-step blocks that were placed
+//          since and still have to be carved out.  A variable that lives for
+//          exactly one step t only meets blocks live at t, so its first fit is
+//          the first hole of L[t] that is large enough; taking it only shrinks
+//          that hole in place (first fit always starts at a hole's start).
+//          The list is held in registers while a wave works on step t.
 //
 // One-step variables of different steps never interact, so between two
 // multi-step variables of the rank order the waves work in parallel: wave w
@@ -36,9 +39,8 @@ namespace lap {
 
 constexpr int PW = 4;               // waves per ordering
 constexpr uint32_t PEND = 512;      // pending (unsorted) entries in LDS
-constexpr uint32_t REC = 1536;      // recent (sorted) entries in LDS
-constexpr int LCH = 18;             // chunks of a per-step list held in registers
-constexpr uint32_t LREG = LCH * WAVE;
+constexpr uint32_t REC = PLAN_REC;  // recent (sorted) entries, global memory
+constexpr uint32_t LH = 768;        // entries of a per-step list a wave can hold in LDS
 constexpr uint32_t CL = PLAN_CL;    // per-step lists need sum of lifetimes <= CL * N
 constexpr int UNROLL = 4;           // chunks loaded ahead by a sweep
 
@@ -99,7 +101,7 @@ __device__ __forceinline__ uint64_t prep_block_scan(uint64_t v, uint64_t *wtmp, 
     return pre + incl;
 }
 
-// live[t] = number of variables live at step t; lstart = exclusive prefix sum of live
+// live[t] = number of variables live at step t; lstart = exclusive prefix sum of live + 1
 __global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_t T,
                                                              const uint32_t *__restrict__ cntd,
                                                              uint32_t *__restrict__ lstart, PlanHeader *hdr)
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_
         const bool in = t < T;
         const uint64_t d = in ? (uint64_t)(int64_t)(int32_t)cntd[t] : 0;     // signed delta
         const uint64_t live = c1 + prep_block_scan(d, wtmp, tot); c1 += tot;
-        const uint64_t lv = in ? live : 0;
+        const uint64_t lv = in ? live + 1 : 0;                // room for the holes: blocks + 1
         const uint64_t incl = c2 + prep_block_scan(lv, wtmp, tot);
         if (in) lstart[t] = (uint32_t)(incl - lv);
         c2 += tot;
@@ -206,13 +208,39 @@ __device__ __forceinline__ void insert_at32(uint64_t *oe, uint64_t *life, uint32
         const bool act = idx < hi;
         uint64_t y = 0, z = 0;
         if (act) { y = oe[idx]; if (life) z = life[idx]; }
-        wave_fence();
+        // the stores carry the loaded values, so they issue after every lane's load; the
+        // next iteration reads strictly lower indices than any store so far
         if (act) { oe[idx + 1] = y; if (life) life[idx + 1] = z; }
-        wave_fence();
         hi = lo;
     }
     if (l == 0) { oe[p] = x; if (life) life[p] = lf; }
     wave_fence();
+}
+
+// index of the first of the nh holes of a list in memory with size >= s
+__device__ __forceinline__ uint32_t mem_first_fit(const uint64_t *Lt, uint32_t nh, uint32_t s)
+{
+    const int l = lane_id();
+    for (uint32_t base = 0; base < nh; base += WAVE) {
+        const uint32_t idx = base + l;
+        const uint64_t m = ballot(idx < nh && (uint32_t)Lt[idx < nh ? idx : 0] >= s);
+        if (m) return base + __ffsll((unsigned long long)m) - 1;
+    }
+    return nh - 1;
+}
+
+// index of the hole of a list in memory that contains address o
+__device__ __forceinline__ uint32_t mem_find_hole(const uint64_t *Lt, uint32_t nh, uint32_t o)
+{
+    const int l = lane_id();
+    for (uint32_t base = 0; base < nh; base += WAVE) {
+        const uint32_t idx = base + l;
+        const uint64_t x = Lt[idx < nh ? idx : 0];
+        const uint32_t st = (uint32_t)(x >> 32), sz = (uint32_t)x;
+        const uint64_t m = ballot(idx < nh && st <= o && o - st < sz);
+        if (m) return base + __ffsll((unsigned long long)m) - 1;
+    }
+    return nh - 1;
 }
 
 // bitonic sort of m (power of two, >= 64) packed entries with their lifetimes, in LDS, one wave
@@ -238,71 +266,89 @@ __device__ __forceinline__ void bitonic_sort(uint64_t *oe, uint64_t *life, uint3
 }
 
 // ---------------------------------------------------------------------------
-// a per-step list held in registers: entry c*64+lane lives in e[c]
+// a per-step hole list held in LDS by one wave (packed start << 32 | size, sorted by start)
 // ---------------------------------------------------------------------------
 
-__device__ __forceinline__ uint32_t reg_count_below(const uint64_t (&e)[LCH], uint32_t cnt, uint64_t key)
+// orders this wave's LDS accesses for the compiler; the LDS unit serves a wave in order
+__device__ __forceinline__ void lds_sync()
 {
-    const int l = lane_id();
-    uint32_t p = 0;
-#pragma unroll
-    for (int c = 0; c < LCH; ++c) {
-        if ((uint32_t)c * WAVE < cnt) {
-            const uint32_t idx = c * WAVE + l;
-            p += (uint32_t)__popcll(ballot(idx < cnt && e[c] < key));
-        }
-    }
-    return p;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
-// entries [p, cnt) move up by one, x goes to position p  (cnt < LREG)
-__device__ __forceinline__ void reg_insert(uint64_t (&e)[LCH], uint32_t cnt, uint32_t p, uint64_t x)
+// index of the first of the nh holes with size >= s (there always is one: the top hole)
+__device__ __forceinline__ uint32_t h_first_fit(const uint64_t *hl, uint32_t nh, uint32_t s)
 {
     const int l = lane_id();
-#pragma unroll
-    for (int c = LCH - 1; c >= 0; --c) {
-        if ((uint32_t)c * WAVE <= cnt && (uint32_t)c * WAVE + WAVE > p) {
-            const uint32_t idx = c * WAVE + l;
-            const uint64_t carry = c > 0 ? read_lane64(e[c > 0 ? c - 1 : 0], WAVE - 1) : 0;
-            const uint64_t prev = lane_shift_up64(e[c], carry);
-            if (idx > p && idx <= cnt) e[c] = prev;
-            else if (idx == p) e[c] = x;
-        }
+    for (uint32_t base = 0; base < nh; base += 2 * WAVE) {
+        const uint32_t i0 = base + l, i1 = base + WAVE + l;
+        const uint32_t z0 = i0 < nh ? (uint32_t)hl[i0] : 0u;
+        const uint32_t z1 = i1 < nh ? (uint32_t)hl[i1] : 0u;
+        const uint64_t m0 = ballot(z0 >= s);                 // s >= 1, empty slots read as size 0
+        if (m0) return base + __ffsll((unsigned long long)m0) - 1;
+        const uint64_t m1 = ballot(z1 >= s);
+        if (m1) return base + WAVE + __ffsll((unsigned long long)m1) - 1;
     }
+    return nh - 1;
 }
 
-__device__ __forceinline__ uint64_t reg_extract(const uint64_t (&e)[LCH], uint32_t j)
-{
-    uint64_t x = 0;
-#pragma unroll
-    for (int c = 0; c < LCH; ++c)
-        if ((uint32_t)c == (j >> 6)) x = read_lane64(e[c], (int)(j & 63));
-    return x;
-}
-
-// First-fit over the cnt sorted entries of a per-step list.  All of them are live at the
-// same step, hence pairwise disjoint in address: ends ascend with offsets and the highest
-// occupied address below entry i is simply the end of entry i-1.  pos = where the block goes.
-__device__ __forceinline__ uint32_t reg_sweep(const uint64_t (&e)[LCH], uint32_t cnt, uint32_t s, uint32_t &pos)
+// index of the hole that contains address o (start <= o < start + size)
+__device__ __forceinline__ uint32_t h_find_hole(const uint64_t *hl, uint32_t nh, uint32_t o)
 {
     const int l = lane_id();
-#pragma unroll
-    for (int c = 0; c < LCH; ++c) {
-        if ((uint32_t)c * WAVE <= cnt) {
-            const uint32_t idx = c * WAVE + l;
-            const uint32_t carry = c > 0 ? read_lane((uint32_t)e[c > 0 ? c - 1 : 0], WAVE - 1) : 0u;
-            const uint32_t prev = lane_shift_up((uint32_t)e[c], carry);
-            const uint32_t o = (uint32_t)(e[c] >> 32);
-            const uint64_t hole = ballot(idx >= cnt || (o >= prev && o - prev >= s));
-            if (hole) {
-                const int first = __ffsll((unsigned long long)hole) - 1;
-                pos = c * WAVE + first;
-                return read_lane(prev, first);
-            }
-        }
+    for (uint32_t base = 0; base < nh; base += WAVE) {
+        const uint32_t idx = base + l;
+        const uint64_t x = idx < nh ? hl[idx] : 0ull;
+        const uint32_t st = (uint32_t)(x >> 32), sz = (uint32_t)x;
+        const uint64_t m = ballot(st <= o && o - st < sz);
+        if (m) return base + __ffsll((unsigned long long)m) - 1;
     }
-    pos = cnt;
-    return 0;
+    return nh - 1;
+}
+
+// entries [p, n) move up by one, x goes to position p
+__device__ __forceinline__ void h_insert(uint64_t *hl, uint32_t n, uint32_t p, uint64_t x)
+{
+    const int l = lane_id();
+    uint32_t hi = n;
+    while (hi > p) {
+        const uint32_t lo = (hi - p > (uint32_t)WAVE) ? hi - WAVE : p;
+        const uint32_t idx = lo + l;
+        uint64_t y = 0;
+        if (idx < hi) y = hl[idx];
+        lds_sync();
+        if (idx < hi) hl[idx + 1] = y;
+        hi = lo;
+    }
+    lds_sync();
+    if (l == 0) hl[p] = x;
+    lds_sync();
+}
+
+// Remove the block [o, en) from the free ranges: it lies inside exactly one hole.  The list
+// holds nh holes followed by ntail other entries (which move up if a hole is split).  Returns
+// the number of holes afterwards; [lo, hi) is extended to the entries that changed.
+__device__ __forceinline__ uint32_t h_carve(uint64_t *hl, uint32_t nh, uint32_t ntail, uint32_t o, uint32_t en,
+                                            uint32_t &lo, uint32_t &hi)
+{
+    const int l = lane_id();
+    const uint32_t h = h_find_hole(hl, nh, o);
+    const uint64_t x = hl[h];
+    const uint32_t st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
+    lo = min(lo, h);
+    lds_sync();
+    if (o == st) {                       // block at the hole's start: the hole shrinks from below
+        if (l == 0) hl[h] = pk(en, hend - en);
+        lds_sync();
+        hi = max(hi, h + 1);
+        return nh;
+    }
+    if (l == 0) hl[h] = pk(st, o - st);  // lower part stays
+    lds_sync();
+    if (en == hend) { hi = max(hi, h + 1); return nh; }
+    h_insert(hl, nh + ntail, h + 1, pk(en, hend - en));   // upper part: a new hole after it
+    hi = max(hi, nh + ntail + 1);
+    return nh + 1;
 }
 
 // ---------------------------------------------------------------------------
@@ -317,11 +363,13 @@ struct FastArgs {
     const PlanHeader *hdr;
     const uint32_t *lstart;      // [T+1]
     uint64_t *m_oe[2], *m_life[2];  // [B][n] x 2  ALL main list, two buffers (merges ping-pong)
+    uint64_t *r_oe, *r_life;     // [B][REC]    ALL recent list
     uint64_t *L;                 // [B][capL]   per-step lists, packed blocks
     uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts
     uint64_t capL;
     uint64_t *offs;              // [B][n]
     uint64_t *fps;               // [B]
+    unsigned long long *probe;   // optional per-wave cycle counters (instrumented builds only)
 };
 
 constexpr int COOP_U = 4;                    // chunks per wave in one cooperative round
@@ -502,7 +550,8 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_
 __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
     __shared__ uint64_t p_oe[PEND], p_life[PEND];
-    __shared__ uint64_t r_oe[REC], r_life[REC];
+    __shared__ uint64_t s_h[PW][LH];         // per-wave hole list; staging area for main merges
+    static_assert(REC * 2 <= PW * LH, "the recent list is staged in the hole-list area");
     __shared__ uint32_t s_np, s_bc;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
@@ -519,6 +568,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     const uint32_t *perm = A.perm + (size_t)b * n;
     uint64_t *m_oe[2] = {A.m_oe[0] + (size_t)b * n, A.m_oe[1] + (size_t)b * n};
     uint64_t *m_life[2] = {A.m_life[0] + (size_t)b * n, A.m_life[1] + (size_t)b * n};
+    uint64_t *r_oe = A.r_oe + (size_t)b * REC;
+    uint64_t *r_life = A.r_life + (size_t)b * REC;
+    uint64_t *hl = s_h[wave];
     uint64_t *L = A.L + (size_t)b * A.capL;
     uint32_t *l_ns = A.l_ns + (size_t)b * T;
     uint32_t *l_nu = A.l_nu + (size_t)b * T;
@@ -530,15 +582,20 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     uint32_t mb = 0, nm = 0, nr = 0;
     uint32_t fp = 0;
     if (threadIdx.x == 0) s_np = 0;
+    if (mode1) {
+        // every step starts with one hole covering the whole address space
+        for (uint32_t t = threadIdx.x; t < T; t += PW * WAVE) {
+            L[A.lstart[t]] = pk(0u, NONE32);
+            l_ns[t] = 1;
+        }
+    }
     __syncthreads();
 
-    // this wave's register-resident per-step list: step, entries, count, first index not yet
-    // written back; wmask remembers (hashed) which lists were stored since the last fence
-    uint32_t cur_t = NONE32, cnt = 0, wb_from = NONE32;
+    // this wave's register-resident per-step list: step, entries, hole count, range of
+    // indices not yet written back; wmask remembers (hashed) which lists were stored since
+    // the last fence
+    uint32_t cur_t = NONE32, cnt = 0, wb_from = NONE32, wb_to = 0;
     uint64_t wmask = 0;
-    uint64_t e[LCH];
-#pragma unroll
-    for (int c = 0; c < LCH; ++c) e[c] = U64_MAX;
     // per lane, for the one-step variable of this lane's rank: list start, sorted and
     // unsorted entry counts of its step (kept current by the code below)
     uint32_t plb = 0, pns = 0, pnu = 0;
@@ -546,22 +603,25 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     auto writeback = [&](uint32_t a_lane) {
         if (cur_t != NONE32 && wb_from != NONE32) {
             uint64_t *Lt = L + A.lstart[cur_t];
-#pragma unroll
-            for (int c = 0; c < LCH; ++c) {
-                const uint32_t idx = c * WAVE + l;
-                if ((uint32_t)c * WAVE < cnt && idx >= wb_from && idx < cnt) Lt[idx] = e[c];
-            }
+            for (uint32_t idx = wb_from + l; idx < wb_to; idx += WAVE) Lt[idx] = hl[idx];
             if (l == 0) { l_ns[cur_t] = cnt; l_nu[cur_t] = 0; }
             wmask |= 1ull << ((cur_t / PW) & 63);
         }
         if (cur_t != NONE32 && a_lane == cur_t) { pns = cnt; pnu = 0; }
         wb_from = NONE32;
+        wb_to = 0;
     };
 
     // recent is full or cannot take `incoming` more entries: merge it into main (all waves)
-    auto make_room = [&](uint32_t incoming) {
+    auto make_room = [&](uint32_t incoming, uint32_t a_lane) {
         if (nr + incoming > REC) {
-            coop_merge_main(m_oe[mb], m_life[mb], nm, r_oe, r_life, nr, m_oe[mb ^ 1], m_life[mb ^ 1], wave);
+            // the hole-list area becomes the staging copy of recent: give the lists back first
+            if (cur_t != NONE32) { writeback(a_lane); cur_t = NONE32; }
+            __syncthreads();
+            uint64_t *st_oe = &s_h[0][0], *st_life = st_oe + REC;
+            for (uint32_t i = threadIdx.x; i < nr; i += PW * WAVE) { st_oe[i] = r_oe[i]; st_life[i] = r_life[i]; }
+            __syncthreads();
+            coop_merge_main(m_oe[mb], m_life[mb], nm, st_oe, st_life, nr, m_oe[mb ^ 1], m_life[mb ^ 1], wave);
             mb ^= 1;
             nm += nr;
             nr = 0;
@@ -570,9 +630,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     };
 
     // pending -> recent (all waves call it; wave 0 sorts and merges in LDS)
-    auto flush = [&](uint32_t np) {
+    auto flush = [&](uint32_t np, uint32_t a_lane) {
         if (np == 0) return;
-        make_room(np);
+        make_room(np, a_lane);
         if (wave == 0) {
             uint32_t m = WAVE;
             while (m < np) m <<= 1;
@@ -586,6 +646,17 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         __syncthreads();
     };
 
+#ifdef LAP_PROBE
+    uint64_t pc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#define PROBE_T(v) const uint64_t v = clock64()
+#define PROBE_ACC(k, v) pc[k] += clock64() - v
+#define PROBE_CNT(k, x) pc[k] += (x)
+    const uint64_t t_begin = clock64();
+#else
+#define PROBE_T(v)
+#define PROBE_ACC(k, v)
+#define PROBE_CNT(k, x)
+#endif
     for (uint32_t r0 = 0; r0 < n; r0 += WAVE) {
         const uint32_t ridx = r0 + l;
         const bool in = ridx < n;
@@ -606,13 +677,15 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         while (p < wn) {
             if ((mm >> p) & 1ull) {
                 // ---- a variable that queries ALL: every wave sweeps, wave 0 keeps recent ----
+                PROBE_T(t2);
                 if (cur_t != NONE32) { writeback(one_step ? a : NONE32); cur_t = NONE32; }
                 __syncthreads();
                 const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
                 const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
                 const uint32_t np = s_np;
                 __syncthreads();
-                flush(np);
+                flush(np, one_step ? a : NONE32);
+                PROBE_ACC(0, t2); PROBE_T(t3);
                 uint32_t o = 0, cm = 0, cr = 0;
                 for (;;) {
                     const uint32_t o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax, s_hq,
@@ -625,11 +698,12 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     o = s_bc;
                     if (o == o1) break;
                 }
+                PROBE_ACC(1, t3); PROBE_T(t4);
                 const uint32_t en = o + vs;
                 fp = max(fp, en);
                 if (threadIdx.x == 0) offs[vv] = (uint64_t)o << sh;
                 if (multi_left > 1) {                   // someone will still query ALL
-                    make_room(1);
+                    make_room(1, NONE32);
                     if (wave == 0) {
                         const uint64_t x = pk(o, en);
                         const uint32_t ip = count_below32(r_oe, nr, x);
@@ -645,6 +719,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         l_nu[t] = l_nu[t] + 1;
                     }
                 }
+                PROBE_ACC(2, t4);
                 --multi_left;
                 __syncthreads();
                 // the tails of the steps it covers grew: refresh the counts of the ranks to come
@@ -652,6 +727,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 ++p;
             } else {
                 // ---- a run of one-step variables: each wave takes the steps it owns --------
+                PROBE_T(t5);
                 const uint64_t rest = (~mm & im) >> p;
                 const uint32_t run = (~rest == 0ull) ? 64u : (uint32_t)(__ffsll((unsigned long long)~rest) - 1);
                 const uint32_t q = p + run;
@@ -661,52 +737,68 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     mine &= mine - 1;
                     const uint32_t vv = read_lane(v, j), t = read_lane(a, j), vs = read_lane(s, j);
                     uint32_t o;
+                    if (t != cur_t) PROBE_CNT(5, 1);
                     if (t != cur_t) {
                         writeback(one_step ? a : NONE32);
                         cur_t = NONE32;
                         const uint32_t base = read_lane(plb, j);
                         const uint32_t ns = read_lane(pns, j), nu = read_lane(pnu, j), tot = ns + nu;
                         if (wmask & (1ull << ((t / PW) & 63))) { wave_fence(); wmask = 0; }
-                        if (tot + 1 <= LREG) {
+                        if (tot + 1 <= LH) {
                             const uint64_t *Lt = L + base;
-#pragma unroll
-                            for (int c = 0; c < LCH; ++c) {
-                                const uint32_t idx = c * WAVE + l;
-                                e[c] = ((uint32_t)c * WAVE < tot && idx < tot) ? Lt[idx] : U64_MAX;
-                            }
-                            for (uint32_t jj = ns; jj < tot; ++jj) {      // merge the unsorted tail
-                                const uint64_t x = reg_extract(e, jj);
-                                const uint32_t pp = reg_count_below(e, jj, x);
-                                reg_insert(e, jj, pp, x);
-                                wb_from = min(wb_from, pp);
+                            for (uint32_t idx = l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
+                            lds_sync();
+                            PROBE_CNT(6, tot - ns);
+                            // carve the multi-step blocks that arrived since out of the holes, last
+                            // tail entry first (a split moves the rest of the tail up with it)
+                            uint32_t nh = ns;
+                            for (uint32_t nt = nu; nt > 0; --nt) {
+                                const uint64_t x = hl[nh + nt - 1];
+                                nh = h_carve(hl, nh, nt - 1, (uint32_t)(x >> 32), (uint32_t)x, wb_from, wb_to);
                             }
                             cur_t = t;
-                            cnt = tot;
+                            cnt = nh;
                         }
                     }
-                    if (cur_t == t && cnt + 1 <= LREG) {
-                        uint32_t pos;
-                        o = reg_sweep(e, cnt, vs, pos);
-                        reg_insert(e, cnt, pos, pk(o, o + vs));
-                        wb_from = min(wb_from, pos);
-                        ++cnt;
+                    if (cur_t == t) {
+                        const uint32_t h = h_first_fit(hl, cnt, vs);
+                        const uint64_t x = hl[h];
+                        o = (uint32_t)(x >> 32);
+                        lds_sync();
+                        if (l == 0) hl[h] = pk(o + vs, (uint32_t)x - vs);
+                        lds_sync();
+                        wb_from = min(wb_from, h);
+                        wb_to = max(wb_to, h + 1);
                     } else {
-                        // list too long for registers: same steps directly in global memory
-                        if (cur_t == t) { writeback(one_step ? a : NONE32); cur_t = NONE32; wave_fence(); wmask = 0; }
+                        // list too long for the LDS area: same steps directly in global memory
                         uint64_t *Lt = L + A.lstart[t];
-                        const uint32_t ns = l_ns[t], nu = l_nu[t], tot = ns + nu;
-                        for (uint32_t jj = ns; jj < tot; ++jj) {
-                            const uint64_t x = Lt[jj];
+                        uint32_t nh = l_ns[t];
+                        for (uint32_t nt = l_nu[t]; nt > 0; --nt) {
+                            const uint64_t xb = Lt[nh + nt - 1];
+                            const uint32_t bo = (uint32_t)(xb >> 32), be = (uint32_t)xb;
+                            const uint32_t h = mem_find_hole(Lt, nh, bo);
+                            const uint64_t x = Lt[h];
+                            const uint32_t st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
                             wave_fence();
-                            const uint32_t pp = count_below32(Lt, jj, x);
-                            insert_at32(Lt, nullptr, jj, pp, x, 0);
+                            if (bo == st) {
+                                if (l == 0) Lt[h] = pk(be, hend - be);
+                            } else {
+                                if (l == 0) Lt[h] = pk(st, bo - st);
+                                if (be != hend) {
+                                    wave_fence();
+                                    insert_at32(Lt, nullptr, nh + nt - 1, h + 1, pk(be, hend - be), 0);
+                                    ++nh;
+                                }
+                            }
+                            wave_fence();
                         }
-                        uint32_t pos = 0;
-                        o = sweep32<false>(Lt, nullptr, tot, pos, 0, vs, 0, 0);
-                        insert_at32(Lt, nullptr, tot, pos, pk(o, o + vs), 0);
-                        if (l == 0) { l_ns[t] = tot + 1; l_nu[t] = 0; }
+                        const uint32_t h = mem_first_fit(Lt, nh, vs);
+                        const uint64_t x = Lt[h];
+                        o = (uint32_t)(x >> 32);
                         wave_fence();
-                        if (one_step && a == t) { pns = tot + 1; pnu = 0; }
+                        if (l == 0) { Lt[h] = pk(o + vs, (uint32_t)x - vs); l_ns[t] = nh; l_nu[t] = 0; }
+                        wave_fence();
+                        if (one_step && a == t) { pns = nh; pnu = 0; }
                     }
                     fp = max(fp, o + vs);
                     if (l == 0) {
@@ -718,6 +810,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         }
                     }
                 }
+                PROBE_ACC(3, t5);
                 p = q;
             }
         }
@@ -726,8 +819,14 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         // it may be reset)
         const uint32_t np_now = s_np;
         __syncthreads();
-        if (np_now + WAVE > PEND) flush(np_now);
+        PROBE_T(t6);
+        if (np_now + WAVE > PEND) flush(np_now, NONE32);
+        PROBE_ACC(4, t6);
     }
+#ifdef LAP_PROBE
+    pc[7] = clock64() - t_begin;
+    if (l == 0 && A.probe) for (int k = 0; k < 8; ++k) A.probe[((size_t)b * PW + wave) * 8 + k] = pc[k];
+#endif
     if (l == 0) s_fp[wave] = fp;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -736,6 +835,10 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         A.fps[b] = (uint64_t)m << sh;
     }
 }
+
+static unsigned long long *g_probe = nullptr;
+// instrumented builds: device buffer of B * PW * 8 counters, or null
+extern "C" void lap_debug_set_probe(void *dev) { g_probe = (unsigned long long *)dev; }
 
 hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
                             const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st)
@@ -750,11 +853,12 @@ hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const 
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
-                             uint64_t *m_life2, uint64_t *L, uint64_t capL, uint32_t *l_ns, uint32_t *l_nu,
-                             uint64_t *offs, uint64_t *fps, hipStream_t st)
+                             uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *L, uint64_t capL,
+                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st)
 {
-    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, L, l_ns, l_nu, capL,
-               offs, fps};
+    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, r_oe, r_life, L, l_ns,
+               l_nu, capL,
+               offs, fps, g_probe};
     hipLaunchKernelGGL(k_place_fast, dim3(B), dim3(PW * WAVE), 0, st, A);
     return hipGetLastError();
 }
