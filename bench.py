@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="BASELINE config 1..5 (5 = transformer-shaped, the largest trace)")
     ap.add_argument("--orderings", type=int, default=0, help="override B (0 = the config's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build plans on ONE GPU (orderings would shard across GPUs, see DESIGN.md); "
@@ -60,6 +62,13 @@ def main() -> int:
     torch.cuda.synchronize()
     upload_s = time.perf_counter() - t0
     assert lap.validate_trace(dt) == 0
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = None
     lap.profile_enable(True)
@@ -97,8 +106,16 @@ def main() -> int:
     alg_bytes = B * (16 * n_edges + 24 * n)
     k_ms = float(np.mean(place_ms))
     achieved = alg_bytes / (k_ms * 1e-3) / 1e9
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (separate runs of this
+    # command, calibrated against a plain copy); only valid for the workload it was measured on
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "k_place_fast_transformer_B1024_hbm_traffic.txt")
+    if args.config == 5 and B == 1024 and os.path.exists(tpath):
+        for ln in open(tpath):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                traffic = int(ln.split(":")[1])
     roofline = dict(bound="hbm", kernel="k_place_fast", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBPS, traffic=None, kernel_ms=k_ms, algorithmic_bytes=alg_bytes,
+                    frac=achieved / HBM_PEAK_GBPS, traffic=traffic, kernel_ms=k_ms, algorithmic_bytes=alg_bytes,
                     sort_kernel_ms=float(np.mean(sort_ms)))
 
     cpu = None
