@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="BASELINE config 1..5 (5 = transformer-shaped, the largest trace)")
     ap.add_argument("--orderings", type=int, default=0, help="override B (0 = the config's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stress", action="store_true",
+                    help="skip the load-profile run on the 2 GiB time-tiled trace")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -132,6 +134,31 @@ def main() -> int:
         cpu = dict(value=n / c_s, unit="placements/s", cores=1, kind="oracle",
                    sample=f"first-fit placement of ordering 0 (size-descending), all {n} variables, {c_s:.1f} s")
 
+    # The load-profile kernel on the largest BASELINE trace moves 3.2 MB (launch-latency bound), so
+    # its HBM fraction is also measured on the same trace repeated along time until the SoA is ~2 GiB.
+    lp_small_ms = lap.profile_last_ms(lap.K_LOAD_SCATTER)
+    stress = None
+    if not args.no_stress:
+        from traces import tile_in_time
+        big = tile_in_time(tr, 670)
+        bdt = lap.DeviceTrace(big, dev, use_gaps=False)
+        ms_k, ms_call = [], []
+        for it in range(6):
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            blp = lap.load_profile(bdt)
+            ms_call.append(1e3 * (time.perf_counter() - c0))
+            ms_k.append(lap.profile_last_ms(lap.K_LOAD_SCATTER))
+        nbytes = 16 * big.n_vars + 8 * big.n_steps
+        k_ms, call_ms = float(np.median(ms_k[1:])), float(np.median(ms_call[1:]))
+        # same curve every iteration: the tiled profile repeats the single-iteration one
+        assert np.array_equal(u64(blp["load"])[:T], u64(lp["load"])) and int(u64(blp["peak"])[0]) == peak
+        stress = dict(workload="configs[4] repeated 670x along time (not a BASELINE config)", n_vars=big.n_vars,
+                      n_steps=big.n_steps, algorithmic_bytes=nbytes, kernel="k_delta_window", kernel_ms=k_ms,
+                      kernel_GBps=nbytes / k_ms / 1e6, kernel_frac=nbytes / k_ms / 1e6 / HBM_PEAK_GBPS,
+                      call_ms=call_ms, call_GBps=nbytes / call_ms / 1e6, call_frac=nbytes / call_ms / 1e6 / HBM_PEAK_GBPS)
+        del bdt, blp
+
     line = {
         "metric": "variable placements/sec across B orderings; footprint / peak-live-bytes ratio",
         "value": value, "unit": "placements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -143,6 +170,7 @@ def main() -> int:
         "footprint_over_peak": best_fp / peak, "best_ordering": int(out["best_ordering"].item()),
         "footprint_over_peak_fixed_orders": [float(x) / peak for x in fps[:4]],
         "roofline": roofline, "cpu_baseline": cpu,
+        "load_profile": {"kernel_ms_on_workload": lp_small_ms, "stress": stress},
     }
     print(json.dumps(line))
     return 0

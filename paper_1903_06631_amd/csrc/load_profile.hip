@@ -42,26 +42,51 @@ __global__ __launch_bounds__(256) void k_delta_lds(uint32_t n, uint32_t nbins,
     }
 }
 
-// Time-local variant for long time lines: a workgroup owns a contiguous chunk
-// of variables, finds the step range its events fall into and, when that
-// range fits the LDS bins, accumulates there; otherwise it adds to global
-// memory directly.
-__global__ __launch_bounds__(256) void k_delta_window(uint32_t n, uint32_t per_block, uint32_t lds_bins,
-                                                      const uint64_t *__restrict__ size,
-                                                      const uint32_t *__restrict__ alloc,
-                                                      const uint32_t *__restrict__ free_,
-                                                      unsigned long long *delta)
+// Time-local variant for long time lines: a workgroup owns 4096 consecutive variables, reads
+// them once (16-byte vector loads, kept in registers), finds the step range their events
+// fall into and, when that range fits the LDS bins, accumulates there and flushes the bins
+// with global atomics; otherwise it adds to global memory directly.
+constexpr int DW_THREADS = 256;
+constexpr int DW_GROUPS = 4;                       // groups of 4 variables per thread
+constexpr uint32_t DW_PER_BLOCK = DW_THREADS * DW_GROUPS * 4;
+
+__global__ __launch_bounds__(DW_THREADS) void k_delta_window(uint32_t n, uint32_t lds_bins,
+                                                             const uint64_t *__restrict__ size,
+                                                             const uint32_t *__restrict__ alloc,
+                                                             const uint32_t *__restrict__ free_,
+                                                             unsigned long long *delta)
 {
     extern __shared__ unsigned long long bins[];
     __shared__ uint32_t s_lo, s_hi;
-    const uint32_t begin = blockIdx.x * per_block;
-    const uint32_t end = min(n, begin + per_block);
+    const uint32_t begin = blockIdx.x * DW_PER_BLOCK;
     if (threadIdx.x == 0) { s_lo = 0xFFFFFFFFu; s_hi = 0; }
     __syncthreads();
+    uint64_t sz[DW_GROUPS][4];
+    uint32_t al[DW_GROUPS][4], fr[DW_GROUPS][4];
     uint32_t lo = 0xFFFFFFFFu, hi = 0;
-    for (uint32_t i = begin + threadIdx.x; i < end; i += blockDim.x) {
-        lo = min(lo, alloc[i]);
-        hi = max(hi, free_[i]);
+#pragma unroll
+    for (int g = 0; g < DW_GROUPS; ++g) {
+        const uint32_t i0 = begin + (g * DW_THREADS + threadIdx.x) * 4;
+        if (i0 + 3 < n) {
+            const ulonglong2 s01 = *(const ulonglong2 *)(size + i0);
+            const ulonglong2 s23 = *(const ulonglong2 *)(size + i0 + 2);
+            const uint4 a4 = *(const uint4 *)(alloc + i0);
+            const uint4 f4 = *(const uint4 *)(free_ + i0);
+            sz[g][0] = s01.x; sz[g][1] = s01.y; sz[g][2] = s23.x; sz[g][3] = s23.y;
+            al[g][0] = a4.x; al[g][1] = a4.y; al[g][2] = a4.z; al[g][3] = a4.w;
+            fr[g][0] = f4.x; fr[g][1] = f4.y; fr[g][2] = f4.z; fr[g][3] = f4.w;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool in = i0 + k < n;
+                sz[g][k] = in ? size[i0 + k] : 0;          // size 0 marks an empty slot
+                al[g][k] = in ? alloc[i0 + k] : 0;
+                fr[g][k] = in ? free_[i0 + k] : 0;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (sz[g][k]) { lo = min(lo, al[g][k]); hi = max(hi, fr[g][k]); }
     }
     for (int m = WAVE / 2; m > 0; m >>= 1) {
         lo = min(lo, (uint32_t)__shfl_xor(lo, m, WAVE));
@@ -70,28 +95,34 @@ __global__ __launch_bounds__(256) void k_delta_window(uint32_t n, uint32_t per_b
     if ((threadIdx.x & (WAVE - 1)) == 0) { atomicMin(&s_lo, lo); atomicMax(&s_hi, hi); }
     __syncthreads();
     lo = s_lo; hi = s_hi;
-    if (begin >= end) return;
+    if (lo > hi) return;                               // nothing in this block
     const bool local = (hi - lo + 1) <= lds_bins;
     if (local) {
         const uint32_t nb = hi - lo + 1;
         for (uint32_t i = threadIdx.x; i < nb; i += blockDim.x) bins[i] = 0;
         __syncthreads();
-        for (uint32_t i = begin + threadIdx.x; i < end; i += blockDim.x) {
-            const uint64_t s = size[i];
-            atomicAdd(&bins[alloc[i] - lo], (unsigned long long)s);
-            atomicAdd(&bins[free_[i] - lo], (unsigned long long)(0ull - s));
-        }
+#pragma unroll
+        for (int g = 0; g < DW_GROUPS; ++g)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (sz[g][k]) {
+                    atomicAdd(&bins[al[g][k] - lo], (unsigned long long)sz[g][k]);
+                    atomicAdd(&bins[fr[g][k] - lo], (unsigned long long)(0ull - sz[g][k]));
+                }
         __syncthreads();
         for (uint32_t i = threadIdx.x; i < nb; i += blockDim.x) {
             const unsigned long long v = bins[i];
             if (v) atomicAdd(&delta[lo + i], v);
         }
     } else {
-        for (uint32_t i = begin + threadIdx.x; i < end; i += blockDim.x) {
-            const uint64_t s = size[i];
-            atomicAdd(&delta[alloc[i]], (unsigned long long)s);
-            atomicAdd(&delta[free_[i]], (unsigned long long)(0ull - s));
-        }
+#pragma unroll
+        for (int g = 0; g < DW_GROUPS; ++g)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (sz[g][k]) {
+                    atomicAdd(&delta[al[g][k]], (unsigned long long)sz[g][k]);
+                    atomicAdd(&delta[fr[g][k]], (unsigned long long)(0ull - sz[g][k]));
+                }
     }
 }
 
@@ -222,10 +253,10 @@ hipError_t launch_delta(uint32_t n, uint32_t T, const uint64_t *size, const uint
         hipLaunchKernelGGL(k_delta_lds, dim3(blocks), dim3(256), nbins * sizeof(uint64_t), st, n, nbins, size, alloc,
                            free_, (unsigned long long *)delta);
     } else {
-        const uint32_t per_block = 16384;
-        const uint32_t blocks = (n + per_block - 1) / per_block;
-        hipLaunchKernelGGL(k_delta_window, dim3(blocks), dim3(256), LDS_BINS * sizeof(uint64_t), st, n, per_block,
-                           LDS_BINS, size, alloc, free_, (unsigned long long *)delta);
+        constexpr uint32_t WIN_BINS = 2048;        // 16 KiB of bins: several workgroups per CU
+        const uint32_t blocks = (n + DW_PER_BLOCK - 1) / DW_PER_BLOCK;
+        hipLaunchKernelGGL(k_delta_window, dim3(blocks), dim3(DW_THREADS), WIN_BINS * sizeof(uint64_t), st, n,
+                           WIN_BINS, size, alloc, free_, (unsigned long long *)delta);
     }
     return hipGetLastError();
 }
