@@ -45,6 +45,9 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(there is no CPU fallback)")
+    # torch brings its own HIP runtime: load it first so that liblap binds to the same one
+    # (two runtimes in one process do not both see the GPU)
+    import torch  # noqa: F401
     lib = C.CDLL(_LIB_PATH)
     lib.lap_workspace_bytes.restype = C.c_size_t
     lib.lap_workspace_bytes.argtypes = [C.c_int, C.c_uint32, C.c_uint32, C.c_uint32]

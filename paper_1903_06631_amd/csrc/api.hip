@@ -1,5 +1,6 @@
 // extern "C" entry points of liblap: argument checks, workspace carving, launches.
 #include <math.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <vector>
@@ -111,9 +112,14 @@ struct ProfScope {
     }
 };
 
-#define LAP_HIP(expr)                          \
-    do {                                       \
-        if ((expr) != hipSuccess) return LAP_E_HIP; \
+// a failing HIP call is reported on stderr (with the runtime's message) and as LAP_E_HIP
+#define LAP_HIP(expr)                                                                          \
+    do {                                                                                       \
+        const hipError_t lap_e_ = (expr);                                                      \
+        if (lap_e_ != hipSuccess) {                                                            \
+            fprintf(stderr, "liblap: %s failed: %s\n", #expr, hipGetErrorString(lap_e_));      \
+            return LAP_E_HIP;                                                                  \
+        }                                                                                      \
     } while (0)
 
 int load_profile_impl(const lap_trace *tr, uint64_t *load, uint64_t *peak, uint32_t *t_peak, uint64_t *delta,
