@@ -376,6 +376,31 @@ constexpr int COOP_U = 4;                    // chunks per wave in one cooperati
 constexpr int ROUND_CH = PW * COOP_U;        // chunks per round
 constexpr uint32_t NONE32 = 0xFFFFFFFFu;
 
+// Lowest offset >= P at which `s` granules are free with respect to the time-overlapping
+// entries of a short UNSORTED list: while some entry meets [P, P+s), move P to the highest
+// end among those that do.
+__device__ __forceinline__ uint32_t fit_unsorted(const uint64_t *oe, const uint64_t *life, uint32_t n, uint32_t P,
+                                                 uint32_t s, uint32_t a, uint32_t f)
+{
+    const int l = lane_id();
+    for (;;) {
+        uint32_t top = 0;
+        for (uint32_t base = 0; base < n; base += WAVE) {
+            const uint32_t idx = base + l;
+            if (idx < n) {
+                const uint64_t x = oe[idx], lf = life[idx];
+                const uint32_t o = (uint32_t)(x >> 32), e = (uint32_t)x;
+                const uint32_t ea = (uint32_t)(lf >> 32), ef = (uint32_t)lf;
+                if (ea < f && a < ef && e > P && o < P + s) top = max(top, e);   // P + s < 2^32
+            }
+        }
+        top = wave_scan_max32(top);
+        top = read_lane(top, WAVE - 1);
+        if (top == 0) return P;
+        P = top;
+    }
+}
+
 // Merge the sorted recent list (LDS, nr entries) and the sorted main list (global, nm
 // entries) into another global buffer, with all PW waves; chunk c of main belongs to wave
 // c % PW and chunks are independent.  A chunk moves its own entries up by the number of
@@ -682,16 +707,15 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 __syncthreads();
                 const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
                 const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
-                const uint32_t np = s_np;
-                __syncthreads();
-                flush(np, one_step ? a : NONE32);
+                const uint32_t np = s_np;         // pending stays unsorted: it is checked directly
                 PROBE_ACC(0, t2); PROBE_T(t3);
                 uint32_t o = 0, cm = 0, cr = 0;
                 for (;;) {
                     const uint32_t o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax, s_hq,
                                                    s_hans);
                     if (wave == 0) {
-                        const uint32_t o2 = nr ? sweep32<true>(r_oe, r_life, nr, cr, o1, vs, va, vf) : o1;
+                        uint32_t o2 = nr ? sweep32<true>(r_oe, r_life, nr, cr, o1, vs, va, vf) : o1;
+                        if (np) o2 = fit_unsorted(p_oe, p_life, np, o2, vs, va, vf);
                         if (l == 0) s_bc = o2;
                     }
                     __syncthreads();
