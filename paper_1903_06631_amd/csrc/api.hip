@@ -40,7 +40,7 @@ size_t ws_plan_lists(uint32_t n, uint32_t T, uint32_t B)
 {
     const size_t bn = (size_t)B * n;
     const size_t wide = 3 * up(bn * 8);
-    const size_t fast = 4 * up(bn * 8) + 2 * up((size_t)B * lap::PLAN_REC * 8) + up(bn * lap::PLAN_CL * 8) +
+    const size_t fast = 4 * up(bn * 8) + 4 * up((size_t)B * lap::PLAN_REC * 8) + up(bn * lap::PLAN_CL * 8) +
                         2 * up((size_t)B * T * 4);
     return wide > fast ? wide : fast;
 }
@@ -233,6 +233,8 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint64_t *f_life2 = cf.take<uint64_t>(bn);
     uint64_t *f_roe = cf.take<uint64_t>((size_t)B * lap::PLAN_REC);
     uint64_t *f_rlife = cf.take<uint64_t>((size_t)B * lap::PLAN_REC);
+    uint64_t *f_roe2 = cf.take<uint64_t>((size_t)B * lap::PLAN_REC);
+    uint64_t *f_rlife2 = cf.take<uint64_t>((size_t)B * lap::PLAN_REC);
     const uint64_t capL = (uint64_t)n * lap::PLAN_CL;
     uint64_t *f_L = cf.take<uint64_t>((size_t)B * capL);
     uint32_t *l_ns = cf.take<uint32_t>((size_t)B * T);
@@ -265,7 +267,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     {
         ProfScope p(LAP_K_PLACE, st);
         LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, hdr, lstart, f_oe, f_life, f_oe2,
-                                       f_life2, f_roe, f_rlife, f_L, capL, l_ns, l_nu, offs, fps, st));
+                                       f_life2, f_roe, f_rlife, f_roe2, f_rlife2, f_L, capL, l_ns, l_nu, offs, fps, st));
         LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, hdr, m_off, m_end, m_life, offs,
                                        fps, st));
     }

@@ -39,13 +39,20 @@ namespace lap {
 
 constexpr int PW = 4;               // waves per ordering
 constexpr uint32_t PEND = 512;      // pending (unsorted) entries in LDS
-constexpr uint32_t REC = PLAN_REC;  // recent (sorted) entries, global memory
+constexpr uint32_t REC = PLAN_REC;  // recent (sorted) entries per buffer, global memory
 constexpr uint32_t LH = 768;        // entries of a per-step list a wave can hold in LDS
 constexpr uint32_t CL = PLAN_CL;    // per-step lists need sum of lifetimes <= CL * N
 constexpr int UNROLL = 4;           // chunks loaded ahead by a sweep
 
 // orders this wave's earlier LDS / global accesses before its later ones (no barrier)
 __device__ __forceinline__ void wave_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
+
+// orders this wave's LDS accesses for the compiler; the LDS unit serves a wave in order
+__device__ __forceinline__ void lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
 __device__ __forceinline__ uint64_t pk(uint32_t off, uint32_t end) { return ((uint64_t)off << 32) | end; }
 
@@ -260,7 +267,7 @@ __device__ __forceinline__ void bitonic_sort(uint64_t *oe, uint64_t *life, uint3
                     life[lo] = v; life[hi] = u;
                 }
             }
-            wave_fence();
+            lds_sync();
         }
     }
 }
@@ -269,12 +276,6 @@ __device__ __forceinline__ void bitonic_sort(uint64_t *oe, uint64_t *life, uint3
 // a per-step hole list held in LDS by one wave (packed start << 32 | size, sorted by start)
 // ---------------------------------------------------------------------------
 
-// orders this wave's LDS accesses for the compiler; the LDS unit serves a wave in order
-__device__ __forceinline__ void lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
 
 // index of the first of the nh holes with size >= s (there always is one: the top hole)
 __device__ __forceinline__ uint32_t h_first_fit(const uint64_t *hl, uint32_t nh, uint32_t s)
@@ -363,7 +364,7 @@ struct FastArgs {
     const PlanHeader *hdr;
     const uint32_t *lstart;      // [T+1]
     uint64_t *m_oe[2], *m_life[2];  // [B][n] x 2  ALL main list, two buffers (merges ping-pong)
-    uint64_t *r_oe, *r_life;     // [B][REC]    ALL recent list
+    uint64_t *r_oe[2], *r_life[2];  // [B][REC] x 2  ALL recent list, two buffers
     uint64_t *L;                 // [B][capL]   per-step lists, packed blocks
     uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts
     uint64_t capL;
@@ -401,17 +402,62 @@ __device__ __forceinline__ uint32_t fit_unsorted(const uint64_t *oe, const uint6
     }
 }
 
-// Merge the sorted recent list (LDS, nr entries) and the sorted main list (global, nm
-// entries) into another global buffer, with all PW waves; chunk c of main belongs to wave
-// c % PW and chunks are independent.  A chunk moves its own entries up by the number of
-// recent entries below each, and writes the recent entries whose place is inside it (after
-// main entries of equal key).  No barrier inside; the caller synchronises before reading dst.
-__device__ __forceinline__ void coop_merge_main(const uint64_t *src_oe, const uint64_t *src_life, uint32_t nm,
-                                                const uint64_t *r_oe, const uint64_t *r_life, uint32_t nr,
-                                                uint64_t *dst_oe, uint64_t *dst_life, uint32_t wave)
+// Readers of the smaller list of a merge: entry j for a wave-uniform, mostly ascending j.
+struct LdsList {                 // the list sits in LDS
+    const uint64_t *oe, *life;
+    __device__ __forceinline__ uint64_t key(uint32_t j) { return oe[j]; }
+    __device__ __forceinline__ uint64_t lifev(uint32_t j) { return life[j]; }
+    // first index >= from (< n) whose key is not below `bound`
+    __device__ __forceinline__ uint32_t advance(uint32_t from, uint32_t n, uint64_t bound)
+    {
+        uint32_t lo = from, hi = n;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (oe[mid] < bound) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    }
+};
+struct GlobalWindow {            // the list sits in global memory: 64 entries at a time in registers
+    const uint64_t *oe, *life;
+    uint32_t n, base;
+    uint64_t w_oe, w_life;
+    __device__ __forceinline__ void load(uint32_t b)
+    {
+        base = b;
+        const uint32_t idx = b + lane_id();
+        w_oe = idx < n ? oe[idx] : U64_MAX;
+        w_life = idx < n ? life[idx] : 0;
+    }
+    __device__ __forceinline__ uint64_t key(uint32_t j)
+    {
+        if (j - base >= (uint32_t)WAVE) load(j & ~(uint32_t)(WAVE - 1));
+        return read_lane64(w_oe, (int)(j - base));
+    }
+    __device__ __forceinline__ uint64_t lifev(uint32_t j)
+    {
+        if (j - base >= (uint32_t)WAVE) load(j & ~(uint32_t)(WAVE - 1));
+        return read_lane64(w_life, (int)(j - base));
+    }
+    __device__ __forceinline__ uint32_t advance(uint32_t from, uint32_t cnt, uint64_t bound)
+    {
+        while (from < cnt && key(from) < bound) ++from;
+        return from;
+    }
+};
+
+// Merge a sorted small list (ns entries, read through `sm`) and a sorted big list (global,
+// nb entries) into another global buffer, with all PW waves; chunk c of the big list belongs
+// to wave c % PW and chunks are independent.  A chunk moves its own entries up by the number
+// of small-list entries below each, and writes the small-list entries whose place is inside
+// it (after big-list entries of equal key).  No barrier inside; the caller synchronises
+// before reading dst.
+template <class Small>
+__device__ __forceinline__ void coop_merge(const uint64_t *src_oe, const uint64_t *src_life, uint32_t nb, Small sm,
+                                           uint32_t ns, uint64_t *dst_oe, uint64_t *dst_life, uint32_t wave)
 {
     const int l = lane_id();
-    const uint32_t nch = nm ? (nm + WAVE - 1) / WAVE : 1;
+    const uint32_t nch = nb ? (nb + WAVE - 1) / WAVE : 1;
     uint32_t jp = 0;
     for (uint32_t c0 = wave; c0 < nch; c0 += 2 * PW) {
         uint64_t key[2], lf[2], prevlast[2];
@@ -421,7 +467,7 @@ __device__ __forceinline__ void coop_merge_main(const uint64_t *src_oe, const ui
             const uint32_t idx = c * WAVE + l;
             key[u] = U64_MAX; lf[u] = 0; prevlast[u] = 0;
             if (c < nch) {
-                if (idx < nm) { key[u] = src_oe[idx]; lf[u] = src_life[idx]; }
+                if (idx < nb) { key[u] = src_oe[idx]; lf[u] = src_life[idx]; }
                 if (c) prevlast[u] = src_oe[c * WAVE - 1];
             }
         }
@@ -430,18 +476,19 @@ __device__ __forceinline__ void coop_merge_main(const uint64_t *src_oe, const ui
             const uint32_t c = c0 + u * PW;
             if (c < nch) {
                 const uint32_t idx = c * WAVE + l;
-                const bool valid = idx < nm;
+                const bool valid = idx < nb;
                 const bool last = c == nch - 1;
                 const uint64_t lastkey = read_lane64(key[u], WAVE - 1);
-                while (jp < nr && r_oe[jp] < prevlast[u]) ++jp;
+                jp = sm.advance(jp, ns, prevlast[u]);
                 uint32_t sh = jp, j = jp;
-                while (j < nr) {
-                    const uint64_t rk = r_oe[j];
+                while (j < ns) {
+                    const uint64_t rk = sm.key(j);
                     if (!last && !(rk < lastkey)) break;
+                    const uint64_t rl = sm.lifev(j);
                     const uint32_t below = (uint32_t)__popcll(ballot(valid && key[u] <= rk));
                     if (l == 0) {
                         dst_oe[c * WAVE + below + j] = rk;
-                        dst_life[c * WAVE + below + j] = r_life[j];
+                        dst_life[c * WAVE + below + j] = rl;
                     }
                     sh += (valid && rk < key[u]) ? 1u : 0u;
                     ++j;
@@ -450,51 +497,6 @@ __device__ __forceinline__ void coop_merge_main(const uint64_t *src_oe, const ui
             }
         }
     }
-}
-
-// Merge a sorted source list (ns entries) into a sorted destination list (nd entries,
-// capacity >= nd + ns), both in LDS, in place, one wave.  Equal keys: destination first.
-__device__ __forceinline__ void merge_lds(uint64_t *d_oe, uint64_t *d_life, uint32_t nd, const uint64_t *s_oe,
-                                          const uint64_t *s_life, uint32_t ns, uint32_t *pos)
-{
-    const int l = lane_id();
-    for (uint32_t j = l; j < ns; j += WAVE) {
-        const uint64_t key = s_oe[j];
-        uint32_t lo = 0, hi = nd;
-        while (lo < hi) {
-            const uint32_t mid = (lo + hi) >> 1;
-            if (d_oe[mid] <= key) lo = mid + 1; else hi = mid;
-        }
-        pos[j] = lo + j;
-    }
-    wave_fence();
-    uint32_t hi = nd;
-    while (hi > 0) {
-        const uint32_t lo = hi > (uint32_t)WAVE ? hi - WAVE : 0;
-        const uint32_t idx = lo + l;
-        const bool act = idx < hi;
-        uint64_t y = 0, z = 0;
-        uint32_t sh = 0;
-        if (act) {
-            y = d_oe[idx]; z = d_life[idx];
-            uint32_t a = 0, b = ns;
-            while (a < b) {
-                const uint32_t mid = (a + b) >> 1;
-                if (s_oe[mid] < y) a = mid + 1; else b = mid;
-            }
-            sh = a;
-        }
-        wave_fence();                         // every lane has read its entry
-        if (act && sh) { d_oe[idx + sh] = y; d_life[idx + sh] = z; }
-        if (ballot(act && sh) == 0) break;    // sorted: nothing below moves either
-        hi = lo;
-    }
-    wave_fence();
-    for (uint32_t j = l; j < ns; j += WAVE) {
-        const uint32_t q = pos[j];
-        d_oe[q] = s_oe[j]; d_life[q] = s_life[j];
-    }
-    wave_fence();
 }
 
 // sweep32 over a long global list with all PW waves: chunk q of a round belongs to wave
@@ -575,12 +577,10 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_
 __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
     __shared__ uint64_t p_oe[PEND], p_life[PEND];
-    __shared__ uint64_t s_h[PW][LH];         // per-wave hole list; staging area for main merges
-    static_assert(REC * 2 <= PW * LH, "the recent list is staged in the hole-list area");
+    __shared__ uint64_t s_h[PW][LH];         // per-wave hole list
     __shared__ uint32_t s_np, s_bc;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
-    __shared__ uint32_t s_pos[PEND];
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
     const bool mode1 = A.hdr->mode1 != 0;
@@ -593,8 +593,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     const uint32_t *perm = A.perm + (size_t)b * n;
     uint64_t *m_oe[2] = {A.m_oe[0] + (size_t)b * n, A.m_oe[1] + (size_t)b * n};
     uint64_t *m_life[2] = {A.m_life[0] + (size_t)b * n, A.m_life[1] + (size_t)b * n};
-    uint64_t *r_oe = A.r_oe + (size_t)b * REC;
-    uint64_t *r_life = A.r_life + (size_t)b * REC;
+    uint64_t *r_oe[2] = {A.r_oe[0] + (size_t)b * REC, A.r_oe[1] + (size_t)b * REC};
+    uint64_t *r_life[2] = {A.r_life[0] + (size_t)b * REC, A.r_life[1] + (size_t)b * REC};
     uint64_t *hl = s_h[wave];
     uint64_t *L = A.L + (size_t)b * A.capL;
     uint32_t *l_ns = A.l_ns + (size_t)b * T;
@@ -603,8 +603,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 
     // variables that will still query ALL: every one when there are no per-step lists
     uint32_t multi_left = mode1 ? A.hdr->n_multi : n;
-    // ALL list state, identical in every wave: main buffer in use, main / recent counts
-    uint32_t mb = 0, nm = 0, nr = 0;
+    // ALL list state, identical in every wave: main / recent buffer in use, their counts
+    uint32_t mb = 0, rb = 0, nm = 0, nr = 0;
+    uint32_t np_multi = 0;      // pending entries that came from ALL queries (they tend to stack)
     uint32_t fp = 0;
     if (threadIdx.x == 0) s_np = 0;
     if (mode1) {
@@ -637,37 +638,31 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         wb_to = 0;
     };
 
-    // recent is full or cannot take `incoming` more entries: merge it into main (all waves)
-    auto make_room = [&](uint32_t incoming, uint32_t a_lane) {
-        if (nr + incoming > REC) {
-            // the hole-list area becomes the staging copy of recent: give the lists back first
-            if (cur_t != NONE32) { writeback(a_lane); cur_t = NONE32; }
-            __syncthreads();
-            uint64_t *st_oe = &s_h[0][0], *st_life = st_oe + REC;
-            for (uint32_t i = threadIdx.x; i < nr; i += PW * WAVE) { st_oe[i] = r_oe[i]; st_life[i] = r_life[i]; }
-            __syncthreads();
-            coop_merge_main(m_oe[mb], m_life[mb], nm, st_oe, st_life, nr, m_oe[mb ^ 1], m_life[mb ^ 1], wave);
+    // pending -> recent, and recent -> main when recent cannot take it (all waves call it)
+    auto flush = [&](uint32_t np) {
+        if (np == 0) return;
+        if (nr + np > REC) {
+            GlobalWindow gw{r_oe[rb], r_life[rb], nr, 0, 0, 0};
+            gw.load(0);
+            coop_merge(m_oe[mb], m_life[mb], nm, gw, nr, m_oe[mb ^ 1], m_life[mb ^ 1], wave);
             mb ^= 1;
             nm += nr;
             nr = 0;
             __syncthreads();
         }
-    };
-
-    // pending -> recent (all waves call it; wave 0 sorts and merges in LDS)
-    auto flush = [&](uint32_t np, uint32_t a_lane) {
-        if (np == 0) return;
-        make_room(np, a_lane);
         if (wave == 0) {
             uint32_t m = WAVE;
             while (m < np) m <<= 1;
             for (uint32_t i = np + l; i < m; i += WAVE) { p_oe[i] = U64_MAX; p_life[i] = 0; }
             wave_fence();
             bitonic_sort(p_oe, p_life, m);
-            merge_lds(r_oe, r_life, nr, p_oe, p_life, np, s_pos);
             if (l == 0) s_np = 0;
         }
+        __syncthreads();
+        coop_merge(r_oe[rb], r_life[rb], nr, LdsList{p_oe, p_life}, np, r_oe[rb ^ 1], r_life[rb ^ 1], wave);
+        rb ^= 1;
         nr += np;
+        np_multi = 0;
         __syncthreads();
     };
 
@@ -707,14 +702,22 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 __syncthreads();
                 const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
                 const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
-                const uint32_t np = s_np;         // pending stays unsorted: it is checked directly
+                // pending stays unsorted and is checked directly, unless many of its entries come
+                // from ALL queries: those stack on each other and would be climbed one by one
+                uint32_t np = s_np;
+                if (np_multi >= 32) {
+                    __syncthreads();
+                    flush(np);
+                    np = 0;
+                }
                 PROBE_ACC(0, t2); PROBE_T(t3);
                 uint32_t o = 0, cm = 0, cr = 0;
                 for (;;) {
                     const uint32_t o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax, s_hq,
                                                    s_hans);
+                    uint32_t o2 = o1;
+                    if (nr) o2 = coop_sweep(r_oe[rb], r_life[rb], nr, cr, o1, vs, va, vf, wave, s_cmax, s_hq, s_hans);
                     if (wave == 0) {
-                        uint32_t o2 = nr ? sweep32<true>(r_oe, r_life, nr, cr, o1, vs, va, vf) : o1;
                         if (np) o2 = fit_unsorted(p_oe, p_life, np, o2, vs, va, vf);
                         if (l == 0) s_bc = o2;
                     }
@@ -725,16 +728,15 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 PROBE_ACC(1, t3); PROBE_T(t4);
                 const uint32_t en = o + vs;
                 fp = max(fp, en);
-                if (threadIdx.x == 0) offs[vv] = (uint64_t)o << sh;
-                if (multi_left > 1) {                   // someone will still query ALL
-                    make_room(1, NONE32);
-                    if (wave == 0) {
-                        const uint64_t x = pk(o, en);
-                        const uint32_t ip = count_below32(r_oe, nr, x);
-                        insert_at32(r_oe, r_life, nr, ip, x, ((uint64_t)va << 32) | vf);
+                if (threadIdx.x == 0) {
+                    offs[vv] = (uint64_t)o << sh;
+                    if (multi_left > 1) {               // someone will still query ALL
+                        p_oe[np] = pk(o, en);
+                        p_life[np] = ((uint64_t)va << 32) | vf;
+                        s_np = np + 1;
                     }
-                    ++nr;
                 }
+                if (multi_left > 1) ++np_multi;
                 if (mode1) {
                     const uint64_t x = pk(o, en);
                     for (uint32_t t = va + wave * WAVE + l; t < vf; t += PW * WAVE) {
@@ -844,7 +846,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         const uint32_t np_now = s_np;
         __syncthreads();
         PROBE_T(t6);
-        if (np_now + WAVE > PEND) flush(np_now, NONE32);
+        if (np_now + WAVE > PEND) flush(np_now);
         PROBE_ACC(4, t6);
     }
 #ifdef LAP_PROBE
@@ -877,10 +879,12 @@ hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const 
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
-                             uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *L, uint64_t capL,
+                             uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
+                             uint64_t *r_life2, uint64_t *L, uint64_t capL,
                              uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st)
 {
-    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, r_oe, r_life, L, l_ns,
+    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, {r_oe, r_oe2}, {r_life, r_life2},
+               L, l_ns,
                l_nu, capL,
                offs, fps, g_probe};
     hipLaunchKernelGGL(k_place_fast, dim3(B), dim3(PW * WAVE), 0, st, A);
