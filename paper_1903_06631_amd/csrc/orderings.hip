@@ -1,7 +1,7 @@
 // Placement orders (Section III-C sorts by size, largest first; the other
 // kinds are the extra heuristic orders evaluated in parallel).
 //
-// One wave per ordering produces perm[b][rank] = variable index: a stable
+// One workgroup per ordering produces perm[b][rank] = variable index: a stable
 // least-significant-digit radix sort (8-bit digits) of the indices 0..N-1 by a
 // 64-bit key.  The key is a pure function of (ordering, index) and is
 // recomputed from the trace on every pass, so only the 4-byte indices move.
@@ -27,16 +27,30 @@ __device__ __forceinline__ uint64_t order_key(uint32_t kind, uint64_t seed, uint
     }
 }
 
-__global__ __launch_bounds__(64) void k_sort_perm(uint32_t n, const uint64_t *__restrict__ size,
-                                                  const uint32_t *__restrict__ alloc,
-                                                  const uint32_t *__restrict__ free_,
-                                                  const uint32_t *__restrict__ kinds,
-                                                  const uint64_t *__restrict__ seeds,
-                                                  uint32_t *perm_all, uint32_t *tmp_all)
+constexpr int SW = 4;                    // waves per ordering
+
+__device__ __forceinline__ void wave_lds_sync()
 {
-    __shared__ uint32_t hist[256];
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Wave w sorts the contiguous quarter [w*n/4, (w+1)*n/4) of the rank array: it counts its own
+// digits, the workgroup turns the 4 x 256 counts into per-wave output positions (digit-major,
+// wave-minor, which keeps the sort stable), and each wave scatters its quarter tile by tile
+// with its private positions -- no workgroup barrier inside the scatter loop.
+__global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64_t *__restrict__ size,
+                                                        const uint32_t *__restrict__ alloc,
+                                                        const uint32_t *__restrict__ free_,
+                                                        const uint32_t *__restrict__ kinds,
+                                                        const uint64_t *__restrict__ seeds,
+                                                        uint32_t *perm_all, uint32_t *tmp_all)
+{
+    __shared__ uint32_t hist[SW][256];
+    __shared__ uint32_t s_skip;
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
+    const uint32_t w = threadIdx.x / WAVE;
     const uint32_t kind = kinds[b];
     const uint64_t seed = seeds[b];
     uint32_t *perm = perm_all + (size_t)b * n;
@@ -46,49 +60,60 @@ __global__ __launch_bounds__(64) void k_sort_perm(uint32_t n, const uint64_t *__
         // caller-supplied permutation: copy.  Indices are clamped so that a malformed
         // array can never cause an out-of-range access downstream.
         const uint32_t *src = (const uint32_t *)(uintptr_t)seed;
-        for (uint32_t i = l; i < n; i += WAVE) perm[i] = min(src[i], n - 1);
+        for (uint32_t i = threadIdx.x; i < n; i += SW * WAVE) perm[i] = min(src[i], n - 1);
         return;
     }
 
+    const uint32_t seg = (n + SW - 1) / SW;
+    const uint32_t lo = min(n, w * seg), hi = min(n, lo + seg);
     // cur == nullptr means the identity (no buffer read yet)
     const uint32_t *cur = nullptr;
     uint32_t *dst = perm;
     const uint64_t lt_mask = (1ull << l) - 1ull;
     for (int pass = 0; pass < 8; ++pass) {
         const int shift = pass * 8;
-        for (int k = l; k < 256; k += WAVE) hist[k] = 0;
-        __syncthreads();
-        for (uint32_t base = 0; base < n; base += WAVE) {
+        for (int k = l; k < 256; k += WAVE) hist[w][k] = 0;
+        wave_lds_sync();
+        for (uint32_t base = lo; base < hi; base += WAVE) {
             const uint32_t r = base + l;
-            if (r < n) {
+            if (r < hi) {
                 const uint32_t i = cur ? cur[r] : r;
                 const uint32_t d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
-                atomicAdd(&hist[d], 1u);
+                atomicAdd(&hist[w][d], 1u);
             }
         }
         __syncthreads();
-        // exclusive scan of the 256 counts (4 per lane), and detection of a constant digit
-        uint32_t c[4], s = 0;
-        bool all_in_one = false;
+        // thread t owns digit t: its total over the waves, an exclusive scan over the digits,
+        // then the start of every wave's share
+        {
+            const uint32_t d = threadIdx.x;
+            uint32_t c[SW], tot = 0;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { c[k] = hist[l * 4 + k]; s += c[k]; all_in_one |= (c[k] == n); }
-        const bool skip = ballot(all_in_one) != 0;
-        uint32_t incl = s;
+            for (int k = 0; k < SW; ++k) { c[k] = hist[k][d]; tot += c[k]; }
+            if (d == 0) s_skip = 0;
+            __syncthreads();
+            if (tot == n) s_skip = 1;                 // every key has this digit: nothing moves
+            // exclusive scan of tot over 256 threads: wave scan + wave totals through hist[0]
+            uint32_t incl = tot;
 #pragma unroll
-        for (int dlt = 1; dlt < WAVE; dlt <<= 1) {
-            const uint32_t t = __shfl_up(incl, dlt, WAVE);
-            if (l >= dlt) incl += t;
+            for (int dlt = 1; dlt < WAVE; dlt <<= 1) {
+                const uint32_t t = __shfl_up(incl, dlt, WAVE);
+                if (l >= dlt) incl += t;
+            }
+            __shared__ uint32_t wtot[SW];
+            if (l == WAVE - 1) wtot[w] = incl;
+            __syncthreads();
+            uint32_t run = incl - tot;
+            for (uint32_t k = 0; k < w; ++k) run += wtot[k];
+#pragma unroll
+            for (int k = 0; k < SW; ++k) { hist[k][d] = run; run += c[k]; }
         }
-        uint32_t run = incl - s;
         __syncthreads();
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { hist[l * 4 + k] = run; run += c[k]; }
-        __syncthreads();
-        if (skip) continue;
-        // stable scatter, one tile of 64 ranks at a time
-        for (uint32_t base = 0; base < n; base += WAVE) {
+        if (s_skip) { __syncthreads(); continue; }
+        // stable scatter of this wave's quarter, one tile of 64 ranks at a time
+        for (uint32_t base = lo; base < hi; base += WAVE) {
             const uint32_t r = base + l;
-            const bool act = r < n;
+            const bool act = r < hi;
             uint32_t i = 0, d = 0;
             if (act) {
                 i = cur ? cur[r] : r;
@@ -103,10 +128,10 @@ __global__ __launch_bounds__(64) void k_sort_perm(uint32_t n, const uint64_t *__
             const uint32_t rank = (uint32_t)__popcll(same & lt_mask);
             const uint32_t cnt = (uint32_t)__popcll(same);
             uint32_t pos = 0;
-            if (act) pos = hist[d] + rank;
-            __syncthreads();
-            if (act && rank == 0) hist[d] += cnt;
-            __syncthreads();
+            if (act) pos = hist[w][d] + rank;
+            wave_lds_sync();
+            if (act && rank == 0) hist[w][d] += cnt;
+            wave_lds_sync();
             if (act) dst[pos] = i;
         }
         __syncthreads();
@@ -114,9 +139,9 @@ __global__ __launch_bounds__(64) void k_sort_perm(uint32_t n, const uint64_t *__
         dst = (dst == perm) ? tmp : perm;
     }
     if (cur == nullptr) {
-        for (uint32_t i = l; i < n; i += WAVE) perm[i] = i;
+        for (uint32_t i = threadIdx.x; i < n; i += SW * WAVE) perm[i] = i;
     } else if (cur != perm) {
-        for (uint32_t i = l; i < n; i += WAVE) perm[i] = tmp[i];
+        for (uint32_t i = threadIdx.x; i < n; i += SW * WAVE) perm[i] = tmp[i];
     }
 }
 
@@ -124,7 +149,7 @@ hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const 
                             const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
                             hipStream_t st)
 {
-    hipLaunchKernelGGL(k_sort_perm, dim3(B), dim3(WAVE), 0, st, n, size, alloc, free_, kinds, seeds, perm, tmp);
+    hipLaunchKernelGGL(k_sort_perm, dim3(B), dim3(SW * WAVE), 0, st, n, size, alloc, free_, kinds, seeds, perm, tmp);
     return hipGetLastError();
 }
 
