@@ -85,7 +85,8 @@ typedef struct {
  *   ALLOC_ASC   arrival order, what an online pool would see
  *   SEEDED      ascending splitmix64 output of (seed + (i+1) * 0x9E3779B97F4A7C15)
  *   EXPLICIT    seed holds a device pointer to a u32[N] permutation
- *               (placement rank -> variable index); it must be a permutation */
+ *               (placement rank -> variable index).  An array that is not a
+ *               permutation of 0..N-1 is replaced by the identity order. */
 enum {
     LAP_ORD_SIZE_DESC = 0,
     LAP_ORD_LIFE_DESC = 1,

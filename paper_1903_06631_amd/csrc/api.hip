@@ -202,7 +202,9 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     if (rc) return rc;
     if (!ords || !best_offsets || !best_footprint || !best_ordering) return LAP_E_NULL;
     if (B == 0) return LAP_E_SIZE;
+    bool any_explicit = false;
     for (uint32_t b = 0; b < B; ++b) {
+        any_explicit |= ords[b].kind == LAP_ORD_EXPLICIT;
         if (ords[b].kind > LAP_ORD_EXPLICIT) return LAP_E_ORDERING;
         if (ords[b].kind == LAP_ORD_EXPLICIT && ords[b].seed == 0) return LAP_E_ORDERING;
     }
@@ -255,7 +257,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint64_t *offs = all_offsets ? all_offsets : offs_ws;
     {
         ProfScope p(LAP_K_SORT, st);
-        LAP_HIP(lap::launch_sort_perm(n, B, tr->size, tr->alloc, tr->free_, kinds, seeds, perm, tmp, st));
+        LAP_HIP(lap::launch_sort_perm(n, B, tr->size, tr->alloc, tr->free_, kinds, seeds, perm, tmp, any_explicit, st));
     }
     static_assert(sizeof(lap::PlanHeader) % 8 == 0, "header is cleared in 64-bit words");
     LAP_HIP(lap::launch_fill_u64((uint64_t *)hdr, sizeof(lap::PlanHeader) / 8, 0, st));

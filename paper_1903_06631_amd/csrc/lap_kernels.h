@@ -27,7 +27,7 @@ hipError_t launch_validate(uint32_t n, uint32_t T, const uint64_t *size, const u
 
 hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                             const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
-                            hipStream_t st);
+                            bool any_explicit, hipStream_t st);
 hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
                             const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st);
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,

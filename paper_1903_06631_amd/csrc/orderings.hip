@@ -145,11 +145,41 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     }
 }
 
+// A caller-supplied order must be a permutation of 0..N-1.  One that is not (an index out of
+// range, or one used twice) is replaced by the identity order, so that every variable is
+// still placed exactly once.  tmp is free after the sort and serves as the "seen" marks.
+__global__ __launch_bounds__(256) void k_sanitize_explicit(uint32_t n, const uint32_t *__restrict__ kinds,
+                                                           const uint64_t *__restrict__ seeds, uint32_t *perm_all,
+                                                           uint32_t *tmp_all)
+{
+    const uint32_t b = blockIdx.x;
+    if (kinds[b] != 5) return;
+    __shared__ uint32_t s_bad;
+    const uint32_t *src = (const uint32_t *)(uintptr_t)seeds[b];
+    uint32_t *perm = perm_all + (size_t)b * n;
+    uint32_t *seen = tmp_all + (size_t)b * n;
+    if (threadIdx.x == 0) s_bad = 0;
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) seen[i] = 0;
+    __syncthreads();
+    bool bad = false;
+    for (uint32_t r = threadIdx.x; r < n; r += blockDim.x) {
+        const uint32_t v = src[r];
+        if (v >= n) bad = true;
+        else if (atomicAdd(&seen[v], 1u) != 0) bad = true;
+    }
+    if (bad) s_bad = 1;
+    __syncthreads();
+    if (s_bad)
+        for (uint32_t r = threadIdx.x; r < n; r += blockDim.x) perm[r] = r;
+}
+
 hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                             const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
-                            hipStream_t st)
+                            bool any_explicit, hipStream_t st)
 {
     hipLaunchKernelGGL(k_sort_perm, dim3(B), dim3(SW * WAVE), 0, st, n, size, alloc, free_, kinds, seeds, perm, tmp);
+    if (any_explicit)
+        hipLaunchKernelGGL(k_sanitize_explicit, dim3(B), dim3(256), 0, st, n, kinds, seeds, perm, tmp);
     return hipGetLastError();
 }
 

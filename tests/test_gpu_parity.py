@@ -131,6 +131,27 @@ def test_plan_pool_explicit_permutations(lap, oracle_mod):
     _check_plan(lap, oracle_mod, tr, kinds, seeds, explicit_np=explicit)
 
 
+def test_plan_pool_malformed_explicit_is_identity(lap, oracle_mod):
+    import torch
+    tr = random_trace(8, 500, 15, size_choices=[1, 2, 3, 4], one_step_frac=0.9, max_life=4)
+    bad1 = np.arange(500, dtype=np.uint32); bad1[7] = 9            # index 9 twice, 7 missing
+    bad2 = np.arange(500, dtype=np.uint32)[::-1].copy(); bad2[0] = 1 << 30   # out of range
+    dt = lap.DeviceTrace(tr)
+    ex = {b: torch.from_numpy(p.view(np.int32)).to(dt.device) for b, p in {0: bad1, 1: bad2}.items()}
+    got = lap.plan_pool(dt, [5, 5, 0], [0, 0, 0], explicit=ex)
+    ident = oracle_mod.place(tr, np.arange(500, dtype=np.uint32))
+    for b in (0, 1):
+        assert np.array_equal(u64(got["all_offsets"])[b], ident[0]) and u64(got["footprints"])[b] == ident[1]
+
+
+@pytest.mark.parametrize("n,T,B", [(64, 9, 1), (128, 3, 3), (9000, 60, 12), (50, 100000, 4)])
+def test_plan_pool_shapes(lap, oracle_mod, n, T, B):
+    """Window-sized inputs, a single ordering, more than one 4096-entry merge, a very long time line."""
+    tr = random_trace(n + T, n, T, size_choices=[1, 2, 3, 5, 8, 300])
+    kinds, seeds = make_orderings(max(B, 5))
+    _check_plan(lap, oracle_mod, tr, kinds[-B:], seeds[-B:])
+
+
 def test_plan_pool_special_cases(lap, oracle_mod):
     kinds, seeds = make_orderings(8)
     # identical lifetimes: blocks stack, footprint = sum of sizes
