@@ -758,6 +758,12 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 const uint32_t run = (~rest == 0ull) ? 64u : (uint32_t)(__ffsll((unsigned long long)~rest) - 1);
                 const uint32_t q = p + run;
                 uint64_t mine = ballot((uint32_t)l >= p && (uint32_t)l < q && (a % PW) == wave);
+                // the list of the NEXT variable of this wave is fetched into registers while the
+                // current one is being placed
+                uint64_t pf[LH / WAVE];
+                uint32_t pf_t = NONE32;
+#pragma unroll
+                for (int c = 0; c < (int)(LH / WAVE); ++c) pf[c] = 0;
                 while (mine) {
                     const int j = __ffsll((unsigned long long)mine) - 1;
                     mine &= mine - 1;
@@ -769,10 +775,18 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         cur_t = NONE32;
                         const uint32_t base = read_lane(plb, j);
                         const uint32_t ns = read_lane(pns, j), nu = read_lane(pnu, j), tot = ns + nu;
-                        if (wmask & (1ull << ((t / PW) & 63))) { wave_fence(); wmask = 0; }
+                        if (pf_t != t && (wmask & (1ull << ((t / PW) & 63)))) { wave_fence(); wmask = 0; }
                         if (tot + 1 <= LH) {
-                            const uint64_t *Lt = L + base;
-                            for (uint32_t idx = l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
+                            if (pf_t == t) {
+#pragma unroll
+                                for (int c = 0; c < (int)(LH / WAVE); ++c) {
+                                    const uint32_t idx = c * WAVE + l;
+                                    if ((uint32_t)c * WAVE < tot && idx < tot) hl[idx] = pf[c];
+                                }
+                            } else {
+                                const uint64_t *Lt = L + base;
+                                for (uint32_t idx = l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
+                            }
                             lds_sync();
                             PROBE_CNT(6, tot - ns);
                             // carve the multi-step blocks that arrived since out of the holes, last
@@ -784,6 +798,21 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                             }
                             cur_t = t;
                             cnt = nh;
+                        }
+                    }
+                    pf_t = NONE32;
+                    if (mine) {
+                        const int jn = __ffsll((unsigned long long)mine) - 1;
+                        const uint32_t tn = read_lane(a, jn);
+                        const uint32_t totn = read_lane(pns, jn) + read_lane(pnu, jn);
+                        if (tn != t && totn + 1 <= LH && !(wmask & (1ull << ((tn / PW) & 63)))) {
+                            const uint64_t *Ln = L + read_lane(plb, jn);
+#pragma unroll
+                            for (int c = 0; c < (int)(LH / WAVE); ++c) {
+                                const uint32_t idx = c * WAVE + l;
+                                pf[c] = ((uint32_t)c * WAVE < totn && idx < totn) ? Ln[idx] : 0ull;
+                            }
+                            pf_t = tn;
                         }
                     }
                     if (cur_t == t) {
