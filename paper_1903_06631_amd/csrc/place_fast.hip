@@ -56,6 +56,22 @@ __device__ __forceinline__ void lds_sync()
 
 __device__ __forceinline__ uint64_t pk(uint32_t off, uint32_t end) { return ((uint64_t)off << 32) | end; }
 
+// A block's lifetime [alloc, free) next to its packed addresses: 64 bits in general, 32 bits
+// (16 + 16) when the time line has at most 65535 steps -- a quarter less list traffic.
+template <class LT> struct Life;
+template <> struct Life<uint64_t> {
+    static __device__ __forceinline__ uint64_t mk(uint32_t a, uint32_t f) { return ((uint64_t)a << 32) | f; }
+    static __device__ __forceinline__ uint32_t a(uint64_t lf) { return (uint32_t)(lf >> 32); }
+    static __device__ __forceinline__ uint32_t f(uint64_t lf) { return (uint32_t)lf; }
+    static __device__ __forceinline__ uint64_t lane(uint64_t v, int l) { return read_lane64(v, l); }
+};
+template <> struct Life<uint32_t> {
+    static __device__ __forceinline__ uint32_t mk(uint32_t a, uint32_t f) { return (a << 16) | f; }
+    static __device__ __forceinline__ uint32_t a(uint32_t lf) { return lf >> 16; }
+    static __device__ __forceinline__ uint32_t f(uint32_t lf) { return lf & 0xFFFFu; }
+    static __device__ __forceinline__ uint32_t lane(uint32_t v, int l) { return read_lane(v, l); }
+};
+
 __device__ __forceinline__ uint32_t wave_scan_max32(uint32_t v) { return wave_scan_max_u32(v); }
 
 // ---------------------------------------------------------------------------
@@ -251,7 +267,8 @@ __device__ __forceinline__ uint32_t mem_find_hole(const uint64_t *Lt, uint32_t n
 }
 
 // bitonic sort of m (power of two, >= 64) packed entries with their lifetimes, in LDS, one wave
-__device__ __forceinline__ void bitonic_sort(uint64_t *oe, uint64_t *life, uint32_t m)
+template <class LT>
+__device__ __forceinline__ void bitonic_sort(uint64_t *oe, LT *life, uint32_t m)
 {
     const int l = lane_id();
     for (uint32_t k = 2; k <= m; k <<= 1) {
@@ -263,7 +280,7 @@ __device__ __forceinline__ void bitonic_sort(uint64_t *oe, uint64_t *life, uint3
                 const uint64_t x = oe[lo], y = oe[hi];
                 if ((x > y) == up) {
                     oe[lo] = y; oe[hi] = x;
-                    const uint64_t u = life[lo], v = life[hi];
+                    const LT u = life[lo], v = life[hi];
                     life[lo] = v; life[hi] = u;
                 }
             }
@@ -363,8 +380,10 @@ struct FastArgs {
     const uint32_t *perm;        // [B][n]
     const PlanHeader *hdr;
     const uint32_t *lstart;      // [T+1]
-    uint64_t *m_oe[2], *m_life[2];  // [B][n] x 2  ALL main list, two buffers (merges ping-pong)
-    uint64_t *r_oe[2], *r_life[2];  // [B][REC] x 2  ALL recent list, two buffers
+    uint64_t *m_oe[2];           // [B][n] x 2  ALL main list, two buffers (merges ping-pong)
+    void *m_life[2];             //             lifetimes of its entries (32- or 64-bit words)
+    uint64_t *r_oe[2];           // [B][REC] x 2  ALL recent list, two buffers
+    void *r_life[2];
     uint64_t *L;                 // [B][capL]   per-step lists, packed blocks
     uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts
     uint64_t capL;
@@ -380,7 +399,8 @@ constexpr uint32_t NONE32 = 0xFFFFFFFFu;
 // Lowest offset >= P at which `s` granules are free with respect to the time-overlapping
 // entries of a short UNSORTED list: while some entry meets [P, P+s), move P to the highest
 // end among those that do.
-__device__ __forceinline__ uint32_t fit_unsorted(const uint64_t *oe, const uint64_t *life, uint32_t n, uint32_t P,
+template <class LT>
+__device__ __forceinline__ uint32_t fit_unsorted(const uint64_t *oe, const LT *life, uint32_t n, uint32_t P,
                                                  uint32_t s, uint32_t a, uint32_t f)
 {
     const int l = lane_id();
@@ -389,9 +409,10 @@ __device__ __forceinline__ uint32_t fit_unsorted(const uint64_t *oe, const uint6
         for (uint32_t base = 0; base < n; base += WAVE) {
             const uint32_t idx = base + l;
             if (idx < n) {
-                const uint64_t x = oe[idx], lf = life[idx];
+                const uint64_t x = oe[idx];
+                const LT lf = life[idx];
                 const uint32_t o = (uint32_t)(x >> 32), e = (uint32_t)x;
-                const uint32_t ea = (uint32_t)(lf >> 32), ef = (uint32_t)lf;
+                const uint32_t ea = Life<LT>::a(lf), ef = Life<LT>::f(lf);
                 if (ea < f && a < ef && e > P && o < P + s) top = max(top, e);   // P + s < 2^32
             }
         }
@@ -403,10 +424,11 @@ __device__ __forceinline__ uint32_t fit_unsorted(const uint64_t *oe, const uint6
 }
 
 // Readers of the smaller list of a merge: entry j for a wave-uniform, mostly ascending j.
-struct LdsList {                 // the list sits in LDS
-    const uint64_t *oe, *life;
+template <class LT> struct LdsList {                 // the list sits in LDS
+    const uint64_t *oe;
+    const LT *life;
     __device__ __forceinline__ uint64_t key(uint32_t j) { return oe[j]; }
-    __device__ __forceinline__ uint64_t lifev(uint32_t j) { return life[j]; }
+    __device__ __forceinline__ LT lifev(uint32_t j) { return life[j]; }
     // first index >= from (< n) whose key is not below `bound`
     __device__ __forceinline__ uint32_t advance(uint32_t from, uint32_t n, uint64_t bound)
     {
@@ -418,10 +440,12 @@ struct LdsList {                 // the list sits in LDS
         return lo;
     }
 };
-struct GlobalWindow {            // the list sits in global memory: 64 entries at a time in registers
-    const uint64_t *oe, *life;
+template <class LT> struct GlobalWindow {   // the list sits in global memory: 64 entries at a time in registers
+    const uint64_t *oe;
+    const LT *life;
     uint32_t n, base;
-    uint64_t w_oe, w_life;
+    uint64_t w_oe;
+    LT w_life;
     __device__ __forceinline__ void load(uint32_t b)
     {
         base = b;
@@ -434,10 +458,10 @@ struct GlobalWindow {            // the list sits in global memory: 64 entries a
         if (j - base >= (uint32_t)WAVE) load(j & ~(uint32_t)(WAVE - 1));
         return read_lane64(w_oe, (int)(j - base));
     }
-    __device__ __forceinline__ uint64_t lifev(uint32_t j)
+    __device__ __forceinline__ LT lifev(uint32_t j)
     {
         if (j - base >= (uint32_t)WAVE) load(j & ~(uint32_t)(WAVE - 1));
-        return read_lane64(w_life, (int)(j - base));
+        return Life<LT>::lane(w_life, (int)(j - base));
     }
     __device__ __forceinline__ uint32_t advance(uint32_t from, uint32_t cnt, uint64_t bound)
     {
@@ -452,15 +476,16 @@ struct GlobalWindow {            // the list sits in global memory: 64 entries a
 // of small-list entries below each, and writes the small-list entries whose place is inside
 // it (after big-list entries of equal key).  No barrier inside; the caller synchronises
 // before reading dst.
-template <class Small>
-__device__ __forceinline__ void coop_merge(const uint64_t *src_oe, const uint64_t *src_life, uint32_t nb, Small sm,
-                                           uint32_t ns, uint64_t *dst_oe, uint64_t *dst_life, uint32_t wave)
+template <class LT, class Small>
+__device__ __forceinline__ void coop_merge(const uint64_t *src_oe, const LT *src_life, uint32_t nb, Small sm,
+                                           uint32_t ns, uint64_t *dst_oe, LT *dst_life, uint32_t wave)
 {
     const int l = lane_id();
     const uint32_t nch = nb ? (nb + WAVE - 1) / WAVE : 1;
     uint32_t jp = 0;
     for (uint32_t c0 = wave; c0 < nch; c0 += 2 * PW) {
-        uint64_t key[2], lf[2], prevlast[2];
+        uint64_t key[2], prevlast[2];
+        LT lf[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const uint32_t c = c0 + u * PW;
@@ -484,7 +509,7 @@ __device__ __forceinline__ void coop_merge(const uint64_t *src_oe, const uint64_
                 while (j < ns) {
                     const uint64_t rk = sm.key(j);
                     if (!last && !(rk < lastkey)) break;
-                    const uint64_t rl = sm.lifev(j);
+                    const LT rl = sm.lifev(j);
                     const uint32_t below = (uint32_t)__popcll(ballot(valid && key[u] <= rk));
                     if (l == 0) {
                         dst_oe[c * WAVE + below + j] = rk;
@@ -505,13 +530,15 @@ __device__ __forceinline__ void coop_merge(const uint64_t *src_oe, const uint64_
 // of the round wins.  Two workgroup barriers per round; the next round's loads are issued
 // before the current round is processed.  All waves pass the same arguments and get the
 // same result.
-__device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_t *life, uint32_t n,
+template <class LT>
+__device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const LT *life, uint32_t n,
                                                uint32_t &cursor, uint32_t P, uint32_t s, uint32_t a, uint32_t f,
                                                uint32_t wave, uint32_t *s_cmax, uint32_t *s_hq, uint32_t *s_hans)
 {
     const int l = lane_id();
     uint32_t i = cursor;
-    uint64_t x[COOP_U], lf[COOP_U], nx[COOP_U], nlf[COOP_U];
+    uint64_t x[COOP_U], nx[COOP_U];
+    LT lf[COOP_U], nlf[COOP_U];
 #pragma unroll
     for (int k = 0; k < COOP_U; ++k) {
         const uint32_t idx = i + (k * PW + wave) * WAVE + l;
@@ -532,7 +559,7 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_
         for (int k = 0; k < COOP_U; ++k) {
             const uint32_t idx = i + (k * PW + wave) * WAVE + l;
             uint32_t e = (uint32_t)x[k];
-            const uint32_t ea = (uint32_t)(lf[k] >> 32), ef = (uint32_t)lf[k];
+            const uint32_t ea = Life<LT>::a(lf[k]), ef = Life<LT>::f(lf[k]);
             if (idx >= n || !(ea < f && a < ef)) e = 0;
             incl[k] = wave_scan_max32(e);
             if (l == WAVE - 1) s_cmax[k * PW + wave] = incl[k];
@@ -574,9 +601,11 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const uint64_
     }
 }
 
+template <class LT>
 __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
-    __shared__ uint64_t p_oe[PEND], p_life[PEND];
+    __shared__ uint64_t p_oe[PEND];
+    __shared__ LT p_life[PEND];
     __shared__ uint64_t s_h[PW][LH];         // per-wave hole list
     __shared__ uint32_t s_np, s_bc;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
@@ -592,9 +621,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     const uint32_t n = A.n, T = A.T;
     const uint32_t *perm = A.perm + (size_t)b * n;
     uint64_t *m_oe[2] = {A.m_oe[0] + (size_t)b * n, A.m_oe[1] + (size_t)b * n};
-    uint64_t *m_life[2] = {A.m_life[0] + (size_t)b * n, A.m_life[1] + (size_t)b * n};
+    LT *m_life[2] = {(LT *)A.m_life[0] + (size_t)b * n, (LT *)A.m_life[1] + (size_t)b * n};
     uint64_t *r_oe[2] = {A.r_oe[0] + (size_t)b * REC, A.r_oe[1] + (size_t)b * REC};
-    uint64_t *r_life[2] = {A.r_life[0] + (size_t)b * REC, A.r_life[1] + (size_t)b * REC};
+    LT *r_life[2] = {(LT *)A.r_life[0] + (size_t)b * REC, (LT *)A.r_life[1] + (size_t)b * REC};
     uint64_t *hl = s_h[wave];
     uint64_t *L = A.L + (size_t)b * A.capL;
     uint32_t *l_ns = A.l_ns + (size_t)b * T;
@@ -642,7 +671,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     auto flush = [&](uint32_t np) {
         if (np == 0) return;
         if (nr + np > REC) {
-            GlobalWindow gw{r_oe[rb], r_life[rb], nr, 0, 0, 0};
+            GlobalWindow<LT> gw{r_oe[rb], r_life[rb], nr, 0, 0, 0};
             gw.load(0);
             coop_merge(m_oe[mb], m_life[mb], nm, gw, nr, m_oe[mb ^ 1], m_life[mb ^ 1], wave);
             mb ^= 1;
@@ -659,7 +688,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
             if (l == 0) s_np = 0;
         }
         __syncthreads();
-        coop_merge(r_oe[rb], r_life[rb], nr, LdsList{p_oe, p_life}, np, r_oe[rb ^ 1], r_life[rb ^ 1], wave);
+        coop_merge(r_oe[rb], r_life[rb], nr, LdsList<LT>{p_oe, p_life}, np, r_oe[rb ^ 1], r_life[rb ^ 1], wave);
         rb ^= 1;
         nr += np;
         np_multi = 0;
@@ -732,7 +761,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     offs[vv] = (uint64_t)o << sh;
                     if (multi_left > 1) {               // someone will still query ALL
                         p_oe[np] = pk(o, en);
-                        p_life[np] = ((uint64_t)va << 32) | vf;
+                        p_life[np] = Life<LT>::mk(va, vf);
                         s_np = np + 1;
                     }
                 }
@@ -861,7 +890,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         if (multi_left > 0) {
                             const uint32_t slot = atomicAdd(&s_np, 1u);
                             p_oe[slot] = pk(o, o + vs);
-                            p_life[slot] = ((uint64_t)t << 32) | (t + 1);
+                            p_life[slot] = Life<LT>::mk(t, t + 1);
                         }
                     }
                 }
@@ -916,7 +945,10 @@ hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t 
                L, l_ns,
                l_nu, capL,
                offs, fps, g_probe};
-    hipLaunchKernelGGL(k_place_fast, dim3(B), dim3(PW * WAVE), 0, st, A);
+    if (T <= 0xFFFFu)
+        hipLaunchKernelGGL(k_place_fast<uint32_t>, dim3(B), dim3(PW * WAVE), 0, st, A);
+    else
+        hipLaunchKernelGGL(k_place_fast<uint64_t>, dim3(B), dim3(PW * WAVE), 0, st, A);
     return hipGetLastError();
 }
 
