@@ -266,14 +266,14 @@ __device__ __forceinline__ uint32_t mem_find_hole(const uint64_t *Lt, uint32_t n
     return nh - 1;
 }
 
-// bitonic sort of m (power of two, >= 64) packed entries with their lifetimes, in LDS, one wave
+// bitonic sort of m (power of two, >= 64) packed entries with their lifetimes, in LDS, by the
+// whole workgroup (a workgroup barrier after every compare-exchange stage)
 template <class LT>
 __device__ __forceinline__ void bitonic_sort(uint64_t *oe, LT *life, uint32_t m)
 {
-    const int l = lane_id();
     for (uint32_t k = 2; k <= m; k <<= 1) {
         for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            for (uint32_t i = l; i < m / 2; i += WAVE) {
+            for (uint32_t i = threadIdx.x; i < m / 2; i += PW * WAVE) {
                 const uint32_t lo = ((i / j) * (j << 1)) + (i % j);
                 const uint32_t hi = lo + j;
                 const bool up = (lo & k) == 0;
@@ -284,7 +284,7 @@ __device__ __forceinline__ void bitonic_sort(uint64_t *oe, LT *life, uint32_t m)
                     life[lo] = v; life[hi] = u;
                 }
             }
-            lds_sync();
+            __syncthreads();
         }
     }
 }
@@ -679,15 +679,12 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
             nr = 0;
             __syncthreads();
         }
-        if (wave == 0) {
-            uint32_t m = WAVE;
-            while (m < np) m <<= 1;
-            for (uint32_t i = np + l; i < m; i += WAVE) { p_oe[i] = U64_MAX; p_life[i] = 0; }
-            wave_fence();
-            bitonic_sort(p_oe, p_life, m);
-            if (l == 0) s_np = 0;
-        }
+        uint32_t m = WAVE;
+        while (m < np) m <<= 1;
+        for (uint32_t i = np + threadIdx.x; i < m; i += PW * WAVE) { p_oe[i] = U64_MAX; p_life[i] = 0; }
+        if (threadIdx.x == 0) s_np = 0;
         __syncthreads();
+        bitonic_sort(p_oe, p_life, m);
         coop_merge(r_oe[rb], r_life[rb], nr, LdsList<LT>{p_oe, p_life}, np, r_oe[rb ^ 1], r_life[rb ^ 1], wave);
         rb ^= 1;
         nr += np;
