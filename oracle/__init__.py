@@ -161,3 +161,31 @@ def score_swaps(tr, link_GBps: float, min_bytes: int, use_gaps=True, check=True)
     if rc:
         return rc
     return dict(candidate=cand, doa_ns=doa, aoa=aoa, wdoa=wdoa, peak_cut=cut)
+
+
+def select_swaps(tr, link_GBps: float, min_bytes: int, score_kind: int, limits, use_gaps=True):
+    lib = _load()
+    n = tr.n_vars
+    limits = _c(limits, np.uint64)
+    L = len(limits)
+    order = np.zeros(n, np.uint32)
+    rank = np.zeros(n, np.uint32)
+    peaks = np.zeros(n + 1, np.uint64)
+    n_sel = np.zeros(max(L, 1), np.uint32)
+    peak_after = np.zeros(max(L, 1), np.uint64)
+    n_cand = C.c_uint32(0)
+    load_min = C.c_uint64(0)
+    rc = lib.lapo_select_swaps(
+        C.c_uint32(n), C.c_uint32(tr.n_steps),
+        _opt(tr.size, np.uint64), _opt(tr.alloc, np.uint32), _opt(tr.free, np.uint32),
+        _opt(tr.gap_lo if use_gaps else None, np.uint32), _opt(tr.gap_hi if use_gaps else None, np.uint32),
+        _opt(tr.step_ns, np.uint64), C.c_double(link_GBps), C.c_uint64(min_bytes), C.c_uint32(score_kind),
+        limits.ctypes.data_as(C.c_void_p), C.c_uint32(L),
+        order.ctypes.data_as(C.c_void_p), rank.ctypes.data_as(C.c_void_p), C.byref(n_cand),
+        peaks.ctypes.data_as(C.c_void_p), n_sel.ctypes.data_as(C.c_void_p), peak_after.ctypes.data_as(C.c_void_p),
+        C.byref(load_min))
+    if rc:
+        raise RuntimeError(f"lapo_select_swaps rc={rc}")
+    nc = int(n_cand.value)
+    return dict(order=order[:nc], rank=rank, n_cand=nc, peaks=peaks[:nc + 1], n_selected=n_sel[:L],
+                peak_after=peak_after[:L], load_min=int(load_min.value))

@@ -31,6 +31,13 @@
  *                       is this build's reading of "how much the peak drops",
  *                       pinned against a literal re-simulation of the load
  *                       curve with the variable removed.
+ *   lapo_select_swaps : pinned (two hand-worked examples, one where the SWDOA
+ *                       order differs from the WDOA order; a dense-matrix
+ *                       re-simulation in exact integers; monotone peaks and
+ *                       minimal-prefix properties).  Tie rule (lower index
+ *                       first) and "away on whole steps only" are this build's
+ *                       readings; load_min takes "synchronously" as: away on
+ *                       every idle step.
  */
 #include <math.h>
 #include <stdint.h>
@@ -368,4 +375,141 @@ int lapo_score_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32_
     }
     free(load); free(C);
     return LAPO_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* selection of swap variables down to a memory-load limit (Section IV-D),  */
+/* with the submodular WDOA order of Section IV-B (iv) and load_min (VI-B)   */
+/* ------------------------------------------------------------------------ */
+
+enum { LAPO_PS_DOA = 0, LAPO_PS_AOA = 1, LAPO_PS_WDOA = 2, LAPO_PS_SWDOA = 3, LAPO_PS_PEAK_CUT = 4 };
+
+/* Whole steps [lo, hi) during which variable i is away when swapped: those inside
+ * [C[t_lo+1]+delta, C[t_hi]-delta); lo = hi = 0 when DOA < 0 or no whole step fits. */
+static void absent_window(uint32_t T, const uint64_t *C, uint32_t tl, uint32_t th, uint64_t delta,
+                          uint32_t *lo_out, uint32_t *hi_out)
+{
+    *lo_out = 0; *hi_out = 0;
+    if (th <= tl) return;
+    const int64_t d = (int64_t)(C[th] - C[tl + 1]) - 2 * (int64_t)delta;
+    if (d < 0) return;
+    const uint64_t out_done = C[tl + 1] + delta, in_start = C[th] - delta;
+    uint32_t lo = 0, hi = 0;
+    while (C[lo] < out_done) ++lo;
+    for (uint32_t t = 0; t <= T; ++t) if (C[t] <= in_start) hi = t;
+    if (hi > lo) { *lo_out = lo; *hi_out = hi; }
+}
+
+/* Section IV-D: the candidates (Section IV-A) are ordered by a priority score, highest first
+ * (equal scores: lower variable index first), and added to the swap list one by one; every
+ * addition removes the variable's size from the load on its absent steps; the walk stops as
+ * soon as the peak load is no larger than the limit.
+ *   score_kind 0..2, 4: order by DOA / AOA / WDOA / peak cut as lapo_score_swaps gives them.
+ *   score_kind 3 (SWDOA, Section IV-B iv): repeatedly take the candidate with the largest
+ *     WDOA measured on the CURRENT (already reduced) load curve, then reduce the curve.
+ * Outputs: order[k] = k-th variable of the priority order (k < *n_cand), rank[i] = its
+ * position or 0xFFFFFFFF for non-candidates, peaks[k] = peak load after the first k
+ * additions (k = 0 .. *n_cand), and for every limit the number of variables selected and
+ * the peak reached (all candidates when the limit is out of reach).
+ * load_min (Section VI-B1): the peak of the curve with every candidate away on ALL its idle
+ * steps gap_lo+1 .. gap_hi-1 (swapped out and in synchronously, transfers not hidden). */
+int lapo_select_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                      const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                      const uint64_t *step_ns, double link_GBps, uint64_t min_bytes, uint32_t score_kind,
+                      const uint64_t *limits, uint32_t n_limits,
+                      uint32_t *order, uint32_t *rank, uint32_t *n_cand, uint64_t *peaks,
+                      uint32_t *n_selected, uint64_t *peak_after, uint64_t *load_min)
+{
+    if (!order || !rank || !n_cand || !peaks || !load_min) return LAPO_E_NULL;
+    if (n_limits && (!limits || !n_selected || !peak_after)) return LAPO_E_NULL;
+    if (score_kind > 4) return LAPO_E_ORDERING;
+    uint8_t *cand = (uint8_t *)malloc(n);
+    int64_t *doa = (int64_t *)malloc((size_t)n * 8);
+    double *aoa = (double *)malloc((size_t)n * 8);
+    uint64_t *wdoa = (uint64_t *)malloc((size_t)n * 8);
+    uint64_t *cut = (uint64_t *)malloc((size_t)n * 8);
+    uint64_t *load = (uint64_t *)malloc((size_t)T * 8);
+    uint64_t *C = (uint64_t *)malloc(((size_t)T + 1) * 8);
+    uint32_t *wlo = (uint32_t *)malloc((size_t)n * 4), *whi = (uint32_t *)malloc((size_t)n * 4);
+    uint8_t *taken = (uint8_t *)calloc(n, 1);
+    int rc = LAPO_E_NOMEM;
+    if (!cand || !doa || !aoa || !wdoa || !cut || !load || !C || !wlo || !whi || !taken) goto done;
+    rc = lapo_score_swaps(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, min_bytes, cand, doa, aoa,
+                          wdoa, cut);
+    if (rc) goto done;
+    {
+        uint64_t peak; uint32_t t_peak;
+        rc = lapo_load_profile(n, T, size, alloc, free_, load, &peak, &t_peak);
+        if (rc) goto done;
+    }
+    const uint64_t bpus = (uint64_t)llround(link_GBps * 1000.0);
+    C[0] = 0;
+    for (uint32_t t = 0; t < T; ++t) C[t + 1] = C[t] + (step_ns ? step_ns[t] : 1000000u);
+    uint32_t nc = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        rank[i] = 0xFFFFFFFFu;
+        const uint32_t tl = gap_lo ? gap_lo[i] : alloc[i], th = gap_hi ? gap_hi[i] : free_[i] - 1;
+        absent_window(T, C, tl, th, (size[i] * 1000u + bpus - 1) / bpus, &wlo[i], &whi[i]);
+        if (cand[i]) ++nc;
+    }
+    *n_cand = nc;
+    /* load_min: every candidate away on all its idle steps */
+    {
+        uint64_t m = 0;
+        for (uint32_t t = 0; t < T; ++t) {
+            uint64_t l = load[t];
+            for (uint32_t i = 0; i < n; ++i) {
+                if (!cand[i]) continue;
+                const uint32_t tl = gap_lo ? gap_lo[i] : alloc[i], th = gap_hi ? gap_hi[i] : free_[i] - 1;
+                if (t > tl && t < th) l -= size[i];
+            }
+            if (l > m) m = l;
+        }
+        *load_min = m;
+    }
+    /* the walk */
+    {
+        uint64_t pk = 0;
+        for (uint32_t t = 0; t < T; ++t) if (load[t] > pk) pk = load[t];
+        peaks[0] = pk;
+    }
+    for (uint32_t k = 0; k < nc; ++k) {
+        /* next variable of the priority order: best score among the candidates not taken yet */
+        uint32_t best = 0xFFFFFFFFu;
+        for (uint32_t i = 0; i < n; ++i) {
+            if (!cand[i] || taken[i]) continue;
+            if (score_kind == LAPO_PS_SWDOA) {           /* WDOA on the current curve */
+                const uint32_t tl = gap_lo ? gap_lo[i] : alloc[i], th = gap_hi ? gap_hi[i] : free_[i] - 1;
+                uint64_t area = 0;
+                for (uint32_t t = tl + 1; t < th; ++t) area += load[t];
+                wdoa[i] = area;
+            }
+            int better;
+            if (best == 0xFFFFFFFFu) better = 1;
+            else switch (score_kind) {
+                case LAPO_PS_DOA: better = doa[i] > doa[best]; break;
+                case LAPO_PS_AOA: better = aoa[i] > aoa[best]; break;
+                case LAPO_PS_PEAK_CUT: better = cut[i] > cut[best]; break;
+                default: better = wdoa[i] > wdoa[best]; break;
+            }
+            if (better) best = i;
+        }
+        taken[best] = 1;
+        order[k] = best;
+        rank[best] = k;
+        for (uint32_t t = wlo[best]; t < whi[best]; ++t) load[t] -= size[best];
+        uint64_t pk = 0;
+        for (uint32_t t = 0; t < T; ++t) if (load[t] > pk) pk = load[t];
+        peaks[k + 1] = pk;
+    }
+    for (uint32_t q = 0; q < n_limits; ++q) {
+        uint32_t k = 0;
+        while (k < nc && peaks[k] > limits[q]) ++k;
+        n_selected[q] = k;
+        peak_after[q] = peaks[k];
+    }
+    rc = LAPO_OK;
+done:
+    free(cand); free(doa); free(aoa); free(wdoa); free(cut); free(load); free(C); free(wlo); free(whi); free(taken);
+    return rc;
 }
