@@ -16,6 +16,10 @@
  *   lap_score_swaps   AutoSwap candidate filter and priority scores (Section
  *                     IV-A, IV-B): DOA, AOA, WDOA, and the drop of the peak
  *                     load when the variable is away for its idle gap.
+ *   lap_select_swaps  AutoSwap selection (Section IV-D): candidates taken in
+ *                     priority order until the peak load is within a limit,
+ *                     for several scores (SWDOA of Section IV-B (iv) among
+ *                     them) and limits at once; load_min of Section VI-B1.
  *
  * Conventions
  *   - Lifetimes are half-open: variable i is live during steps
@@ -59,7 +63,7 @@ enum {
     LAP_E_NULL = -1,       /* a required pointer is NULL (or only one of gap_lo/gap_hi given) */
     LAP_E_SIZE = -2,       /* n_vars, n_steps or B is 0, or a size exceeds the supported maximum */
     LAP_E_WORKSPACE = -3,  /* ws is NULL, misaligned or smaller than lap_workspace_bytes() */
-    LAP_E_ORDERING = -4,   /* unknown ordering kind, or NULL permutation for LAP_ORD_EXPLICIT */
+    LAP_E_ORDERING = -4,   /* unknown ordering or score kind, or NULL permutation for LAP_ORD_EXPLICIT */
     LAP_E_LINK = -5,       /* link_GBps <= 0, not finite, or rounds to 0 bytes per microsecond */
     LAP_E_TRACE = -6,      /* size 0, alloc >= free, free > n_steps, gap outside [alloc, free-1], step_ns 0 */
     LAP_E_RANGE = -7,      /* sum of sizes >= 2^63, a size >= 2^53, sum of step_ns >= 2^53, max size * n_steps >= 2^64 */
@@ -102,10 +106,17 @@ typedef struct {
     uint64_t seed;
 } lap_ordering;
 
-enum { LAP_WS_LOAD_PROFILE = 0, LAP_WS_PLAN_POOL = 1, LAP_WS_SCORE_SWAPS = 2, LAP_WS_VALIDATE = 3 };
+enum {
+    LAP_WS_LOAD_PROFILE = 0,
+    LAP_WS_PLAN_POOL = 1,
+    LAP_WS_SCORE_SWAPS = 2,
+    LAP_WS_VALIDATE = 3,
+    LAP_WS_SELECT_SWAPS = 4
+};
 
-/* Bytes of workspace the given call needs (B is ignored except for PLAN_POOL).
- * Returns 0 for an unknown call id. */
+/* Bytes of workspace the given call needs.  B is the number of orderings for PLAN_POOL, the
+ * number of score kinds for SELECT_SWAPS, and ignored otherwise.  Returns 0 for an unknown
+ * call id. */
 size_t lap_workspace_bytes(int which_call, uint32_t n_vars, uint32_t n_steps, uint32_t B);
 
 /* Section II Def. 2 / Def. 4, Eq. 1.
@@ -143,6 +154,36 @@ int lap_score_swaps(const lap_trace *trace, double link_GBps, uint64_t min_bytes
                     uint8_t *candidate, int64_t *doa_ns, double *aoa, uint64_t *wdoa, uint64_t *peak_cut,
                     void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Priority scores a selection can walk by (Section IV-B). */
+enum { LAP_PS_DOA = 0, LAP_PS_AOA = 1, LAP_PS_WDOA = 2, LAP_PS_SWDOA = 3, LAP_PS_PEAK_CUT = 4 };
+
+/* Section IV-D, for K priority scores and L load limits at once.  The candidates of
+ * Section IV-A are put in priority order, highest score first, equal scores by ascending
+ * variable index, and added to the swap list one by one; an added variable leaves the load
+ * curve on the whole steps between the end of its swap-out and the start of its swap-in
+ * (none if its DOA is negative).  A limit is served by the shortest prefix of the order whose
+ * remaining peak is <= the limit, or by all candidates when the limit is out of reach.
+ * LAP_PS_SWDOA (Section IV-B iv) builds its order as it goes: the next variable is the one
+ * with the largest WDOA measured on the curve already reduced by the earlier picks.
+ *   load, link_GBps, min_bytes   as for lap_score_swaps
+ *   score_kinds [K] host, K <= 64          limits [L] host, L <= 1024 (L may be 0)
+ *   order      [K*N]     out: order[k*N + j] = j-th variable of kind k's order, j < n_cand;
+ *                             the rest of each row is left untouched
+ *   rank       [K*N]     out or NULL: position of a variable in the order, 0xFFFFFFFF if not a candidate
+ *   peaks      [K*(N+1)] out: peaks[k*(N+1) + j] = peak load after the first j additions, j <= n_cand
+ *   n_cand     [1]       out: number of candidates
+ *   n_selected [K*L]     out: variables selected for each limit
+ *   peak_after [K*L]     out: peak load reached for each limit
+ *   load_min   [1]       out: Section VI-B1, the peak of the curve with every candidate away on
+ *                             all its idle steps gap_lo+1 .. gap_hi-1 (transfers not hidden)
+ * The walk is sequential: one workgroup per score kind, about n_cand * (n_cand + T) / 1024
+ * steps of work each. */
+int lap_select_swaps(const lap_trace *trace, double link_GBps, uint64_t min_bytes, const uint64_t *load,
+                     const uint32_t *score_kinds, uint32_t K, const uint64_t *limits, uint32_t L,
+                     uint32_t *order, uint32_t *rank, uint64_t *peaks, uint32_t *n_cand,
+                     uint32_t *n_selected, uint64_t *peak_after, uint64_t *load_min,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
 /* Checks the trace content on the device, waits for the stream, and returns
  * LAP_OK, LAP_E_TRACE or LAP_E_RANGE. */
 int lap_validate_trace(const lap_trace *trace, void *ws, size_t ws_bytes, void *hip_stream);
@@ -153,7 +194,7 @@ const char *lap_status_string(int status);
  * its dominant kernel with HIP events on the caller's stream; after the
  * stream is synchronised lap_profile_last_ms returns that kernel's duration
  * in ms (negative if none was recorded).  Not thread safe. */
-enum { LAP_K_LOAD_SCATTER = 0, LAP_K_PLACE = 1, LAP_K_SCORE = 2, LAP_K_SORT = 3, LAP_K_COUNT = 4 };
+enum { LAP_K_LOAD_SCATTER = 0, LAP_K_PLACE = 1, LAP_K_SCORE = 2, LAP_K_SORT = 3, LAP_K_SELECT = 4, LAP_K_COUNT = 5 };
 int lap_profile_enable(int on);
 float lap_profile_last_ms(int kernel_id);
 

@@ -15,11 +15,13 @@ from .binding import (  # noqa: F401
     profile_enable,
     profile_last_ms,
     score_swaps,
+    select_swaps,
     status_string,
     validate_trace,
     workspace_bytes,
 )
 
 ORD_SIZE_DESC, ORD_LIFE_DESC, ORD_AREA_DESC, ORD_ALLOC_ASC, ORD_SEEDED, ORD_EXPLICIT = range(6)
-WS_LOAD_PROFILE, WS_PLAN_POOL, WS_SCORE_SWAPS, WS_VALIDATE = range(4)
-K_LOAD_SCATTER, K_PLACE, K_SCORE, K_SORT = range(4)
+WS_LOAD_PROFILE, WS_PLAN_POOL, WS_SCORE_SWAPS, WS_VALIDATE, WS_SELECT_SWAPS = range(5)
+K_LOAD_SCATTER, K_PLACE, K_SCORE, K_SORT, K_SELECT = range(5)
+PS_DOA, PS_AOA, PS_WDOA, PS_SWDOA, PS_PEAK_CUT = range(5)

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "liblap.so")
 _lib = None
 
 EXPORTS = [
-    "lap_workspace_bytes", "lap_load_profile", "lap_plan_pool", "lap_score_swaps",
+    "lap_workspace_bytes", "lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
     "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms",
 ]
 
@@ -64,6 +64,11 @@ def load_library():
     lib.lap_score_swaps.argtypes = [C.POINTER(_Trace), C.c_double, C.c_uint64, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lap_select_swaps.restype = C.c_int
+    lib.lap_select_swaps.argtypes = [C.POINTER(_Trace), C.c_double, C.c_uint64, C.c_void_p,
+                                     C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lap_validate_trace.restype = C.c_int
     lib.lap_validate_trace.argtypes = [C.POINTER(_Trace), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lap_profile_enable.restype = C.c_int
@@ -231,6 +236,39 @@ def score_swaps(dt: DeviceTrace, link_GBps: float, min_bytes: int, load=None, sy
                              ws.data_ptr(), need, _stream_ptr(dt.device))
     if rc:
         raise LapError(rc, "lap_score_swaps")
+    if sync:
+        torch.cuda.current_stream(dt.device).synchronize()
+    return out
+
+
+def select_swaps(dt: DeviceTrace, link_GBps: float, min_bytes: int, score_kinds: Sequence[int],
+                 limits: Sequence[int] = (), load=None, want_rank: bool = True, sync: bool = True):
+    """lap_select_swaps: returns device tensors order[K,N], rank[K,N] (optional), peaks[K,N+1], n_cand[1],
+    n_selected[K,L], peak_after[K,L], load_min[1] (rows are valid up to n_cand; see include/lap.h)."""
+    torch = _torch()
+    lib = load_library()
+    n, K, L = dt.n_vars, len(score_kinds), len(limits)
+    kinds = (C.c_uint32 * max(K, 1))(*[int(k) for k in score_kinds])
+    lims = (C.c_uint64 * max(L, 1))(*[int(x) for x in limits])
+    out = dict(
+        order=torch.empty((K, n), dtype=torch.int32, device=dt.device),
+        rank=torch.empty((K, n), dtype=torch.int32, device=dt.device) if want_rank else None,
+        peaks=torch.empty((K, n + 1), dtype=torch.int64, device=dt.device),
+        n_cand=torch.empty(1, dtype=torch.int32, device=dt.device),
+        n_selected=torch.empty((K, L), dtype=torch.int32, device=dt.device),
+        peak_after=torch.empty((K, L), dtype=torch.int64, device=dt.device),
+        load_min=torch.empty(1, dtype=torch.int64, device=dt.device),
+    )
+    ws, need = dt.workspace(4, K)
+    tr = dt.c_struct()
+    p = lambda t: None if t is None else t.data_ptr()
+    rc = lib.lap_select_swaps(C.byref(tr), float(link_GBps), int(min_bytes), p(load),
+                              kinds, K, lims if L else None, L,
+                              p(out["order"]), p(out["rank"]), p(out["peaks"]), p(out["n_cand"]),
+                              p(out["n_selected"]) if L else None, p(out["peak_after"]) if L else None,
+                              p(out["load_min"]), ws.data_ptr(), need, _stream_ptr(dt.device))
+    if rc:
+        raise LapError(rc, "lap_select_swaps")
     if sync:
         torch.cuda.current_stream(dt.device).synchronize()
     return out

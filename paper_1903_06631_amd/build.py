@@ -7,7 +7,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblap.so")
-SOURCES = ["api.hip", "load_profile.hip", "orderings.hip", "place_fast.hip", "place_wide.hip", "swap_scores.hip"]
+SOURCES = ["api.hip", "load_profile.hip", "orderings.hip", "place_fast.hip", "place_wide.hip", "swap_scores.hip",
+           "select_swaps.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -67,6 +67,18 @@ size_t ws_score(uint32_t T)
 
 size_t ws_validate() { return up(8 * 8); }
 
+constexpr uint32_t SELECT_MAX_LIMITS = 1024;
+constexpr uint32_t SELECT_MAX_KINDS = 64;
+
+size_t ws_select(uint32_t n, uint32_t T, uint32_t K)
+{
+    const size_t N = n;
+    return ws_score(T) + up(N) + 4 * up(N * 8) + 2 * up(N * 4)      // scores and away windows of every variable
+           + 3 * up(N * 4) + up(((size_t)T + 1) * 8) + ALIGN          // candidate slots, load_min differences, counter
+           + up((size_t)SELECT_MAX_KINDS * 4) + up((size_t)SELECT_MAX_LIMITS * 8)
+           + (size_t)K * (up(N * 8) + up(N * 4) + up((size_t)T * 8)); // per kind: slot scores, slot variables, curve
+}
+
 int check_trace_args(const lap_trace *tr)
 {
     if (!tr) return LAP_E_NULL;
@@ -146,6 +158,7 @@ size_t lap_workspace_bytes(int which, uint32_t n_vars, uint32_t n_steps, uint32_
     case LAP_WS_PLAN_POOL: return ws_plan(n_vars, n_steps, B);
     case LAP_WS_SCORE_SWAPS: return ws_score(n_steps);
     case LAP_WS_VALIDATE: return ws_validate();
+    case LAP_WS_SELECT_SWAPS: return ws_select(n_vars, n_steps, B);
     default: return 0;
     }
 }
@@ -157,7 +170,7 @@ const char *lap_status_string(int s)
     case LAP_E_NULL: return "null pointer argument";
     case LAP_E_SIZE: return "zero or unsupported size";
     case LAP_E_WORKSPACE: return "workspace missing, misaligned or too small";
-    case LAP_E_ORDERING: return "bad ordering descriptor";
+    case LAP_E_ORDERING: return "bad ordering descriptor or score kind";
     case LAP_E_LINK: return "bad link bandwidth";
     case LAP_E_TRACE: return "invalid trace content";
     case LAP_E_RANGE: return "trace values out of the supported range";
@@ -315,7 +328,94 @@ int lap_score_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, c
         ProfScope p(LAP_K_SCORE, st);
         LAP_HIP(lap::launch_score(n, T, tr->size, tr->alloc, tr->free_, tr->gap_lo, tr->gap_hi, (uint64_t)bpus,
                                   min_bytes, load, C, S, PM, SM, table, peak, t_peak, candidate, doa_ns, aoa, wdoa,
-                                  peak_cut, st));
+                                  peak_cut, nullptr, nullptr, st));
+    }
+    return LAP_OK;
+}
+
+int lap_select_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, const uint64_t *load,
+                     const uint32_t *score_kinds, uint32_t K, const uint64_t *limits, uint32_t L, uint32_t *order,
+                     uint32_t *rank, uint64_t *peaks, uint32_t *n_cand, uint32_t *n_selected, uint64_t *peak_after,
+                     uint64_t *load_min, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!score_kinds || !order || !peaks || !n_cand || !load_min) return LAP_E_NULL;
+    if (L && (!limits || !n_selected || !peak_after)) return LAP_E_NULL;
+    if (K == 0 || K > SELECT_MAX_KINDS || L > SELECT_MAX_LIMITS) return LAP_E_SIZE;
+    for (uint32_t k = 0; k < K; ++k)
+        if (score_kinds[k] > LAP_PS_PEAK_CUT) return LAP_E_ORDERING;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps) || link_GBps * 1000.0 >= 9.0e18) return LAP_E_LINK;
+    const long long bpus = llround(link_GBps * 1000.0);
+    if (bpus <= 0) return LAP_E_LINK;
+    const uint32_t n = tr->n_vars, T = tr->n_steps;
+    rc = check_ws(ws, ws_bytes, ws_select(n, T, K));
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t t1 = (size_t)T + 1;
+    Carver c(ws);
+    uint64_t *load_ws = c.take<uint64_t>(T);
+    uint64_t *delta = c.take<uint64_t>(t1);
+    uint64_t *C = c.take<uint64_t>(t1);
+    uint64_t *S = c.take<uint64_t>(t1);
+    uint64_t *PM = c.take<uint64_t>(t1);
+    uint64_t *SM = c.take<uint64_t>(t1);
+    const uint32_t levels = table_levels(T);
+    uint64_t *table = c.take<uint64_t>((size_t)levels * T);
+    uint64_t *peak = c.take<uint64_t>(1);
+    uint32_t *t_peak = c.take<uint32_t>(1);
+    uint8_t *cand = c.take<uint8_t>(n);
+    int64_t *doa = c.take<int64_t>(n);
+    double *aoa = c.take<double>(n);
+    uint64_t *wdoa = c.take<uint64_t>(n);
+    uint64_t *cut = c.take<uint64_t>(n);
+    uint32_t *win_lo = c.take<uint32_t>(n);
+    uint32_t *win_hi = c.take<uint32_t>(n);
+    uint32_t *cidx = c.take<uint32_t>(n);
+    uint32_t *c_ilo = c.take<uint32_t>(n);
+    uint32_t *c_ihi = c.take<uint32_t>(n);
+    uint64_t *dmin = c.take<uint64_t>(t1);
+    uint32_t *nc = c.take<uint32_t>(1);
+    uint32_t *d_kinds = c.take<uint32_t>(SELECT_MAX_KINDS);
+    uint64_t *d_limits = c.take<uint64_t>(SELECT_MAX_LIMITS);
+    uint64_t *r_score = c.take<uint64_t>(0);
+    c.used += (size_t)K * up((size_t)n * 8);
+    uint32_t *r_var = c.take<uint32_t>(0);
+    c.used += (size_t)K * up((size_t)n * 4);
+    uint64_t *l_cur = c.take<uint64_t>(0);
+    c.used += (size_t)K * up((size_t)T * 8);
+
+    static thread_local std::vector<uint32_t> hk;
+    static thread_local std::vector<uint64_t> hl;
+    hk.assign(score_kinds, score_kinds + K);
+    hl.assign(limits, limits + L);
+    LAP_HIP(hipMemcpyAsync(d_kinds, hk.data(), (size_t)K * 4, hipMemcpyHostToDevice, st));
+    if (L) LAP_HIP(hipMemcpyAsync(d_limits, hl.data(), (size_t)L * 8, hipMemcpyHostToDevice, st));
+
+    if (!load) {
+        rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
+        if (rc) return rc;
+        load = load_ws;
+    }
+    LAP_HIP(lap::launch_swap_prefix(T, load, tr->step_ns, C, S, PM, SM, peak, t_peak, st));
+    LAP_HIP(lap::launch_sparse_table(T, load, table, levels, st));
+    LAP_HIP(lap::launch_score(n, T, tr->size, tr->alloc, tr->free_, tr->gap_lo, tr->gap_hi, (uint64_t)bpus, min_bytes,
+                              load, C, S, PM, SM, table, peak, t_peak, cand, doa, aoa, wdoa, cut, win_lo, win_hi, st));
+    LAP_HIP(lap::launch_fill_u64(dmin, t1, 0, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)nc, 1, 0, st));
+    lap::SelectArgs a;
+    a.n = n; a.T = T; a.K = K; a.L = L;
+    a.size = tr->size; a.gap_lo = tr->gap_lo; a.gap_hi = tr->gap_hi; a.alloc = tr->alloc; a.free_ = tr->free_;
+    a.load = load; a.cand = cand; a.doa = doa; a.aoa = aoa; a.wdoa = wdoa; a.cut = cut;
+    a.win_lo = win_lo; a.win_hi = win_hi; a.nc = nc; a.cidx = cidx; a.c_ilo = c_ilo; a.c_ihi = c_ihi; a.dmin = dmin;
+    a.kinds = d_kinds; a.limits = d_limits;
+    // per-kind regions are laid out with the kind as the slowest index and a stride of n (or T) elements
+    a.r_score = r_score; a.r_var = r_var; a.l_cur = l_cur;
+    a.order = order; a.rank = rank; a.peaks = peaks; a.n_cand = n_cand; a.n_selected = n_selected;
+    a.peak_after = peak_after; a.load_min = load_min;
+    {
+        ProfScope p(LAP_K_SELECT, st);
+        LAP_HIP(lap::launch_select_swaps(a, st));
     }
     return LAP_OK;
 }

@@ -50,6 +50,36 @@ hipError_t launch_score(uint32_t n, uint32_t T, const uint64_t *size, const uint
                         const uint32_t *gap_lo, const uint32_t *gap_hi, uint64_t bpus, uint64_t min_bytes,
                         const uint64_t *load, const uint64_t *C, const uint64_t *S, const uint64_t *PM,
                         const uint64_t *SM, const uint64_t *table, const uint64_t *peak, const uint32_t *t_peak,
-                        uint8_t *cand, int64_t *doa, double *aoa, uint64_t *wdoa, uint64_t *cut, hipStream_t st);
+                        uint8_t *cand, int64_t *doa, double *aoa, uint64_t *wdoa, uint64_t *cut, uint32_t *win_lo,
+                        uint32_t *win_hi, hipStream_t st);
+
+// Selection of swap variables (select_swaps.hip).  All pointers are device memory.
+struct SelectArgs {
+    uint32_t n, T, K, L;
+    const uint64_t *size;
+    const uint32_t *gap_lo, *gap_hi, *alloc, *free_;
+    const uint64_t *load;
+    const uint8_t *cand;
+    const int64_t *doa;
+    const double *aoa;
+    const uint64_t *wdoa, *cut;
+    const uint32_t *win_lo, *win_hi;
+    uint32_t *nc;              // [1] number of candidates (device counter)
+    uint32_t *cidx;            // [n] candidate slot -> variable
+    uint32_t *c_ilo, *c_ihi;   // [n] idle steps [ilo, ihi) of the candidate in a slot
+    uint64_t *dmin;            // [T+1] difference array of the load removed for load_min
+    const uint32_t *kinds;     // [K]
+    const uint64_t *limits;    // [L]
+    uint64_t *r_score;         // [K][n] current score of every slot
+    uint32_t *r_var;           // [K][n] variable of the slot, 0xFFFFFFFF once taken
+    uint64_t *l_cur;           // [K][T] current load curve
+    uint32_t *order, *rank;    // [K][n] outputs (rank may be null)
+    uint64_t *peaks;           // [K][n+1]
+    uint32_t *n_cand;          // [1]
+    uint32_t *n_selected;      // [K][L]
+    uint64_t *peak_after;      // [K][L]
+    uint64_t *load_min;        // [1]
+};
+hipError_t launch_select_swaps(const SelectArgs &a, hipStream_t st);
 
 }  // namespace lap

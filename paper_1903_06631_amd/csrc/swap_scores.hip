@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256) void k_score(uint32_t n, uint32_t T, const uin
                                                const uint64_t *__restrict__ peak_p, const uint32_t *__restrict__ tpeak_p,
                                                uint8_t *__restrict__ cand, int64_t *__restrict__ doa,
                                                double *__restrict__ aoa, uint64_t *__restrict__ wdoa,
-                                               uint64_t *__restrict__ cut)
+                                               uint64_t *__restrict__ cut, uint32_t *__restrict__ win_lo,
+                                               uint32_t *__restrict__ win_hi)
 {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -108,6 +109,7 @@ __global__ __launch_bounds__(256) void k_score(uint32_t n, uint32_t T, const uin
     const uint32_t tl = gap_lo ? gap_lo[i] : a;
     const uint32_t th = gap_hi ? gap_hi[i] : f - 1;
     uint8_t c = 0; int64_t d = 0; double ar = 0.0; uint64_t w = 0, pc = 0;
+    uint32_t wl = 0, wh = 0;          // whole steps [wl, wh) during which a swapped variable is away
     if (th > tl) {
         c = (s >= min_bytes && a <= t_peak && t_peak < f) ? 1 : 0;
         const uint64_t delta = (s * 1000ull + bpus - 1) / bpus;
@@ -125,6 +127,7 @@ __global__ __launch_bounds__(256) void k_score(uint32_t n, uint32_t T, const uin
             while (l0 < h0) { const uint32_t m = (l0 + h0 + 1) >> 1; if (C[m] <= in_start) l0 = m; else h0 = m - 1; }
             const uint32_t hi = l0;
             if (hi > lo) {
+                wl = lo; wh = hi;
                 const uint32_t len = hi - lo;
                 const uint32_t k = 31 - __clz(len);
                 const uint64_t *lvl = table + (size_t)k * T;
@@ -135,6 +138,7 @@ __global__ __launch_bounds__(256) void k_score(uint32_t n, uint32_t T, const uin
         }
     }
     cand[i] = c; doa[i] = d; aoa[i] = ar; wdoa[i] = w; cut[i] = pc;
+    if (win_lo) { win_lo[i] = wl; win_hi[i] = wh; }
 }
 
 hipError_t launch_swap_prefix(uint32_t T, const uint64_t *load, const uint64_t *step_ns, uint64_t *C, uint64_t *S,
@@ -160,11 +164,12 @@ hipError_t launch_score(uint32_t n, uint32_t T, const uint64_t *size, const uint
                         const uint32_t *gap_lo, const uint32_t *gap_hi, uint64_t bpus, uint64_t min_bytes,
                         const uint64_t *load, const uint64_t *C, const uint64_t *S, const uint64_t *PM,
                         const uint64_t *SM, const uint64_t *table, const uint64_t *peak, const uint32_t *t_peak,
-                        uint8_t *cand, int64_t *doa, double *aoa, uint64_t *wdoa, uint64_t *cut, hipStream_t st)
+                        uint8_t *cand, int64_t *doa, double *aoa, uint64_t *wdoa, uint64_t *cut, uint32_t *win_lo,
+                        uint32_t *win_hi, hipStream_t st)
 {
     const uint32_t blocks = (n + 255) / 256;
     hipLaunchKernelGGL(k_score, dim3(blocks), dim3(256), 0, st, n, T, size, alloc, free_, gap_lo, gap_hi, bpus,
-                       min_bytes, load, C, S, PM, SM, table, peak, t_peak, cand, doa, aoa, wdoa, cut);
+                       min_bytes, load, C, S, PM, SM, table, peak, t_peak, cand, doa, aoa, wdoa, cut, win_lo, win_hi);
     return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(lap):
     hdr = open(os.path.join(ROOT, "include", "lap.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(lap_[a-z_]+)\s*\(", hdr))
-    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_workspace_bytes",
+    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps", "lap_workspace_bytes",
             "lap_validate_trace", "lap_status_string"} <= declared
     lib = lap.load_library()
     for name in declared:
@@ -42,6 +42,7 @@ def test_workspace_sizes(lap):
     assert lap.workspace_bytes(1, 120, 22, 16) >= 16 * 120 * (4 + 8)
     assert lap.workspace_bytes(2, 120, 22) >= 6 * 23 * 8
     assert lap.workspace_bytes(3, 1, 1) > 0
+    assert lap.workspace_bytes(4, 120, 22, 2) > lap.workspace_bytes(4, 120, 22, 1) > lap.workspace_bytes(2, 120, 22)
     assert lap.workspace_bytes(42, 1, 1) == 0
     assert lap.workspace_bytes(1, 120, 22, 32) > lap.workspace_bytes(1, 120, 22, 16)
 
@@ -85,6 +86,19 @@ def test_argument_errors(lap):
     for link in (0.0, -3.0, float("nan"), float("inf"), 1e-9):
         assert lib.lap_score_swaps(C.byref(good), link, 1, None, fake, fake, fake, fake, fake,
                                    fake, 1 << 20, None) == -5
+
+    # selection: NULL outputs, sizes, score kinds, link, workspace
+    kinds = (C.c_uint32 * 2)(3, 0)
+    lims = (C.c_uint64 * 1)(5)
+    sel = lambda **kw: lib.lap_select_swaps(
+        C.byref(good), kw.get("link", 64.0), 1, None, kw.get("kinds", kinds), kw.get("K", 2), kw.get("lims", lims),
+        kw.get("L", 1), kw.get("order", fake), None, fake, fake, kw.get("nsel", fake), fake, fake, fake,
+        kw.get("ws", 1 << 30), None)
+    assert sel(order=None) == -1 and sel(kinds=None) == -1 and sel(lims=None) == -1 and sel(nsel=None) == -1
+    assert sel(K=0) == -2 and sel(K=65) == -2 and sel(L=1025) == -2
+    assert sel(kinds=(C.c_uint32 * 2)(3, 5)) == -4
+    assert sel(link=0.0) == -5
+    assert sel(ws=lap.workspace_bytes(4, 4, 3, 2) - 1) == -3
 
 
 def test_no_cpu_fallback(lap, monkeypatch, tmp_path):
