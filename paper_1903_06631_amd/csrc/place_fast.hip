@@ -73,6 +73,7 @@ template <> struct Life<uint32_t> {
 };
 
 __device__ __forceinline__ uint32_t wave_scan_max32(uint32_t v) { return wave_scan_max_u32(v); }
+__device__ __forceinline__ uint32_t wave_reduce_max32(uint32_t v) { return read_lane(wave_scan_max_u32(v), WAVE - 1); }
 
 // ---------------------------------------------------------------------------
 // preparation: granule shift, lifetime statistics, per-step list layout
@@ -601,6 +602,37 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const LT *lif
     }
 }
 
+// One pass of a multi-step variable over the per-step hole lists of its lifetime [a, f):
+// every thread takes steps a + tid, a + tid + 256, ... and finds the lowest offset >= o at
+// which s granules fit into a hole of that step (binary search on the hole ends, which
+// ascend with the starts, then a short walk); returns the largest such offset over the
+// thread's steps.  Only the sorted part of a list (the holes) is read: blocks still waiting
+// in a list's tail belong to multi-step variables, which the ALL list covers.  The topmost
+// hole of every list is unbounded, so every search ends.
+__device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ L, const uint32_t *__restrict__ lstart,
+                                                   const uint32_t *l_ns, uint32_t a, uint32_t f, uint32_t o,
+                                                   uint32_t s)
+{
+    uint32_t best = o;
+    const uint32_t need = o + s;
+    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE) {
+        const uint64_t *Lt = L + lstart[t];
+        uint32_t lo = 0, hi = max(l_ns[t], 1u) - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            const uint64_t x = Lt[mid];
+            if ((uint32_t)(x >> 32) + (uint32_t)x >= need) hi = mid; else lo = mid + 1;
+        }
+        for (;;) {
+            const uint64_t x = Lt[lo];
+            const uint32_t st = (uint32_t)(x >> 32), from = max(o, st);
+            if (st + (uint32_t)x - from >= s) { best = max(best, from); break; }
+            ++lo;
+        }
+    }
+    return best;
+}
+
 template <class LT>
 __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
@@ -610,6 +642,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     __shared__ uint32_t s_np, s_bc;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
+    __shared__ uint32_t s_sf[PW];
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
     const bool mode1 = A.hdr->mode1 != 0;
@@ -749,6 +782,15 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     }
                     __syncthreads();
                     o = s_bc;
+                    if (mode1) {
+                        // one-step variables are not in ALL: the hole lists of the steps it lives
+                        // through stand for them
+                        uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, o, vs);
+                        c = wave_reduce_max32(c);
+                        if (l == 0) s_sf[wave] = c;
+                        __syncthreads();
+                        o = max(max(s_sf[0], s_sf[1]), max(s_sf[2], s_sf[3]));
+                    }
                     if (o == o1) break;
                 }
                 PROBE_ACC(1, t3); PROBE_T(t4);
@@ -882,14 +924,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         if (one_step && a == t) { pns = nh; pnu = 0; }
                     }
                     fp = max(fp, o + vs);
-                    if (l == 0) {
-                        offs[vv] = (uint64_t)o << sh;
-                        if (multi_left > 0) {
-                            const uint32_t slot = atomicAdd(&s_np, 1u);
-                            p_oe[slot] = pk(o, o + vs);
-                            p_life[slot] = Life<LT>::mk(t, t + 1);
-                        }
-                    }
+                    if (l == 0) offs[vv] = (uint64_t)o << sh;
                 }
                 PROBE_ACC(3, t5);
                 p = q;
