@@ -344,6 +344,20 @@ __device__ __forceinline__ void h_insert(uint64_t *hl, uint32_t n, uint32_t p, u
     lds_sync();
 }
 
+// entries (p, n) move down by one: entry p disappears
+__device__ __forceinline__ void h_delete(uint64_t *hl, uint32_t n, uint32_t p)
+{
+    const int l = lane_id();
+    for (uint32_t lo = p + 1; lo < n; lo += WAVE) {
+        const uint32_t idx = lo + l;
+        uint64_t y = 0;
+        if (idx < n) y = hl[idx];
+        lds_sync();
+        if (idx < n) hl[idx - 1] = y;
+        lds_sync();
+    }
+}
+
 // Remove the block [o, en) from the free ranges: it lies inside exactly one hole.  The list
 // holds nh holes followed by ntail other entries (which move up if a hole is split).  Returns
 // the number of holes afterwards; [lo, hi) is extended to the entries that changed.
@@ -356,6 +370,11 @@ __device__ __forceinline__ uint32_t h_carve(uint64_t *hl, uint32_t nh, uint32_t 
     const uint32_t st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
     lo = min(lo, h);
     lds_sync();
+    if (o == st && en == hend) {         // the hole is used up: it leaves the list
+        h_delete(hl, nh + ntail, h);
+        hi = max(hi, nh + ntail - 1);
+        return nh - 1;
+    }
     if (o == st) {                       // block at the hole's start: the hole shrinks from below
         if (l == 0) hl[h] = pk(en, hend - en);
         lds_sync();
@@ -888,10 +907,16 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         const uint64_t x = hl[h];
                         o = (uint32_t)(x >> 32);
                         lds_sync();
-                        if (l == 0) hl[h] = pk(o + vs, (uint32_t)x - vs);
-                        lds_sync();
                         wb_from = min(wb_from, h);
-                        wb_to = max(wb_to, h + 1);
+                        if ((uint32_t)x == vs) {         // used up: the hole leaves the list
+                            h_delete(hl, cnt, h);
+                            --cnt;
+                            wb_to = max(wb_to, cnt);
+                        } else {
+                            if (l == 0) hl[h] = pk(o + vs, (uint32_t)x - vs);
+                            lds_sync();
+                            wb_to = max(wb_to, h + 1);
+                        }
                     } else {
                         // list too long for the LDS area: same steps directly in global memory
                         uint64_t *Lt = L + A.lstart[t];
