@@ -7,7 +7,10 @@
 // recomputed from the trace on every pass, so only the 4-byte indices move.
 // Descending kinds sort the bitwise complement of the key; stability keeps
 // equal keys in ascending index order.  A pass whose digit is the same for
-// every variable is skipped.
+// every variable is skipped.  The seeded shuffle's keys are distinct and spread
+// over all 64 bits, so only their top 24 (32 for very large N) bits are radix
+// sorted; the few runs of variables that share those bits are then put in order
+// by their full keys, one thread per run.
 #include "lap_dev.h"
 #include "lap_kernels.h"
 
@@ -70,7 +73,8 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     const uint32_t *cur = nullptr;
     uint32_t *dst = perm;
     const uint64_t lt_mask = (1ull << l) - 1ull;
-    for (int pass = 0; pass < 8; ++pass) {
+    const int first_pass = (kind == 4) ? (n <= (1u << 22) ? 5 : 4) : 0;
+    for (int pass = first_pass; pass < 8; ++pass) {
         const int shift = pass * 8;
         for (int k = l; k < 256; k += WAVE) hist[w][k] = 0;
         wave_lds_sync();
@@ -142,6 +146,25 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
         for (uint32_t i = threadIdx.x; i < n; i += SW * WAVE) perm[i] = i;
     } else if (cur != perm) {
         for (uint32_t i = threadIdx.x; i < n; i += SW * WAVE) perm[i] = tmp[i];
+    }
+    if (first_pass == 0) return;
+    // Runs of equal sorted bits: the thread at a run's first rank sorts the run by the full
+    // key (insertion sort; the keys of a seeded order are distinct).  Every entry a run
+    // moves keeps the run's sorted bits, so the neighbours' run tests are not disturbed.
+    __syncthreads();
+    const int pshift = first_pass * 8;
+    for (uint32_t r = threadIdx.x; r < n; r += SW * WAVE) {
+        const uint64_t p0 = mix64(seed, perm[r]) >> pshift;
+        if (r > 0 && (mix64(seed, perm[r - 1]) >> pshift) == p0) continue;       // not a run's first rank
+        uint32_t m = 1;
+        while (r + m < n && (mix64(seed, perm[r + m]) >> pshift) == p0) ++m;
+        for (uint32_t x = 1; x < m; ++x) {
+            const uint32_t vi = perm[r + x];
+            const uint64_t vk = mix64(seed, vi);
+            uint32_t y = x;
+            while (y > 0 && mix64(seed, perm[r + y - 1]) > vk) { perm[r + y] = perm[r + y - 1]; --y; }
+            perm[r + y] = vi;
+        }
     }
 }
 

@@ -153,6 +153,16 @@ def test_plan_pool_shapes(lap, oracle_mod, n, T, B):
     _check_plan(lap, oracle_mod, tr, kinds[-B:], seeds[-B:])
 
 
+def test_plan_pool_seeded_orders_with_equal_leading_key_bits(lap, oracle_mod):
+    # 70 000 variables: about 150 pairs of seeded keys agree in their top 24 bits, the part the
+    # radix sort looks at; the order inside such runs must come from the full keys
+    tr = random_trace(77, 70000, 3000, max_life=3, one_step_frac=0.9)
+    seeds = [5, 1 << 40, 631]
+    keys = np.array([[oracle_mod.mix64(s, i) >> 40 for i in range(tr.n_vars)] for s in seeds[:1]])
+    assert len(np.unique(keys[0])) < tr.n_vars          # there are such runs
+    _check_plan(lap, oracle_mod, tr, [4, 4, 4], seeds)
+
+
 def test_plan_pool_special_cases(lap, oracle_mod):
     kinds, seeds = make_orderings(8)
     # identical lifetimes: blocks stack, footprint = sum of sizes
