@@ -99,12 +99,13 @@ def make_perm(tr, kind: int, seed: int = 0, explicit=None):
     return perm
 
 
-def place(tr, perm):
+def place(tr, perm, best_fit: bool = False):
     lib = _load()
     perm = _c(perm, np.uint32)
     off = np.zeros(tr.n_vars, np.uint64)
     fp = C.c_uint64(0)
-    rc = lib.lapo_place(C.c_uint32(tr.n_vars), _opt(tr.size, np.uint64), _opt(tr.alloc, np.uint32),
+    fn = lib.lapo_place_best if best_fit else lib.lapo_place
+    rc = fn(C.c_uint32(tr.n_vars), _opt(tr.size, np.uint64), _opt(tr.alloc, np.uint32),
                         _opt(tr.free, np.uint32), perm.ctypes.data_as(C.c_void_p),
                         off.ctypes.data_as(C.c_void_p), C.byref(fp))
     if rc:

@@ -26,6 +26,10 @@
  *   lapo_place        : pinned (granule brute force, validity and lower-bound
  *                       invariants of Eq. 2, exhaustive orderings on N<=8
  *                       against an independent exhaustive offset search).
+ *   lapo_place_best   : pinned (granule brute force that lists the free runs of
+ *                       an occupancy bitmap, hand-worked example where it
+ *                       differs from first-fit, validity and Eq. 2 invariants,
+ *                       equality with first-fit when at most one hole fits).
  *   lapo_score_swaps  : DOA/AOA/WDOA pinned (hand-worked example, closed
  *                       forms, sign rule of Section IV-B); the peak-cut score
  *                       is this build's reading of "how much the peak drops",
@@ -257,6 +261,48 @@ int lapo_place(uint32_t n, const uint64_t *size, const uint32_t *alloc, const ui
             if (nb[j].off >= o && nb[j].off - o >= s) break;   /* hole [o, nb.off) fits */
             if (nb[j].end > o) o = nb[j].end;
         }
+        off[v] = o;
+        pa[r] = a; pf[r] = f; ps[r].off = o; ps[r].end = o + s;
+        if (o + s > fp) fp = o + s;
+    }
+    *footprint = fp;
+    free(pa); free(pf); free(ps); free(nb);
+    return LAPO_OK;
+}
+
+/* Section III-C, the other policy: best-fit.  Same walk over the neighbours' blocks, but
+ * every hole is looked at -- the free range below the lowest block and the free ranges between
+ * blocks -- and the SMALLEST one that is large enough is taken (the lowest of several equally
+ * small ones); the block goes to that hole's start.  When no hole fits the block goes above
+ * the topmost neighbour, as with first-fit. */
+int lapo_place_best(uint32_t n, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
+                    const uint32_t *perm, uint64_t *off, uint64_t *footprint)
+{
+    if (!size || !alloc || !free_ || !perm || !off || !footprint) return LAPO_E_NULL;
+    if (n == 0) return LAPO_E_SIZE;
+    uint32_t *pa = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
+    uint32_t *pf = (uint32_t *)malloc((size_t)n * sizeof(uint32_t));
+    span *ps = (span *)malloc((size_t)n * sizeof(span));
+    span *nb = (span *)malloc((size_t)n * sizeof(span));
+    if (!pa || !pf || !ps || !nb) { free(pa); free(pf); free(ps); free(nb); return LAPO_E_NOMEM; }
+    uint64_t fp = 0;
+    for (uint32_t r = 0; r < n; ++r) {
+        const uint32_t v = perm[r];
+        const uint32_t a = alloc[v], f = free_[v];
+        const uint64_t s = size[v];
+        uint32_t m = 0;
+        for (uint32_t j = 0; j < r; ++j)
+            if (pa[j] < f && a < pf[j]) nb[m++] = ps[j];
+        qsort(nb, m, sizeof(span), cmp_span);
+        uint64_t top = 0, best_gap = UINT64_MAX, best_at = 0;
+        for (uint32_t j = 0; j < m; ++j) {
+            if (nb[j].off > top) {                               /* hole [top, nb.off) */
+                const uint64_t gap = nb[j].off - top;
+                if (gap >= s && gap < best_gap) { best_gap = gap; best_at = top; }
+            }
+            if (nb[j].end > top) top = nb[j].end;
+        }
+        const uint64_t o = best_gap != UINT64_MAX ? best_at : top;
         off[v] = o;
         pa[r] = a; pf[r] = f; ps[r].off = o; ps[r].end = o + s;
         if (o + s > fp) fp = o + s;
