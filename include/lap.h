@@ -100,9 +100,16 @@ enum {
     LAP_ORD_EXPLICIT = 5
 };
 
+/* Where a variable goes among the holes between its neighbours' blocks (Section III-C).
+ *   FIT_FIRST  the lowest hole that is large enough (lowest feasible offset)
+ *   FIT_BEST   the smallest hole that is large enough, the lowest of equally small ones (the
+ *              paper's default).  A hole is a free range below the neighbours' highest end.
+ * With both, a variable that fits no hole goes above the neighbours' highest end. */
+enum { LAP_FIT_FIRST = 0, LAP_FIT_BEST = 1 };
+
 typedef struct {
-    uint32_t kind;
-    uint32_t pad;
+    uint32_t kind;  /* LAP_ORD_* */
+    uint32_t fit;   /* LAP_FIT_*; zero-initialised descriptors plan first-fit */
     uint64_t seed;
 } lap_ordering;
 
@@ -126,7 +133,7 @@ size_t lap_workspace_bytes(int which_call, uint32_t n_vars, uint32_t n_steps, ui
 int lap_load_profile(const lap_trace *trace, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
                      void *ws, size_t ws_bytes, void *hip_stream);
 
-/* Section III-C with first-fit, for B orderings at once.
+/* Section III-C, for B orderings (each with its own fit policy) at once.
  *   ords           [B] host
  *   best_offsets   [N]   out: byte offset of every variable under the best ordering
  *   best_footprint [1]   out: pool size of the best ordering (max offset + size)

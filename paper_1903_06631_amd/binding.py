@@ -30,7 +30,7 @@ class _Trace(C.Structure):
 
 
 class _Ordering(C.Structure):
-    _fields_ = [("kind", C.c_uint32), ("pad", C.c_uint32), ("seed", C.c_uint64)]
+    _fields_ = [("kind", C.c_uint32), ("fit", C.c_uint32), ("seed", C.c_uint64)]
 
 
 def lib_path() -> str:
@@ -170,17 +170,17 @@ def load_profile(dt: DeviceTrace, sync: bool = True):
     return dict(load=load, peak=peak, t_peak=t_peak)
 
 
-def make_orderings(kinds: Sequence[int], seeds: Sequence[int]):
+def make_orderings(kinds: Sequence[int], seeds: Sequence[int], fits: Optional[Sequence[int]] = None):
     arr = (_Ordering * len(kinds))()
     for b, (k, s) in enumerate(zip(kinds, seeds)):
         arr[b].kind = int(k)
-        arr[b].pad = 0
+        arr[b].fit = 0 if fits is None else int(fits[b])
         arr[b].seed = int(s)
     return arr
 
 
 def plan_pool(dt: DeviceTrace, kinds: Sequence[int], seeds: Sequence[int], *, explicit: Optional[dict] = None,
-              want_all: bool = True, want_footprints: bool = True, sync: bool = True, out: Optional[dict] = None):
+              fits: Optional[Sequence[int]] = None, want_all: bool = True, want_footprints: bool = True, sync: bool = True, out: Optional[dict] = None):
     """lap_plan_pool.  explicit: {ordering index: int32 device tensor with a permutation} for kind 5.
 
     Returns device tensors: best_offsets[N], best_footprint[1], best_ordering[1],
@@ -193,7 +193,7 @@ def plan_pool(dt: DeviceTrace, kinds: Sequence[int], seeds: Sequence[int], *, ex
         for b, t in explicit.items():
             assert t.dtype == torch.int32 and t.is_contiguous() and t.numel() == n
             seeds[b] = t.data_ptr()
-    ords = make_orderings(kinds, seeds)
+    ords = make_orderings(kinds, seeds, fits)
     if out is None:
         out = dict(
             best_offsets=torch.empty(n, dtype=torch.int64, device=dt.device),

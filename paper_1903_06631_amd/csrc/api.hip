@@ -49,7 +49,7 @@ size_t ws_plan(uint32_t n, uint32_t T, uint32_t B)
 {
     const size_t bn = (size_t)B * n;
     return up(sizeof(lap::PlanHeader)) + 2 * up(((size_t)T + 2) * 4)   // header, step counts, list starts
-           + up((size_t)B * 4) + up((size_t)B * 8)                    // kinds, seeds
+           + 2 * up((size_t)B * 4) + up((size_t)B * 8)                // kinds, fit policies, seeds
            + 2 * up(bn * 4)                                            // perm, sort scratch
            + up((size_t)B * 8)                                         // footprints
            + up(bn * 8)                                                // offsets of every ordering
@@ -215,11 +215,14 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     if (rc) return rc;
     if (!ords || !best_offsets || !best_footprint || !best_ordering) return LAP_E_NULL;
     if (B == 0) return LAP_E_SIZE;
-    bool any_explicit = false;
+    bool any_explicit = false, any_best = false, any_first = false;
     for (uint32_t b = 0; b < B; ++b) {
         any_explicit |= ords[b].kind == LAP_ORD_EXPLICIT;
         if (ords[b].kind > LAP_ORD_EXPLICIT) return LAP_E_ORDERING;
         if (ords[b].kind == LAP_ORD_EXPLICIT && ords[b].seed == 0) return LAP_E_ORDERING;
+        if (ords[b].fit > LAP_FIT_BEST) return LAP_E_ORDERING;
+        any_best |= ords[b].fit == LAP_FIT_BEST;
+        any_first |= ords[b].fit == LAP_FIT_FIRST;
     }
     const uint32_t n = tr->n_vars, T = tr->n_steps;
     if ((uint64_t)n * lap::PLAN_CL >= (1ull << 32)) return LAP_E_SIZE;
@@ -232,6 +235,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint32_t *cntd = c.take<uint32_t>((size_t)T + 2);
     uint32_t *lstart = c.take<uint32_t>((size_t)T + 2);
     uint32_t *kinds = c.take<uint32_t>(B);
+    uint32_t *fits = c.take<uint32_t>(B);
     uint64_t *seeds = c.take<uint64_t>(B);
     uint32_t *perm = c.take<uint32_t>(bn);
     uint32_t *tmp = c.take<uint32_t>(bn);
@@ -258,12 +262,14 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     // The descriptors are split into two arrays and copied from pageable host memory: the
     // runtime stages such a copy before it returns.  The staging vectors live for the
     // thread's lifetime all the same.
-    static thread_local std::vector<uint32_t> hk;
+    static thread_local std::vector<uint32_t> hk, hf;
     static thread_local std::vector<uint64_t> hs;
     hk.resize(B);
+    hf.resize(B);
     hs.resize(B);
-    for (uint32_t b = 0; b < B; ++b) { hk[b] = ords[b].kind; hs[b] = ords[b].seed; }
+    for (uint32_t b = 0; b < B; ++b) { hk[b] = ords[b].kind; hf[b] = ords[b].fit; hs[b] = ords[b].seed; }
     LAP_HIP(hipMemcpyAsync(kinds, hk.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(hipMemcpyAsync(fits, hf.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
     LAP_HIP(hipMemcpyAsync(seeds, hs.data(), (size_t)B * 8, hipMemcpyHostToDevice, st));
 
     uint64_t *fps = footprints ? footprints : fps_ws;
@@ -281,9 +287,10 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_nu, ((size_t)B * T + 1) / 2, 0, st));
     {
         ProfScope p(LAP_K_PLACE, st);
-        LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, hdr, lstart, f_oe, f_life, f_oe2,
+        LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, fits, any_first, any_best, hdr,
+                                       lstart, f_oe, f_life, f_oe2,
                                        f_life2, f_roe, f_rlife, f_roe2, f_rlife2, f_L, capL, l_ns, l_nu, offs, fps, st));
-        LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, hdr, m_off, m_end, m_life, offs,
+        LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, fits, hdr, m_off, m_end, m_life, offs,
                                        fps, st));
     }
     LAP_HIP(lap::launch_select(n, B, fps, offs, best_footprint, best_ordering, best_offsets, st));

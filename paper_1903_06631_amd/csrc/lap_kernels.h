@@ -31,14 +31,16 @@ hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const 
 hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
                             const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st);
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
-                             const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr,
+                             const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,
+                             bool any_best, const PlanHeader *hdr,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,
                              uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st);
 constexpr uint32_t PLAN_REC = 4096;   // entries of the sorted "recent" list per ordering
 hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc,
-                             const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr, uint64_t *m_off,
+                             const uint32_t *free_, const uint32_t *perm, const uint32_t *fits,
+                             const PlanHeader *hdr, uint64_t *m_off,
                              uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st);
 hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs, uint64_t *best_fp,
                          uint32_t *best_idx, uint64_t *best_offsets, hipStream_t st);

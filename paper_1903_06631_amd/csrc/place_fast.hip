@@ -311,6 +311,24 @@ __device__ __forceinline__ uint32_t h_first_fit(const uint64_t *hl, uint32_t nh,
     return nh - 1;
 }
 
+// Best-fit: index of the smallest of the nh-1 bounded holes with size >= s (the lowest of
+// equally small ones); the unbounded top hole, the last entry, when none fits
+__device__ __forceinline__ uint32_t h_best_fit(const uint64_t *hl, uint32_t nh, uint32_t s)
+{
+    const int l = lane_id();
+    uint64_t best = U64_MAX;
+    for (uint32_t base = 0; base + 1 < nh; base += WAVE) {
+        const uint32_t idx = base + l;
+        if (idx + 1 < nh) {
+            const uint32_t z = (uint32_t)hl[idx];
+            if (z >= s) best = umin64(best, ((uint64_t)z << 32) | idx);
+        }
+    }
+#pragma unroll
+    for (int m = WAVE / 2; m > 0; m >>= 1) best = umin64(best, shfl_xor64(best, m));
+    return best == U64_MAX ? nh - 1 : (uint32_t)best;
+}
+
 // index of the hole that contains address o (start <= o < start + size)
 __device__ __forceinline__ uint32_t h_find_hole(const uint64_t *hl, uint32_t nh, uint32_t o)
 {
@@ -398,6 +416,7 @@ struct FastArgs {
     const uint64_t *size;
     const uint32_t *alloc, *free_;
     const uint32_t *perm;        // [B][n]
+    const uint32_t *fits;        // [B] 0 = first-fit, 1 = best-fit
     const PlanHeader *hdr;
     const uint32_t *lstart;      // [T+1]
     uint64_t *m_oe[2];           // [B][n] x 2  ALL main list, two buffers (merges ping-pong)
@@ -652,7 +671,61 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
     return best;
 }
 
+// Best-fit needs the size of the hole that starts at a feasible offset p.  In the hole lists:
+// every thread takes its steps of [a, f), finds the hole that holds p (the first whose end lies
+// above p) and returns the lowest such end over its steps (0xFFFFFFFF = unbounded).
+__device__ __forceinline__ uint32_t steps_extent_pass(const uint64_t *__restrict__ L,
+                                                      const uint32_t *__restrict__ lstart, const uint32_t *l_ns,
+                                                      uint32_t a, uint32_t f, uint32_t p)
+{
+    uint32_t e = NONE32;
+    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE) {
+        const uint64_t *Lt = L + lstart[t];
+        uint32_t lo = 0, hi = max(l_ns[t], 1u) - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            const uint64_t x = Lt[mid];
+            if ((uint32_t)(x >> 32) + (uint32_t)x > p) hi = mid; else lo = mid + 1;
+        }
+        const uint64_t x = Lt[lo];
+        e = min(e, (uint32_t)(x >> 32) + (uint32_t)x);
+    }
+    return e;
+}
+
+// In a sorted list: offset of the first entry at or after index `from` that overlaps [a, f) in
+// time, 0xFFFFFFFF if there is none.  All waves call it with the same arguments.
 template <class LT>
+__device__ __forceinline__ uint32_t coop_next_overlap(const uint64_t *oe, const LT *life, uint32_t n, uint32_t from,
+                                                      uint32_t a, uint32_t f, uint32_t wave, uint32_t *s_x)
+{
+    const int l = lane_id();
+    for (uint32_t base = from; base < n; base += PW * WAVE) {
+        const uint32_t idx = base + wave * WAVE + l;
+        bool hit = false;
+        uint32_t off = 0;
+        if (idx < n) {
+            const uint64_t x = oe[idx];
+            const LT lf = life[idx];
+            hit = Life<LT>::a(lf) < f && a < Life<LT>::f(lf);
+            off = (uint32_t)(x >> 32);
+        }
+        const uint64_t m = ballot(hit);
+        uint32_t first = NONE32;
+        if (m) first = read_lane(off, __ffsll((unsigned long long)m) - 1);
+        if (l == 0) s_x[wave] = first;
+        __syncthreads();
+        uint32_t r = NONE32;
+#pragma unroll
+        for (int w = PW - 1; w >= 0; --w)
+            if (s_x[w] != NONE32) r = s_x[w];         // the lowest wave's chunk comes first in the list
+        __syncthreads();
+        if (r != NONE32) return r;
+    }
+    return NONE32;
+}
+
+template <class LT, bool BEST>
 __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
     __shared__ uint64_t p_oe[PEND];
@@ -664,9 +737,10 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     __shared__ uint32_t s_sf[PW];
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
+    const uint32_t b = blockIdx.x;
+    if ((A.fits[b] != 0) != BEST) return;   // the other instantiation handles this ordering
     const bool mode1 = A.hdr->mode1 != 0;
     const uint32_t sh = A.hdr->shift;
-    const uint32_t b = blockIdx.x;
     const int l = lane_id();
     const uint32_t wave = threadIdx.x / WAVE;
 
@@ -789,28 +863,72 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     np = 0;
                 }
                 PROBE_ACC(0, t2); PROBE_T(t3);
-                uint32_t o = 0, cm = 0, cr = 0;
-                for (;;) {
-                    const uint32_t o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax, s_hq,
-                                                   s_hans);
-                    uint32_t o2 = o1;
-                    if (nr) o2 = coop_sweep(r_oe[rb], r_life[rb], nr, cr, o1, vs, va, vf, wave, s_cmax, s_hq, s_hans);
-                    if (wave == 0) {
-                        if (np) o2 = fit_unsorted(p_oe, p_life, np, o2, vs, va, vf);
-                        if (l == 0) s_bc = o2;
+                uint32_t cm = 0, cr = 0;
+                // lowest offset >= `from` that is free of every neighbour: the sorted lists, the
+                // pending entries and (with per-step lists) the hole lists are asked in turn until
+                // none of them moves the candidate
+                auto fit_from = [&](uint32_t from) -> uint32_t {
+                    uint32_t o = from;
+                    for (;;) {
+                        const uint32_t o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax,
+                                                       s_hq, s_hans);
+                        uint32_t o2 = o1;
+                        if (nr)
+                            o2 = coop_sweep(r_oe[rb], r_life[rb], nr, cr, o1, vs, va, vf, wave, s_cmax, s_hq, s_hans);
+                        if (wave == 0) {
+                            if (np) o2 = fit_unsorted(p_oe, p_life, np, o2, vs, va, vf);
+                            if (l == 0) s_bc = o2;
+                        }
+                        __syncthreads();
+                        o = s_bc;
+                        if (mode1) {
+                            // one-step variables are not in ALL: the hole lists of the steps it lives
+                            // through stand for them
+                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, o, vs);
+                            c = wave_reduce_max32(c);
+                            if (l == 0) s_sf[wave] = c;
+                            __syncthreads();
+                            o = max(max(s_sf[0], s_sf[1]), max(s_sf[2], s_sf[3]));
+                        }
+                        if (o == o1) return o;
                     }
-                    __syncthreads();
-                    o = s_bc;
-                    if (mode1) {
-                        // one-step variables are not in ALL: the hole lists of the steps it lives
-                        // through stand for them
-                        uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, o, vs);
-                        c = wave_reduce_max32(c);
+                };
+                uint32_t o;
+                if constexpr (!BEST) {
+                    o = fit_from(0);
+                } else {
+                    // Best-fit: the feasible offsets found in ascending order are the starts of the
+                    // holes that fit; a hole ends at the lowest start of a neighbour above it.  The
+                    // smallest such hole wins, the first of equally small ones; an exact fit ends the
+                    // search; with no neighbour above, the offset is the top of the neighbours.
+                    uint32_t best_gap = NONE32, best_off = 0, from = 0;
+                    for (;;) {
+                        const uint32_t pp = fit_from(from);
+                        __syncthreads();
+                        // the sweeps stopped at the first entry above the hole: the next neighbour is
+                        // the first time-overlapping entry from there on
+                        uint32_t e = coop_next_overlap(m_oe[mb], m_life[mb], nm, cm, va, vf, wave, s_hq);
+                        e = min(e, coop_next_overlap(r_oe[rb], r_life[rb], nr, cr, va, vf, wave, s_hq));
+                        uint32_t c = NONE32;
+                        if (wave == 0) {
+                            for (uint32_t idx = l; idx < np; idx += WAVE) {
+                                const LT lf = p_life[idx];
+                                const uint32_t po = (uint32_t)(p_oe[idx] >> 32);
+                                if (Life<LT>::a(lf) < vf && va < Life<LT>::f(lf) && po >= pp) c = min(c, po);
+                            }
+                        }
+                        if (mode1) c = min(c, steps_extent_pass(L, A.lstart, l_ns, va, vf, pp));
+                        c = ~wave_reduce_max32(~c);
                         if (l == 0) s_sf[wave] = c;
                         __syncthreads();
-                        o = max(max(s_sf[0], s_sf[1]), max(s_sf[2], s_sf[3]));
+                        e = min(e, min(min(s_sf[0], s_sf[1]), min(s_sf[2], s_sf[3])));
+                        __syncthreads();
+                        if (e == NONE32) { o = best_gap == NONE32 ? pp : best_off; break; }
+                        const uint32_t gap = e - pp;
+                        if (gap < best_gap) { best_gap = gap; best_off = pp; }
+                        if (gap == vs) { o = pp; break; }
+                        from = e;
                     }
-                    if (o == o1) break;
                 }
                 PROBE_ACC(1, t3); PROBE_T(t4);
                 const uint32_t en = o + vs;
@@ -903,7 +1021,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         }
                     }
                     if (cur_t == t) {
-                        const uint32_t h = h_first_fit(hl, cnt, vs);
+                        const uint32_t h = BEST ? h_best_fit(hl, cnt, vs) : h_first_fit(hl, cnt, vs);
                         const uint64_t x = hl[h];
                         o = (uint32_t)(x >> 32);
                         lds_sync();
@@ -940,7 +1058,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                             }
                             wave_fence();
                         }
-                        const uint32_t h = mem_first_fit(Lt, nh, vs);
+                        const uint32_t h = BEST ? h_best_fit(Lt, nh, vs) : mem_first_fit(Lt, nh, vs);
                         const uint64_t x = Lt[h];
                         o = (uint32_t)(x >> 32);
                         wave_fence();
@@ -992,20 +1110,25 @@ hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const 
 }
 
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
-                             const uint32_t *free_, const uint32_t *perm, const PlanHeader *hdr,
+                             const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,
+                             bool any_best, const PlanHeader *hdr,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,
                              uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st)
 {
-    FastArgs A{n, T, size, alloc, free_, perm, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, {r_oe, r_oe2}, {r_life, r_life2},
+    FastArgs A{n, T, size, alloc, free_, perm, fits, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, {r_oe, r_oe2}, {r_life, r_life2},
                L, l_ns,
                l_nu, capL,
                offs, fps, g_probe};
-    if (T <= 0xFFFFu)
-        hipLaunchKernelGGL(k_place_fast<uint32_t>, dim3(B), dim3(PW * WAVE), 0, st, A);
-    else
-        hipLaunchKernelGGL(k_place_fast<uint64_t>, dim3(B), dim3(PW * WAVE), 0, st, A);
+    // each instantiation leaves the orderings of the other policy alone
+    if (T <= 0xFFFFu) {
+        if (any_first) hipLaunchKernelGGL((k_place_fast<uint32_t, false>), dim3(B), dim3(PW * WAVE), 0, st, A);
+        if (any_best) hipLaunchKernelGGL((k_place_fast<uint32_t, true>), dim3(B), dim3(PW * WAVE), 0, st, A);
+    } else {
+        if (any_first) hipLaunchKernelGGL((k_place_fast<uint64_t, false>), dim3(B), dim3(PW * WAVE), 0, st, A);
+        if (any_best) hipLaunchKernelGGL((k_place_fast<uint64_t, true>), dim3(B), dim3(PW * WAVE), 0, st, A);
+    }
     return hipGetLastError();
 }
 

@@ -60,6 +60,26 @@ __device__ __forceinline__ uint64_t sweep(const uint64_t *off, const uint64_t *e
     }
 }
 
+// offset of the first entry at or after index `from` that overlaps [a, f) in time, 2^64-1 if none
+__device__ __forceinline__ uint64_t next_overlap(const uint64_t *off, const uint64_t *life, uint32_t n,
+                                                 uint32_t from, uint32_t a, uint32_t f)
+{
+    const int l = lane_id();
+    for (uint32_t base = from; base < n; base += WAVE) {
+        const uint32_t idx = base + l;
+        bool hit = false;
+        uint64_t o = 0;
+        if (idx < n) {
+            const uint64_t lf = life[idx];
+            hit = (uint32_t)(lf >> 32) < f && a < (uint32_t)lf;
+            o = off[idx];
+        }
+        const uint64_t m = ballot(hit);
+        if (m) return shfl64(o, __ffsll((unsigned long long)m) - 1);
+    }
+    return U64_MAX;
+}
+
 // number of entries of a sorted list with off < key (all lanes get the result)
 __device__ __forceinline__ uint32_t count_below(const uint64_t *off, uint32_t n, uint64_t key)
 {
@@ -154,6 +174,7 @@ __global__ __launch_bounds__(64) void k_place_wide(uint32_t n, const uint64_t *_
                                               const uint32_t *__restrict__ alloc,
                                               const uint32_t *__restrict__ free_,
                                               const uint32_t *__restrict__ perm_all,
+                                              const uint32_t *__restrict__ fits,
                                               const PlanHeader *__restrict__ hdr,
                                               uint64_t *m_off_all, uint64_t *m_end_all, uint64_t *m_life_all,
                                               uint64_t *__restrict__ offs_all, uint64_t *__restrict__ fps)
@@ -162,6 +183,7 @@ __global__ __launch_bounds__(64) void k_place_wide(uint32_t n, const uint64_t *_
     if (hdr->fast) return;                 // the 32-bit granule kernel handles this trace
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
+    const bool best_fit = fits[b] != 0;
     const uint32_t *perm = perm_all + (size_t)b * n;
     uint64_t *m_off = m_off_all + (size_t)b * n;
     uint64_t *m_end = m_end_all + (size_t)b * n;
@@ -177,11 +199,26 @@ __global__ __launch_bounds__(64) void k_place_wide(uint32_t n, const uint64_t *_
 
         uint64_t o = 0;
         uint32_t cm = 0, cr = 0;
+        uint64_t best_gap = U64_MAX, best_off = 0;
         for (;;) {
-            const uint64_t o1 = sweep(m_off, m_end, m_life, nm, cm, o, s, a, f);
-            const uint64_t o2 = nr ? sweep(r_off, r_end, r_life, nr, cr, o1, s, a, f) : o1;
-            o = o2;
-            if (o2 == o1) break;
+            // lowest feasible offset >= o
+            for (;;) {
+                const uint64_t o1 = sweep(m_off, m_end, m_life, nm, cm, o, s, a, f);
+                const uint64_t o2 = nr ? sweep(r_off, r_end, r_life, nr, cr, o1, s, a, f) : o1;
+                o = o2;
+                if (o2 == o1) break;
+            }
+            if (!best_fit) break;
+            // best-fit: o starts a hole that fits; it ends at the next neighbour above (the sweeps
+            // stopped at the first entry above the hole).  Smallest hole wins, the first of equals;
+            // an exact fit ends the search; no neighbour above: o is the top of the neighbours.
+            const uint64_t e = umin64(next_overlap(m_off, m_life, nm, cm, a, f),
+                                      next_overlap(r_off, r_life, nr, cr, a, f));
+            if (e == U64_MAX) { if (best_gap != U64_MAX) o = best_off; break; }
+            const uint64_t gap = e - o;
+            if (gap < best_gap) { best_gap = gap; best_off = o; }
+            if (gap == s) break;
+            o = e;
         }
 
         if (l == 0) offs[v] = o;
@@ -236,11 +273,11 @@ __global__ __launch_bounds__(256) void k_copy_best(uint32_t n, const uint64_t *_
 }
 
 hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
-                        const uint32_t *perm, const PlanHeader *hdr, uint64_t *m_off, uint64_t *m_end,
-                        uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st)
+                        const uint32_t *perm, const uint32_t *fits, const PlanHeader *hdr, uint64_t *m_off,
+                        uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_place_wide, dim3(B), dim3(WAVE), 0, st, n, size, alloc, free_, perm, hdr, m_off, m_end,
-                       m_life, offs, fps);
+    hipLaunchKernelGGL(k_place_wide, dim3(B), dim3(WAVE), 0, st, n, size, alloc, free_, perm, fits, hdr, m_off,
+                       m_end, m_life, offs, fps);
     return hipGetLastError();
 }
 

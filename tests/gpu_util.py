@@ -11,14 +11,14 @@ def u64(t):
     return t.cpu().numpy().view(np.uint64)
 
 
-def oracle_all_orderings(oracle, tr, kinds, seeds, explicit=None, which=None):
+def oracle_all_orderings(oracle, tr, kinds, seeds, explicit=None, which=None, fits=None):
     """Oracle offsets/footprints for the given orderings (ctypes releases the GIL)."""
     idx = list(range(len(kinds))) if which is None else list(which)
 
     def one(b):
         ex = None if not explicit or b not in explicit else explicit[b]
         perm = oracle.make_perm(tr, int(kinds[b]), int(seeds[b]), explicit=ex)
-        off, fp = oracle.place(tr, perm)
+        off, fp = oracle.place(tr, perm, best_fit=bool(fits[b]) if fits is not None else False)
         return b, perm, off, fp
 
     with ThreadPoolExecutor(WORKERS) as ex:

@@ -82,6 +82,9 @@ def test_argument_errors(lap):
     assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -4
     ords[1].kind, ords[1].seed = 5, 0
     assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -4
+    ords[1].kind, ords[1].fit = 4, 2        # unknown fit policy
+    assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -4
+    ords[1].fit = 0
     # link
     for link in (0.0, -3.0, float("nan"), float("inf"), 1e-9):
         assert lib.lap_score_swaps(C.byref(good), link, 1, None, fake, fake, fake, fake, fake,

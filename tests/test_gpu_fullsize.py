@@ -58,6 +58,29 @@ def test_full_size_plan(lap, oracle_mod, cfg, sample, step_stride):
         assert _neighbours_disjoint(tr, u64(all_off[b]), steps), f"cfg {cfg} ordering {b}"
 
 
+def test_full_size_best_fit(lap, oracle_mod):
+    """Config 5 with every ordering planned best-fit: sampled orderings against the oracle, the
+    invariants on all of them."""
+    tr = make_config(5)
+    B = tr.meta["B"]
+    kinds, seeds = make_orderings(B)
+    dt = lap.DeviceTrace(tr)
+    got = lap.plan_pool(dt, kinds, seeds, fits=[1] * B)
+    fps = u64(got["footprints"])
+    all_off = got["all_offsets"]
+    sample = [0, 3, 4, 700]
+    ref = oracle_all_orderings(oracle_mod, tr, kinds, seeds, which=sample, fits=[1] * B)
+    for b, (_, off, fp) in ref.items():
+        assert np.array_equal(u64(all_off[b]), off), f"ordering {b}"
+        assert fps[b] == fp
+    _, peak, _ = oracle_mod.load_profile(tr)
+    top = (all_off + dt.size[None, :]).max(dim=1).values
+    assert np.array_equal(u64(top), fps) and (fps >= peak).all()
+    best = int(got["best_ordering"].item())
+    for b in (best, 9, B - 1):
+        assert _neighbours_disjoint(tr, u64(all_off[b]), range(tr.n_steps)), f"ordering {b}"
+
+
 def test_full_size_load_and_scores(lap, oracle_mod):
     tr = make_config(4)
     dt = lap.DeviceTrace(tr)

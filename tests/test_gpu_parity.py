@@ -54,15 +54,15 @@ def test_load_profile_peak_ties_and_extremes(lap, oracle_mod):
     _check_load(lap, oracle_mod, tr)
 
 
-def _check_plan(lap, oracle, tr, kinds, seeds, explicit_np=None, which=None):
+def _check_plan(lap, oracle, tr, kinds, seeds, explicit_np=None, which=None, fits=None):
     import torch
     dt = lap.DeviceTrace(tr)
     explicit = None
     if explicit_np:
         explicit = {b: torch.from_numpy(p.astype(np.uint32).view(np.int32)).to(dt.device)
                     for b, p in explicit_np.items()}
-    got = lap.plan_pool(dt, kinds, seeds, explicit=explicit)
-    ref = oracle_all_orderings(oracle, tr, kinds, seeds, explicit_np, which)
+    got = lap.plan_pool(dt, kinds, seeds, explicit=explicit, fits=fits)
+    ref = oracle_all_orderings(oracle, tr, kinds, seeds, explicit_np, which, fits)
     all_off = u64(got["all_offsets"])
     fps = u64(got["footprints"])
     for b, (_, off, fp) in ref.items():
@@ -161,6 +161,62 @@ def test_plan_pool_seeded_orders_with_equal_leading_key_bits(lap, oracle_mod):
     keys = np.array([[oracle_mod.mix64(s, i) >> 40 for i in range(tr.n_vars)] for s in seeds[:1]])
     assert len(np.unique(keys[0])) < tr.n_vars          # there are such runs
     _check_plan(lap, oracle_mod, tr, [4, 4, 4], seeds)
+
+
+def _mixed(B):
+    """first-fit and best-fit orderings side by side, all six kinds of order"""
+    kinds = [b % 5 for b in range(B)]
+    seeds = [631 + b for b in range(B)]
+    fits = [(b // 5 + b) % 2 for b in range(B)]
+    return kinds, seeds, fits
+
+
+def test_best_fit_golden(lap, oracle_mod):
+    from helpers import read_golden
+    g = read_golden("e4_best_fit.txt")
+    tr = mk_trace([int(x) * 512 for x in g["size"][0]], g["alloc"][0], g["free"][0], T=3)
+    import torch
+    ident = torch.arange(9, dtype=torch.int32, device="cuda")
+    dt = lap.DeviceTrace(tr)
+    got = lap.plan_pool(dt, [5, 5], [0, 0], explicit={0: ident, 1: ident}, fits=[0, 1])
+    off = u64(got["all_offsets"]) // 512
+    assert off[0].tolist() == [int(x) for x in g["first_fit"][0]]
+    assert off[1].tolist() == [int(x) for x in g["best_fit"][0]]
+    assert u64(got["footprints"]).tolist() == [14 * 512, 12 * 512] and int(got["best_ordering"].item()) == 1
+
+
+@pytest.mark.parametrize("seed,n,T", [(0, 1, 1), (1, 2, 2), (2, 64, 5), (3, 65, 9), (4, 300, 12), (5, 511, 30),
+                                      (6, 1000, 64), (7, 2500, 200), (8, 4097, 33)])
+def test_best_fit_random(lap, oracle_mod, seed, n, T):
+    tr = random_trace(1200 + seed, n, T)
+    kinds, seeds, fits = _mixed(20)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds, fits=fits)
+
+
+@pytest.mark.parametrize("seed,n,T,frac,max_life", [
+    (0, 3000, 40, 0.9, 6), (1, 8000, 100, 0.95, 30), (2, 20000, 64, 0.98, 64), (3, 6000, 500, 0.8, 4),
+    (4, 5000, 12, 0.99, 12), (5, 9000, 70000, 0.9, 3)])
+def test_best_fit_per_step_lists(lap, oracle_mod, seed, n, T, frac, max_life):
+    """mostly one-step variables (hole lists in use), a few long-lived ones that walk the holes"""
+    tr = random_trace(1300 + seed, n, T, max_life=max_life, one_step_frac=frac)
+    kinds, seeds, fits = _mixed(10)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds, fits=fits)
+
+
+def test_best_fit_64bit_offsets(lap, oracle_mod):
+    tr = random_trace(1400, 700, 20, granule=1, max_life=10)
+    tr.size = tr.size * np.uint64(1 << 20) + np.uint64(1)        # odd sizes: the 64-bit kernel runs
+    assert int(tr.size.sum()) >= 1 << 32
+    kinds, seeds, fits = _mixed(10)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds, fits=fits)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_best_fit_configs(lap, oracle_mod, cfg):
+    tr = make_config(cfg)
+    kinds, seeds = make_orderings(16)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds, fits=[1] * 16)
+    _check_plan(lap, oracle_mod, tr, kinds, seeds, fits=[b % 2 for b in range(16)])
 
 
 def test_plan_pool_special_cases(lap, oracle_mod):
