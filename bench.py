@@ -39,6 +39,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stress", action="store_true",
                     help="skip the load-profile run on the 2 GiB time-tiled trace")
+    ap.add_argument("--no-extras", action="store_true", help="skip the best-fit and selection legs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -134,6 +135,33 @@ def main() -> int:
         cpu = dict(value=n / c_s, unit="placements/s", cores=1, kind="oracle",
                    sample=f"first-fit placement of ordering 0 (size-descending), all {n} variables, {c_s:.1f} s")
 
+    # The rows built beyond the timed path (never part of `value`): the same orderings planned
+    # best-fit, and the selection walk for all five priority scores down to a sweep of limits.
+    extra = None
+    if not args.no_extras:
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        bf = lap.plan_pool(dt, kinds, seeds, want_all=False, fits=[1] * B)
+        bf_s = time.perf_counter() - c0
+        bf_ms = lap.profile_last_ms(lap.K_PLACE)
+        bfps = u64(bf["footprints"])
+        limits = [peak * q // 20 for q in range(21)]
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        sel = lap.select_swaps(dt, tr.meta["link_GBps"], tr.meta["min_bytes"], [0, 1, 2, 3, 4], limits,
+                               load=lp["load"])
+        sel_s = time.perf_counter() - c0
+        extra = dict(best_fit=dict(call_ms=1e3 * bf_s, kernel_ms=bf_ms, placements_per_s=B * n / bf_s,
+                                   footprint_over_peak=int(u64(bf["best_footprint"])[0]) / peak,
+                                   footprint_over_peak_fixed_orders=[float(x) / peak for x in bfps[:4]],
+                                   mean_footprint_over_first_fit=float(np.mean(bfps.astype(np.float64) /
+                                                                               fps.astype(np.float64)))),
+                     select_swaps=dict(call_ms=1e3 * sel_s, kernel_ms=lap.profile_last_ms(lap.K_SELECT),
+                                       score_kinds=5, limits=len(limits), candidates=int(sel["n_cand"].item()),
+                                       load_min_over_peak=int(u64(sel["load_min"])[0]) / peak,
+                                       lowest_peak_over_peak=int(u64(sel["peak_after"])[3, 0]) / peak))
+        lap.plan_pool(dt, kinds[:1], seeds[:1], want_all=False)      # leave the profile slots on first-fit
+
     # The load-profile kernel on the largest BASELINE trace moves 3.2 MB (launch-latency bound), so
     # its HBM fraction is also measured on the same trace repeated along time until the SoA is ~2 GiB.
     lp_small_ms = lap.profile_last_ms(lap.K_LOAD_SCATTER)
@@ -169,7 +197,7 @@ def main() -> int:
                    "link_GBps": tr.meta["link_GBps"], "trace_bytes": dt.nbytes(), "upload_ms": 1e3 * upload_s},
         "footprint_over_peak": best_fp / peak, "best_ordering": int(out["best_ordering"].item()),
         "footprint_over_peak_fixed_orders": [float(x) / peak for x in fps[:4]],
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "beyond_the_timed_path": extra,
         "load_profile": {"kernel_ms_on_workload": lp_small_ms, "stress": stress},
     }
     print(json.dumps(line))

@@ -11,8 +11,9 @@
  *   lap_plan_pool     SmartPool placement (Section III-C): variables taken in
  *                     a heuristic order, each put at the lowest address that
  *                     none of its already-placed, time-overlapping neighbours
- *                     uses (first-fit); many orders evaluated in parallel and
- *                     the smallest footprint kept.
+ *                     uses (first-fit), or in the smallest hole between them
+ *                     that fits (best-fit); many orders evaluated in parallel
+ *                     and the smallest footprint kept.
  *   lap_score_swaps   AutoSwap candidate filter and priority scores (Section
  *                     IV-A, IV-B): DOA, AOA, WDOA, and the drop of the peak
  *                     load when the variable is away for its idle gap.
