@@ -91,14 +91,18 @@ typedef struct {
  *   SEEDED      ascending splitmix64 output of (seed + (i+1) * 0x9E3779B97F4A7C15)
  *   EXPLICIT    seed holds a device pointer to a u32[N] permutation
  *               (placement rank -> variable index).  An array that is not a
- *               permutation of 0..N-1 is replaced by the identity order. */
+ *               permutation of 0..N-1 is replaced by the identity order.
+ *   CLASS_SEEDED  seeded shuffle inside size classes: class = floor(log2 size), larger
+ *               classes first, ascending SEEDED key within a class -- random orders that
+ *               stay close to the paper's largest-first order */
 enum {
     LAP_ORD_SIZE_DESC = 0,
     LAP_ORD_LIFE_DESC = 1,
     LAP_ORD_AREA_DESC = 2,
     LAP_ORD_ALLOC_ASC = 3,
     LAP_ORD_SEEDED = 4,
-    LAP_ORD_EXPLICIT = 5
+    LAP_ORD_EXPLICIT = 5,
+    LAP_ORD_CLASS_SEEDED = 6
 };
 
 /* Where a variable goes among the holes between its neighbours' blocks (Section III-C).

@@ -22,7 +22,8 @@
  *                       hand-worked example; kind 4 (seeded) is pinned only as
  *                       "a permutation, deterministic, published splitmix64
  *                       test vector" -- the paper defines no seeded order:
- *                       PARITY UNPINNED by the paper for kind 4.
+ *                       PARITY UNPINNED by the paper for kinds 4 and 6 (6 is
+ *                       checked against numpy lexsort on (class, key, index)).
  *   lapo_place        : pinned (granule brute force, validity and lower-bound
  *                       invariants of Eq. 2, exhaustive orderings on N<=8
  *                       against an independent exhaustive offset search).
@@ -170,18 +171,44 @@ static int cmp_key_desc(const void *a, const void *b)
     return x->idx < y->idx ? -1 : (x->idx > y->idx);
 }
 
+typedef struct { uint32_t cls; uint64_t key; uint32_t idx; } classed;
+
+static int cmp_class_desc_key_asc(const void *a, const void *b)
+{
+    const classed *x = (const classed *)a, *y = (const classed *)b;
+    if (x->cls != y->cls) return x->cls > y->cls ? -1 : 1;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    return x->idx < y->idx ? -1 : (x->idx > y->idx);
+}
+
 /* Section III-C sorts the variables by size, largest first (kind 0).  The
  * other kinds are the extra heuristic orders evaluated in parallel:
  *   1 lifetime descending, 2 size x lifetime descending, 3 alloc step
  *   ascending (arrival order, what an online pool would see), 4 seeded
- *   shuffle (ascending mix64 key), 5 caller-supplied permutation.
+ *   shuffle (ascending mix64 key), 5 caller-supplied permutation, 6 seeded
+ *   shuffle inside size classes: class = floor(log2 size), larger classes
+ *   first, ascending mix64 key within a class (a randomised relative of the
+ *   paper's order that keeps big blocks early).
  * Equal keys keep ascending variable index (a stable sort). */
 int lapo_make_perm(uint32_t n, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                    uint32_t kind, uint64_t seed, const uint32_t *explicit_perm, uint32_t *perm)
 {
     if (!size || !alloc || !free_ || !perm) return LAPO_E_NULL;
     if (n == 0) return LAPO_E_SIZE;
-    if (kind > 5) return LAPO_E_ORDERING;
+    if (kind > 6) return LAPO_E_ORDERING;
+    if (kind == 6) {
+        classed *c = (classed *)malloc((size_t)n * sizeof(classed));
+        if (!c) return LAPO_E_NOMEM;
+        for (uint32_t i = 0; i < n; ++i) {
+            uint32_t lg = 0;
+            while ((size[i] >> lg) > 1) ++lg;          /* floor(log2 size), size > 0 */
+            c[i].cls = lg; c[i].key = mix64(seed, i); c[i].idx = i;
+        }
+        qsort(c, n, sizeof(classed), cmp_class_desc_key_asc);
+        for (uint32_t r = 0; r < n; ++r) perm[r] = c[r].idx;
+        free(c);
+        return LAPO_OK;
+    }
     if (kind == 5) {
         if (!explicit_perm) return LAPO_E_NULL;
         unsigned char *seen = (unsigned char *)calloc(n, 1);

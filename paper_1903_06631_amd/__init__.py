@@ -21,7 +21,7 @@ from .binding import (  # noqa: F401
     workspace_bytes,
 )
 
-ORD_SIZE_DESC, ORD_LIFE_DESC, ORD_AREA_DESC, ORD_ALLOC_ASC, ORD_SEEDED, ORD_EXPLICIT = range(6)
+ORD_SIZE_DESC, ORD_LIFE_DESC, ORD_AREA_DESC, ORD_ALLOC_ASC, ORD_SEEDED, ORD_EXPLICIT, ORD_CLASS_SEEDED = range(7)
 WS_LOAD_PROFILE, WS_PLAN_POOL, WS_SCORE_SWAPS, WS_VALIDATE, WS_SELECT_SWAPS = range(5)
 K_LOAD_SCATTER, K_PLACE, K_SCORE, K_SORT, K_SELECT = range(5)
 FIT_FIRST, FIT_BEST = range(2)

@@ -218,7 +218,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     bool any_explicit = false, any_best = false, any_first = false;
     for (uint32_t b = 0; b < B; ++b) {
         any_explicit |= ords[b].kind == LAP_ORD_EXPLICIT;
-        if (ords[b].kind > LAP_ORD_EXPLICIT) return LAP_E_ORDERING;
+        if (ords[b].kind > LAP_ORD_CLASS_SEEDED) return LAP_E_ORDERING;
         if (ords[b].kind == LAP_ORD_EXPLICIT && ords[b].seed == 0) return LAP_E_ORDERING;
         if (ords[b].fit > LAP_FIT_BEST) return LAP_E_ORDERING;
         any_best |= ords[b].fit == LAP_FIT_BEST;

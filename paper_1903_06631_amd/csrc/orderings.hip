@@ -7,8 +7,9 @@
 // recomputed from the trace on every pass, so only the 4-byte indices move.
 // Descending kinds sort the bitwise complement of the key; stability keeps
 // equal keys in ascending index order.  A pass whose digit is the same for
-// every variable is skipped.  The seeded shuffle's keys are distinct and spread
-// over all 64 bits, so only their top 24 (32 for very large N) bits are radix
+// every variable is skipped.  The seeded shuffles' keys are distinct and spread
+// over all 64 bits, so only their top 24 bits (32 for very large N, and for the
+// shuffle inside size classes, whose top 6 bits are the class) are radix
 // sorted; the few runs of variables that share those bits are then put in order
 // by their full keys, one thread per run.
 #include "lap_dev.h"
@@ -26,8 +27,25 @@ __device__ __forceinline__ uint64_t order_key(uint32_t kind, uint64_t seed, uint
     case 1: return ~(uint64_t)(free_[i] - alloc[i]);
     case 2: return ~(size[i] * (uint64_t)(free_[i] - alloc[i]));
     case 3: return (uint64_t)alloc[i];
+    case 6: {
+        // size class (floor(log2 size)) descending in the top 6 bits, then the shuffle key
+        const uint64_t c = (uint64_t)__clzll((long long)size[i]);          // 63 - class
+        return (c << 58) | (mix64(seed, i) >> 6);
+    }
     default: return mix64(seed, i);
     }
+}
+
+// full comparison of two variables of a seeded kind (4 or 6): the radix key above drops the
+// low bits of the shuffle key, the order does not
+__device__ __forceinline__ bool seeded_after(uint32_t kind, uint64_t seed, uint32_t x, uint32_t y,
+                                             const uint64_t *__restrict__ size)
+{
+    if (kind == 6) {
+        const int cx = __clzll((long long)size[x]), cy = __clzll((long long)size[y]);
+        if (cx != cy) return cx > cy;
+    }
+    return mix64(seed, x) > mix64(seed, y);
 }
 
 constexpr int SW = 4;                    // waves per ordering
@@ -73,7 +91,7 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     const uint32_t *cur = nullptr;
     uint32_t *dst = perm;
     const uint64_t lt_mask = (1ull << l) - 1ull;
-    const int first_pass = (kind == 4) ? (n <= (1u << 22) ? 5 : 4) : 0;
+    const int first_pass = (kind == 4) ? (n <= (1u << 22) ? 5 : 4) : (kind == 6) ? 4 : 0;
     for (int pass = first_pass; pass < 8; ++pass) {
         const int shift = pass * 8;
         for (int k = l; k < 256; k += WAVE) hist[w][k] = 0;
@@ -149,20 +167,20 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     }
     if (first_pass == 0) return;
     // Runs of equal sorted bits: the thread at a run's first rank sorts the run by the full
-    // key (insertion sort; the keys of a seeded order are distinct).  Every entry a run
+    // key (insertion sort; the shuffle keys of one seed are distinct).  Every entry a run
     // moves keeps the run's sorted bits, so the neighbours' run tests are not disturbed.
     __syncthreads();
     const int pshift = first_pass * 8;
     for (uint32_t r = threadIdx.x; r < n; r += SW * WAVE) {
-        const uint64_t p0 = mix64(seed, perm[r]) >> pshift;
-        if (r > 0 && (mix64(seed, perm[r - 1]) >> pshift) == p0) continue;       // not a run's first rank
+        const uint64_t p0 = order_key(kind, seed, perm[r], size, alloc, free_) >> pshift;
+        if (r > 0 && (order_key(kind, seed, perm[r - 1], size, alloc, free_) >> pshift) == p0)
+            continue;                                                            // not a run's first rank
         uint32_t m = 1;
-        while (r + m < n && (mix64(seed, perm[r + m]) >> pshift) == p0) ++m;
+        while (r + m < n && (order_key(kind, seed, perm[r + m], size, alloc, free_) >> pshift) == p0) ++m;
         for (uint32_t x = 1; x < m; ++x) {
             const uint32_t vi = perm[r + x];
-            const uint64_t vk = mix64(seed, vi);
             uint32_t y = x;
-            while (y > 0 && mix64(seed, perm[r + y - 1]) > vk) { perm[r + y] = perm[r + y - 1]; --y; }
+            while (y > 0 && seeded_after(kind, seed, perm[r + y - 1], vi, size)) { perm[r + y] = perm[r + y - 1]; --y; }
             perm[r + y] = vi;
         }
     }

@@ -78,7 +78,7 @@ def test_argument_errors(lap):
     need = lap.workspace_bytes(1, 4, 3, 2)
     assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, need - 1, None) == -3
     # orderings
-    ords[1].kind = 6
+    ords[1].kind = 7
     assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -4
     ords[1].kind, ords[1].seed = 5, 0
     assert lib.lap_plan_pool(C.byref(good), ords, 2, fake, fake, fake, None, None, fake, 1 << 30, None) == -4

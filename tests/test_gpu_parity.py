@@ -163,6 +163,15 @@ def test_plan_pool_seeded_orders_with_equal_leading_key_bits(lap, oracle_mod):
     _check_plan(lap, oracle_mod, tr, [4, 4, 4], seeds)
 
 
+@pytest.mark.parametrize("seed,n,T", [(0, 1, 1), (1, 300, 12), (2, 5000, 60), (3, 70000, 3000)])
+def test_plan_pool_class_seeded_orders(lap, oracle_mod, seed, n, T):
+    """shuffles inside size classes (kind 6), both fit policies"""
+    kw = dict(max_life=3, one_step_frac=0.9) if n > 10000 else {}
+    tr = random_trace(1500 + seed, n, T, **kw)
+    B = 3 if n > 10000 else 8
+    _check_plan(lap, oracle_mod, tr, [6] * B, [77 + b for b in range(B)], fits=[b % 2 for b in range(B)])
+
+
 def _mixed(B):
     """first-fit and best-fit orderings side by side, all six kinds of order"""
     kinds = [b % 5 for b in range(B)]

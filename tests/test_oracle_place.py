@@ -66,6 +66,22 @@ def test_fixed_kinds_match_lexsort(oracle_mod, seed):
     assert oracle_mod.make_perm(tr, 4, seed=632 + seed).tolist() != p.tolist()
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_class_seeded_matches_lexsort(oracle_mod, seed):
+    """kind 6: size class floor(log2 size) descending, shuffle key ascending inside a class."""
+    tr = random_trace(50 + seed, 700, 19, size_choices=[1, 2, 3, 4, 7, 8, 9, 100, 128, 129, 1 << 20, (1 << 21) - 1])
+    idx = np.arange(tr.n_vars)
+    cls = np.array([int(x).bit_length() - 1 for x in tr.size])
+    key = np.array([oracle_mod.mix64(900 + seed, int(i)) for i in idx], dtype=np.uint64)
+    want = np.lexsort((idx, key, -cls))
+    p = oracle_mod.make_perm(tr, 6, seed=900 + seed)
+    assert p.tolist() == want.tolist()
+    # larger classes first, so no variable is preceded by one less than half its size
+    sz = tr.size[p].astype(np.int64)
+    assert all(sz[i] * 2 > sz[i + 1:].max() for i in range(0, len(sz) - 1, 37))
+    assert oracle_mod.make_perm(tr, 6, seed=901 + seed).tolist() != p.tolist()
+
+
 def test_explicit_perm_is_validated(oracle_mod):
     tr = random_trace(1, 5, 4)
     with pytest.raises(RuntimeError):

@@ -33,7 +33,7 @@ CONFIG_NAMES = {
 }
 
 # ordering kinds of the boundary (same numbering as include/lap.h)
-ORD_SIZE_DESC, ORD_LIFE_DESC, ORD_AREA_DESC, ORD_ALLOC_ASC, ORD_SEEDED, ORD_EXPLICIT = range(6)
+ORD_SIZE_DESC, ORD_LIFE_DESC, ORD_AREA_DESC, ORD_ALLOC_ASC, ORD_SEEDED, ORD_EXPLICIT, ORD_CLASS_SEEDED = range(7)
 
 _M64 = (1 << 64) - 1
 
