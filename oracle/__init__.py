@@ -190,3 +190,14 @@ def select_swaps(tr, link_GBps: float, min_bytes: int, score_kind: int, limits, 
     nc = int(n_cand.value)
     return dict(order=order[:nc], rank=rank, n_cand=nc, peaks=peaks[:nc + 1], n_selected=n_sel[:L],
                 peak_after=peak_after[:L], load_min=int(load_min.value))
+
+
+def detect_iteration(tokens, min_period: int = 1) -> int:
+    lib = _load()
+    tokens = _c(tokens, np.uint64)
+    period = C.c_uint32(0)
+    rc = lib.lapo_detect_iteration(tokens.ctypes.data_as(C.c_void_p), C.c_uint32(len(tokens)),
+                                   C.c_uint32(min_period), C.byref(period))
+    if rc:
+        raise RuntimeError(f"lapo_detect_iteration rc={rc}")
+    return int(period.value)

@@ -36,6 +36,9 @@
  *                       is this build's reading of "how much the peak drops",
  *                       pinned against a literal re-simulation of the load
  *                       curve with the variable removed.
+ *   lapo_detect_iteration : pinned (Z-function of the reversed stream, streams built
+ *                       from a known iteration with warm-up prefix and partial tail,
+ *                       inner repetitions against min_period).
  *   lapo_select_swaps : pinned (two hand-worked examples, one where the SWDOA
  *                       order differs from the WDOA order; a dense-matrix
  *                       re-simulation in exact integers; monotone peaks and
@@ -585,4 +588,29 @@ int lapo_select_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32
 done:
     free(cand); free(doa); free(aoa); free(wdoa); free(cut); free(load); free(C); free(wlo); free(whi); free(taken);
     return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* iteration detection on a recorded request stream (Section V)              */
+/* ------------------------------------------------------------------------ */
+
+/* The requests of the first iterations are recorded in a list; an iteration has been seen as
+ * soon as the list ends with two consecutive equal subsequences, and that subsequence is one
+ * iteration's operations.  tokens[i] stands for request i (operation kind and size, whatever the
+ * caller folds into 64 bits; addresses are not part of it, they differ between iterations).
+ * *period = the smallest p >= min_period (min_period >= 1) with
+ *     tokens[M-2p+i] == tokens[M-p+i]  for all 0 <= i < p,
+ * or 0 when there is none (in particular when 2*min_period > M).  The iteration is then
+ * tokens[M-p .. M). */
+int lapo_detect_iteration(const uint64_t *tokens, uint32_t M, uint32_t min_period, uint32_t *period)
+{
+    if (!tokens || !period) return LAPO_E_NULL;
+    if (M == 0 || min_period == 0) return LAPO_E_SIZE;
+    *period = 0;
+    for (uint32_t p = min_period; 2 * (uint64_t)p <= M; ++p) {
+        uint32_t i = 0;
+        while (i < p && tokens[M - 2 * p + i] == tokens[M - p + i]) ++i;
+        if (i == p) { *period = p; break; }
+    }
+    return LAPO_OK;
 }
