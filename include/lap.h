@@ -17,6 +17,7 @@
  *   lap_score_swaps   AutoSwap candidate filter and priority scores (Section
  *                     IV-A, IV-B): DOA, AOA, WDOA, and the drop of the peak
  *                     load when the variable is away for its idle gap.
+ *   lap_detect_iteration  finds one iteration in a recorded request stream (Section V).
  *   lap_select_swaps  AutoSwap selection (Section IV-D): candidates taken in
  *                     priority order until the peak load is within a limit,
  *                     for several scores (SWDOA of Section IV-B (iv) among
@@ -123,7 +124,8 @@ enum {
     LAP_WS_PLAN_POOL = 1,
     LAP_WS_SCORE_SWAPS = 2,
     LAP_WS_VALIDATE = 3,
-    LAP_WS_SELECT_SWAPS = 4
+    LAP_WS_SELECT_SWAPS = 4,
+    LAP_WS_DETECT_ITERATION = 5   /* n_vars = number of requests */
 };
 
 /* Bytes of workspace the given call needs.  B is the number of orderings for PLAN_POOL, the
@@ -195,6 +197,19 @@ int lap_select_swaps(const lap_trace *trace, double link_GBps, uint64_t min_byte
                      uint32_t *order, uint32_t *rank, uint64_t *peaks, uint32_t *n_cand,
                      uint32_t *n_selected, uint64_t *peak_after, uint64_t *load_min,
                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Section V: the requests of the first iterations are recorded in a list, and an iteration has
+ * been seen once the list ends with two equal consecutive subsequences; that subsequence is one
+ * iteration's operations.
+ *   tokens [n_requests] device: one 64-bit value per recorded request (operation kind and size,
+ *                       whatever the caller folds in; not the address, which changes between
+ *                       iterations)
+ *   min_period >= 1     shortest iteration the caller accepts (guards against a short repeat
+ *                       inside an iteration that happens to end the list)
+ *   period [1] device   out: the smallest p >= min_period with tokens[M-2p+i] == tokens[M-p+i]
+ *                       for all i < p, or 0 if there is none; the iteration is tokens[M-p .. M) */
+int lap_detect_iteration(const uint64_t *tokens, uint32_t n_requests, uint32_t min_period, uint32_t *period,
+                         void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Checks the trace content on the device, waits for the stream, and returns
  * LAP_OK, LAP_E_TRACE or LAP_E_RANGE. */

@@ -8,6 +8,7 @@ call fails, an exception is raised.
 from .binding import (  # noqa: F401
     DeviceTrace,
     LapError,
+    detect_iteration,
     lib_path,
     load_library,
     load_profile,
@@ -22,7 +23,7 @@ from .binding import (  # noqa: F401
 )
 
 ORD_SIZE_DESC, ORD_LIFE_DESC, ORD_AREA_DESC, ORD_ALLOC_ASC, ORD_SEEDED, ORD_EXPLICIT, ORD_CLASS_SEEDED = range(7)
-WS_LOAD_PROFILE, WS_PLAN_POOL, WS_SCORE_SWAPS, WS_VALIDATE, WS_SELECT_SWAPS = range(5)
+WS_LOAD_PROFILE, WS_PLAN_POOL, WS_SCORE_SWAPS, WS_VALIDATE, WS_SELECT_SWAPS, WS_DETECT_ITERATION = range(6)
 K_LOAD_SCATTER, K_PLACE, K_SCORE, K_SORT, K_SELECT = range(5)
 FIT_FIRST, FIT_BEST = range(2)
 PS_DOA, PS_AOA, PS_WDOA, PS_SWDOA, PS_PEAK_CUT = range(5)

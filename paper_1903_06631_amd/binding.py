@@ -13,6 +13,7 @@ _lib = None
 
 EXPORTS = [
     "lap_workspace_bytes", "lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
+    "lap_detect_iteration",
     "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms",
 ]
 
@@ -69,6 +70,9 @@ def load_library():
                                      C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lap_detect_iteration.restype = C.c_int
+    lib.lap_detect_iteration.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                         C.c_void_p]
     lib.lap_validate_trace.restype = C.c_int
     lib.lap_validate_trace.argtypes = [C.POINTER(_Trace), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lap_profile_enable.restype = C.c_int
@@ -272,6 +276,25 @@ def select_swaps(dt: DeviceTrace, link_GBps: float, min_bytes: int, score_kinds:
     if sync:
         torch.cuda.current_stream(dt.device).synchronize()
     return out
+
+
+def detect_iteration(tokens, min_period: int = 1, sync: bool = True):
+    """lap_detect_iteration: tokens is an int64 device tensor (bit patterns of the 64-bit request tokens);
+    returns a 1-element int32 device tensor with the period (0 = none)."""
+    torch = _torch()
+    lib = load_library()
+    assert tokens.dtype == torch.int64 and tokens.is_contiguous() and tokens.is_cuda
+    m = tokens.numel()
+    need = workspace_bytes(5, m, 0, 0)
+    ws = torch.empty(need, dtype=torch.uint8, device=tokens.device)
+    period = torch.empty(1, dtype=torch.int32, device=tokens.device)
+    rc = lib.lap_detect_iteration(tokens.data_ptr(), m, int(min_period), period.data_ptr(), ws.data_ptr(), need,
+                                  _stream_ptr(tokens.device))
+    if rc:
+        raise LapError(rc, "lap_detect_iteration")
+    if sync:
+        torch.cuda.current_stream(tokens.device).synchronize()
+    return period
 
 
 def validate_trace(dt: DeviceTrace) -> int:

@@ -159,6 +159,7 @@ size_t lap_workspace_bytes(int which, uint32_t n_vars, uint32_t n_steps, uint32_
     case LAP_WS_SCORE_SWAPS: return ws_score(n_steps);
     case LAP_WS_VALIDATE: return ws_validate();
     case LAP_WS_SELECT_SWAPS: return ws_select(n_vars, n_steps, B);
+    case LAP_WS_DETECT_ITERATION: return up(((size_t)n_vars + 1) * 8);
     default: return 0;
     }
 }
@@ -424,6 +425,18 @@ int lap_select_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, 
         ProfScope p(LAP_K_SELECT, st);
         LAP_HIP(lap::launch_select_swaps(a, st));
     }
+    return LAP_OK;
+}
+
+int lap_detect_iteration(const uint64_t *tokens, uint32_t n_requests, uint32_t min_period, uint32_t *period,
+                         void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!tokens || !period) return LAP_E_NULL;
+    if (n_requests == 0 || n_requests == 0xFFFFFFFFu || min_period == 0) return LAP_E_SIZE;
+    const int rc = check_ws(ws, ws_bytes, up(((size_t)n_requests + 1) * 8));
+    if (rc) return rc;
+    LAP_HIP(lap::launch_detect_iteration(tokens, n_requests, min_period, (uint64_t *)ws, period,
+                                         (hipStream_t)hip_stream));
     return LAP_OK;
 }
 

@@ -84,4 +84,7 @@ struct SelectArgs {
 };
 hipError_t launch_select_swaps(const SelectArgs &a, hipStream_t st);
 
+hipError_t launch_detect_iteration(const uint64_t *tokens, uint32_t M, uint32_t min_period, uint64_t *P,
+                                   uint32_t *period, hipStream_t st);
+
 }  // namespace lap

@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported(lap):
     hdr = open(os.path.join(ROOT, "include", "lap.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(lap_[a-z_]+)\s*\(", hdr))
-    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps", "lap_workspace_bytes",
+    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps", "lap_detect_iteration",
+            "lap_workspace_bytes",
             "lap_validate_trace", "lap_status_string"} <= declared
     lib = lap.load_library()
     for name in declared:
@@ -102,6 +103,12 @@ def test_argument_errors(lap):
     assert sel(kinds=(C.c_uint32 * 2)(3, 5)) == -4
     assert sel(link=0.0) == -5
     assert sel(ws=lap.workspace_bytes(4, 4, 3, 2) - 1) == -3
+
+    # iteration detection
+    assert lib.lap_detect_iteration(None, 8, 1, fake, fake, 1 << 20, None) == -1
+    assert lib.lap_detect_iteration(fake, 0, 1, fake, fake, 1 << 20, None) == -2
+    assert lib.lap_detect_iteration(fake, 8, 0, fake, fake, 1 << 20, None) == -2
+    assert lib.lap_detect_iteration(fake, 8, 1, fake, fake, 8, None) == -3
 
 
 def test_no_cpu_fallback(lap, monkeypatch, tmp_path):
