@@ -201,3 +201,23 @@ def detect_iteration(tokens, min_period: int = 1) -> int:
     if rc:
         raise RuntimeError(f"lapo_detect_iteration rc={rc}")
     return int(period.value)
+
+
+def schedule_swaps(tr, link_GBps: float, swap_list, use_gaps=True):
+    lib = _load()
+    sl = _c(swap_list, np.uint32)
+    k, T = len(sl), tr.n_steps
+    o = [np.zeros(max(k, 1), np.int64) for _ in range(4)]
+    load = np.zeros(T, np.uint64)
+    peak = C.c_uint64(0)
+    late = C.c_uint64(0)
+    rc = lib.lapo_schedule_swaps(
+        C.c_uint32(tr.n_vars), C.c_uint32(T), _opt(tr.size, np.uint64), _opt(tr.alloc, np.uint32),
+        _opt(tr.free, np.uint32), _opt(tr.gap_lo if use_gaps else None, np.uint32),
+        _opt(tr.gap_hi if use_gaps else None, np.uint32), _opt(tr.step_ns, np.uint64), C.c_double(link_GBps),
+        sl.ctypes.data_as(C.c_void_p), C.c_uint32(k), *[a.ctypes.data_as(C.c_void_p) for a in o],
+        load.ctypes.data_as(C.c_void_p), C.byref(peak), C.byref(late))
+    if rc:
+        raise RuntimeError(f"lapo_schedule_swaps rc={rc}")
+    return dict(out_start=o[0][:k], out_end=o[1][:k], in_start=o[2][:k], in_end=o[3][:k], load=load,
+                peak=int(peak.value), late_ns=int(late.value))

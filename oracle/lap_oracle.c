@@ -39,6 +39,11 @@
  *   lapo_detect_iteration : pinned (Z-function of the reversed stream, streams built
  *                       from a known iteration with warm-up prefix and partial tail,
  *                       inner repetitions against min_period).
+ *   lapo_schedule_swaps : pinned (hand-worked example; the properties that define an
+ *                       as-soon-as-possible and an as-late-as-possible stream schedule
+ *                       uniquely; an event-queue re-simulation of the swap-out stream;
+ *                       load re-derived with exact fractions).  The stalls of a tight
+ *                       limit (the paper's LOAD'') are not modelled.
  *   lapo_select_swaps : pinned (two hand-worked examples, one where the SWDOA
  *                       order differs from the WDOA order; a dense-matrix
  *                       re-simulation in exact integers; monotone peaks and
@@ -612,5 +617,102 @@ int lapo_detect_iteration(const uint64_t *tokens, uint32_t M, uint32_t min_perio
         while (i < p && tokens[M - 2 * p + i] == tokens[M - p + i]) ++i;
         if (i == p) { *period = p; break; }
     }
+    return LAPO_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* swap schedule (Section IV-E), without the stalls a tight limit may force  */
+/* ------------------------------------------------------------------------ */
+
+typedef struct { uint32_t step, var, pos; } sched_key;
+
+static int cmp_sched(const void *a, const void *b)
+{
+    const sched_key *x = (const sched_key *)a, *y = (const sched_key *)b;
+    if (x->step != y->step) return x->step < y->step ? -1 : 1;
+    return x->var < y->var ? -1 : (x->var > y->var);
+}
+
+/* Section IV-E: the selected variables are swapped out when not in use and prefetched before
+ * their next access.  Swap-outs run one after the other on one stream in ascending order of
+ * their access (ties: variable index); each starts as soon as its access has completed (the end
+ * of step gap_lo) and the previous swap-out has finished.  Swap-ins run one after the other on a
+ * second stream in the order of the next accesses; each starts as late as it can so that it has
+ * finished when its access begins (the start of step gap_hi) and the swap-in after it can still
+ * start on time.  All times in ns from the start of the iteration (swap-in times may be negative
+ * when the stream is overbooked).  A transfer of a variable takes ceil(size*1000/bytes_per_us).
+ *   swap_list[k]            the selected variables (distinct)
+ *   out_start/out_end/in_start/in_end [k]   per list position
+ *   load_sched[T]           load with every selected variable away on the whole steps that lie
+ *                           between the end of its swap-out and the start of its swap-in
+ *   peak_sched              its maximum
+ *   late_ns                 sum over the list of max(0, out_end - in_start): transfer time the
+ *                           plan cannot hide (the swap-in would have to start before the
+ *                           swap-out is done) */
+int lapo_schedule_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                        const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                        const uint64_t *step_ns, double link_GBps, const uint32_t *swap_list, uint32_t k,
+                        int64_t *out_start, int64_t *out_end, int64_t *in_start, int64_t *in_end,
+                        uint64_t *load_sched, uint64_t *peak_sched, uint64_t *late_ns)
+{
+    if (!size || !alloc || !free_ || !load_sched || !peak_sched || !late_ns) return LAPO_E_NULL;
+    if (k && (!swap_list || !out_start || !out_end || !in_start || !in_end)) return LAPO_E_NULL;
+    if (n == 0 || T == 0) return LAPO_E_SIZE;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps)) return LAPO_E_LINK;
+    const uint64_t bpus = (uint64_t)llround(link_GBps * 1000.0);
+    if (bpus == 0) return LAPO_E_LINK;
+    uint64_t *C = (uint64_t *)malloc(((size_t)T + 1) * 8);
+    sched_key *q = (sched_key *)malloc(((size_t)k + 1) * sizeof(sched_key));
+    if (!C || !q) { free(C); free(q); return LAPO_E_NOMEM; }
+    C[0] = 0;
+    for (uint32_t t = 0; t < T; ++t) C[t + 1] = C[t] + (step_ns ? step_ns[t] : 1000000u);
+    for (uint32_t t = 0; t < T; ++t) load_sched[t] = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint32_t t = alloc[i]; t < free_[i]; ++t) load_sched[t] += size[i];
+    /* swap-outs: as soon as possible, in access order */
+    for (uint32_t j = 0; j < k; ++j) {
+        const uint32_t v = swap_list[j];
+        q[j].step = gap_lo ? gap_lo[v] : alloc[v]; q[j].var = v; q[j].pos = j;
+    }
+    qsort(q, k, sizeof(sched_key), cmp_sched);
+    int64_t stream_free = 0;
+    for (uint32_t j = 0; j < k; ++j) {
+        const uint32_t v = q[j].var;
+        const int64_t delta = (int64_t)((size[v] * 1000u + bpus - 1) / bpus);
+        const int64_t ready = (int64_t)C[q[j].step + 1];
+        const int64_t st = ready > stream_free ? ready : stream_free;
+        out_start[q[j].pos] = st;
+        out_end[q[j].pos] = st + delta;
+        stream_free = st + delta;
+    }
+    /* swap-ins: as late as possible, in next-access order, planned from the last one back */
+    for (uint32_t j = 0; j < k; ++j) {
+        const uint32_t v = swap_list[j];
+        q[j].step = gap_hi ? gap_hi[v] : free_[v] - 1; q[j].var = v; q[j].pos = j;
+    }
+    qsort(q, k, sizeof(sched_key), cmp_sched);
+    int64_t next_start = INT64_MAX;
+    for (uint32_t j = k; j-- > 0;) {
+        const uint32_t v = q[j].var;
+        const int64_t delta = (int64_t)((size[v] * 1000u + bpus - 1) / bpus);
+        const int64_t due = (int64_t)C[q[j].step];
+        const int64_t en = due < next_start ? due : next_start;
+        in_end[q[j].pos] = en;
+        in_start[q[j].pos] = en - delta;
+        next_start = en - delta;
+    }
+    /* the load under this plan, and what it cannot hide */
+    uint64_t late = 0;
+    for (uint32_t j = 0; j < k; ++j) {
+        const uint32_t v = swap_list[j];
+        if (out_end[j] > in_start[j]) { late += (uint64_t)(out_end[j] - in_start[j]); continue; }
+        for (uint32_t t = 0; t < T; ++t)
+            if ((int64_t)C[t] >= out_end[j] && (int64_t)C[t + 1] <= in_start[j]) load_sched[t] -= size[v];
+    }
+    uint64_t pk = 0;
+    for (uint32_t t = 0; t < T; ++t) if (load_sched[t] > pk) pk = load_sched[t];
+    *peak_sched = pk;
+    *late_ns = late;
+    free(C); free(q);
     return LAPO_OK;
 }
