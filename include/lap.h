@@ -17,6 +17,7 @@
  *   lap_score_swaps   AutoSwap candidate filter and priority scores (Section
  *                     IV-A, IV-B): DOA, AOA, WDOA, and the drop of the peak
  *                     load when the variable is away for its idle gap.
+ *   lap_schedule_swaps  the swap-out / swap-in plan of Section IV-E and the load under it.
  *   lap_detect_iteration  finds one iteration in a recorded request stream (Section V).
  *   lap_select_swaps  AutoSwap selection (Section IV-D): candidates taken in
  *                     priority order until the peak load is within a limit,
@@ -125,7 +126,8 @@ enum {
     LAP_WS_SCORE_SWAPS = 2,
     LAP_WS_VALIDATE = 3,
     LAP_WS_SELECT_SWAPS = 4,
-    LAP_WS_DETECT_ITERATION = 5   /* n_vars = number of requests */
+    LAP_WS_DETECT_ITERATION = 5,  /* n_vars = number of requests */
+    LAP_WS_SCHEDULE_SWAPS = 6
 };
 
 /* Bytes of workspace the given call needs.  B is the number of orderings for PLAN_POOL, the
@@ -197,6 +199,28 @@ int lap_select_swaps(const lap_trace *trace, double link_GBps, uint64_t min_byte
                      uint32_t *order, uint32_t *rank, uint64_t *peaks, uint32_t *n_cand,
                      uint32_t *n_selected, uint64_t *peak_after, uint64_t *load_min,
                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Section IV-E, the plan before any stall: the selected variables' swap-outs run one after the
+ * other on one stream in ascending order of their access (ties: variable index), each as soon as
+ * the access is over (end of step gap_lo) and the stream is free; their swap-ins run one after the
+ * other on a second stream in the order of the next accesses, each as late as possible such that
+ * it is done when its access begins (start of step gap_hi) and the swap-in after it can start on
+ * time.  Times are ns from the start of the iteration; a swap-in time is negative when that
+ * stream is overbooked.
+ *   load       [T] from lap_load_profile, or NULL to compute it here
+ *   swap_list  [k] device: distinct variable indices (for example a prefix of an order of
+ *              lap_select_swaps); k may be 0
+ *   out_start, out_end, in_start, in_end [k] out, by list position
+ *   load_sched [T] out: load with every listed variable away on the whole steps between the end
+ *              of its swap-out and the start of its swap-in
+ *   peak_sched [1] out: its maximum
+ *   late_ns    [1] out: sum of max(0, out_end - in_start), transfer time the plan cannot hide
+ * The stalls that a tight limit forces on top of this plan are not modelled. */
+int lap_schedule_swaps(const lap_trace *trace, double link_GBps, const uint64_t *load,
+                       const uint32_t *swap_list, uint32_t k,
+                       int64_t *out_start, int64_t *out_end, int64_t *in_start, int64_t *in_end,
+                       uint64_t *load_sched, uint64_t *peak_sched, uint64_t *late_ns,
+                       void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Section V: the requests of the first iterations are recorded in a list, and an iteration has
  * been seen once the list ends with two equal consecutive subsequences; that subsequence is one

@@ -13,7 +13,7 @@ _lib = None
 
 EXPORTS = [
     "lap_workspace_bytes", "lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
-    "lap_detect_iteration",
+    "lap_detect_iteration", "lap_schedule_swaps",
     "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms",
 ]
 
@@ -70,6 +70,10 @@ def load_library():
                                      C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lap_schedule_swaps.restype = C.c_int
+    lib.lap_schedule_swaps.argtypes = [C.POINTER(_Trace), C.c_double, C.c_void_p, C.c_void_p, C.c_uint32,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lap_detect_iteration.restype = C.c_int
     lib.lap_detect_iteration.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
@@ -273,6 +277,29 @@ def select_swaps(dt: DeviceTrace, link_GBps: float, min_bytes: int, score_kinds:
                               p(out["load_min"]), ws.data_ptr(), need, _stream_ptr(dt.device))
     if rc:
         raise LapError(rc, "lap_select_swaps")
+    if sync:
+        torch.cuda.current_stream(dt.device).synchronize()
+    return out
+
+
+def schedule_swaps(dt: DeviceTrace, link_GBps: float, swap_list, load=None, sync: bool = True):
+    """lap_schedule_swaps: swap_list is an int32 device tensor of variable indices.  Returns device tensors
+    out_start, out_end, in_start, in_end [k] (int64 ns), load[T], peak[1], late_ns[1]."""
+    torch = _torch()
+    lib = load_library()
+    assert swap_list.dtype == torch.int32 and swap_list.is_contiguous()
+    k = swap_list.numel()
+    mk = lambda m, dtp=torch.int64: torch.empty(m, dtype=dtp, device=dt.device)
+    out = dict(out_start=mk(k), out_end=mk(k), in_start=mk(k), in_end=mk(k), load=mk(dt.n_steps), peak=mk(1),
+               late_ns=mk(1))
+    ws, need = dt.workspace(6)
+    tr = dt.c_struct()
+    p = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    rc = lib.lap_schedule_swaps(C.byref(tr), float(link_GBps), p(load), p(swap_list), k, p(out["out_start"]),
+                                p(out["out_end"]), p(out["in_start"]), p(out["in_end"]), p(out["load"]),
+                                p(out["peak"]), p(out["late_ns"]), ws.data_ptr(), need, _stream_ptr(dt.device))
+    if rc:
+        raise LapError(rc, "lap_schedule_swaps")
     if sync:
         torch.cuda.current_stream(dt.device).synchronize()
     return out

@@ -70,6 +70,14 @@ size_t ws_validate() { return up(8 * 8); }
 constexpr uint32_t SELECT_MAX_LIMITS = 1024;
 constexpr uint32_t SELECT_MAX_KINDS = 64;
 
+size_t ws_schedule(uint32_t n, uint32_t T)
+{
+    const size_t t1 = (size_t)T + 1, N = n;
+    return up((size_t)T * 8) + 6 * up(t1 * 8)          // load, delta, C, S, PM, SM, diff  (diff counted below)
+           + up(t1 * 8) + 2 * ALIGN                    // diff; peak, t_peak
+           + 4 * up(N * 4) + 2 * ALIGN;                // posmap, perm_lo, perm_hi, sort scratch; kinds, seeds
+}
+
 size_t ws_select(uint32_t n, uint32_t T, uint32_t K)
 {
     const size_t N = n;
@@ -160,6 +168,7 @@ size_t lap_workspace_bytes(int which, uint32_t n_vars, uint32_t n_steps, uint32_
     case LAP_WS_VALIDATE: return ws_validate();
     case LAP_WS_SELECT_SWAPS: return ws_select(n_vars, n_steps, B);
     case LAP_WS_DETECT_ITERATION: return up(((size_t)n_vars + 1) * 8);
+    case LAP_WS_SCHEDULE_SWAPS: return ws_schedule(n_vars, n_steps);
     default: return 0;
     }
 }
@@ -425,6 +434,65 @@ int lap_select_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, 
         ProfScope p(LAP_K_SELECT, st);
         LAP_HIP(lap::launch_select_swaps(a, st));
     }
+    return LAP_OK;
+}
+
+int lap_schedule_swaps(const lap_trace *tr, double link_GBps, const uint64_t *load, const uint32_t *swap_list,
+                       uint32_t k, int64_t *out_start, int64_t *out_end, int64_t *in_start, int64_t *in_end,
+                       uint64_t *load_sched, uint64_t *peak_sched, uint64_t *late_ns, void *ws, size_t ws_bytes,
+                       void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!load_sched || !peak_sched || !late_ns) return LAP_E_NULL;
+    if (k && (!swap_list || !out_start || !out_end || !in_start || !in_end)) return LAP_E_NULL;
+    if (k > tr->n_vars) return LAP_E_SIZE;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps) || link_GBps * 1000.0 >= 9.0e18) return LAP_E_LINK;
+    const long long bpus = llround(link_GBps * 1000.0);
+    if (bpus <= 0) return LAP_E_LINK;
+    const uint32_t n = tr->n_vars, T = tr->n_steps;
+    rc = check_ws(ws, ws_bytes, ws_schedule(n, T));
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t t1 = (size_t)T + 1;
+    Carver c(ws);
+    uint64_t *load_ws = c.take<uint64_t>(T);
+    uint64_t *delta = c.take<uint64_t>(t1);
+    uint64_t *C = c.take<uint64_t>(t1);
+    uint64_t *S = c.take<uint64_t>(t1);
+    uint64_t *PM = c.take<uint64_t>(t1);
+    uint64_t *SM = c.take<uint64_t>(t1);
+    uint64_t *diff = c.take<uint64_t>(t1);
+    uint64_t *peak = c.take<uint64_t>(1);
+    uint32_t *t_peak = c.take<uint32_t>(1);
+    uint32_t *posmap = c.take<uint32_t>(n);
+    uint32_t *perm_lo = c.take<uint32_t>(n);
+    uint32_t *perm_hi = c.take<uint32_t>(n);
+    uint32_t *tmp = c.take<uint32_t>(n);
+    uint32_t *kinds = c.take<uint32_t>(1);
+    uint64_t *seeds = c.take<uint64_t>(1);
+
+    if (!load) {
+        rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
+        if (rc) return rc;
+        load = load_ws;
+    }
+    LAP_HIP(lap::launch_swap_prefix(T, load, tr->step_ns, C, S, PM, SM, peak, t_peak, st));
+    // all variables by (first access, index) and by (next access, index): the ascending-step sort of
+    // the placement orders, fed with the access steps
+    static const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
+    LAP_HIP(hipMemcpyAsync(kinds, &h_kind, 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_fill_u64(seeds, 1, 0, st));
+    const uint32_t *step_lo = tr->gap_lo ? tr->gap_lo : tr->alloc;
+    const uint32_t *step_hi = tr->gap_hi ? tr->gap_hi : tr->free_;
+    LAP_HIP(lap::launch_sort_perm(n, 1, tr->size, step_lo, tr->free_, kinds, seeds, perm_lo, tmp, false, st));
+    LAP_HIP(lap::launch_sort_perm(n, 1, tr->size, step_hi, tr->free_, kinds, seeds, perm_hi, tmp, false, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)posmap, ((size_t)n + 1) / 2, ~0ull, st));
+    LAP_HIP(lap::launch_fill_u64(diff, t1, 0, st));
+    LAP_HIP(lap::launch_fill_u64(late_ns, 1, 0, st));
+    LAP_HIP(lap::launch_schedule_swaps(n, T, k, tr->size, step_lo, step_hi, tr->gap_hi ? 0u : 1u, C, perm_lo, perm_hi,
+                                       posmap, swap_list, (uint64_t)bpus, out_start, out_end, in_start, in_end, diff,
+                                       late_ns, load, load_sched, peak_sched, st));
     return LAP_OK;
 }
 

@@ -84,6 +84,13 @@ struct SelectArgs {
 };
 hipError_t launch_select_swaps(const SelectArgs &a, hipStream_t st);
 
+hipError_t launch_schedule_swaps(uint32_t n, uint32_t T, uint32_t k, const uint64_t *size, const uint32_t *step_lo,
+                                 const uint32_t *step_hi, uint32_t hi_minus, const uint64_t *C,
+                                 const uint32_t *perm_lo, const uint32_t *perm_hi, uint32_t *posmap,
+                                 const uint32_t *list, uint64_t bpus, int64_t *out_start, int64_t *out_end,
+                                 int64_t *in_start, int64_t *in_end, uint64_t *diff, uint64_t *late,
+                                 const uint64_t *load, uint64_t *load_sched, uint64_t *peak, hipStream_t st);
+
 hipError_t launch_detect_iteration(const uint64_t *tokens, uint32_t M, uint32_t min_period, uint64_t *P,
                                    uint32_t *period, hipStream_t st);
 
