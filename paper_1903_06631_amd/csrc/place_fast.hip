@@ -1,22 +1,22 @@
-// First-fit placement of every variable under many orderings (Section III-C):
-// the 32-bit granule path.
+// Placement of every variable under many orderings (Section III-C), first-fit or
+// best-fit: the 32-bit granule path.
 //
 // Offsets are multiples of g = 2^shift, the largest power of two dividing every
 // size (an offset is a sum of sizes).  When sum(size)/g < 2^32 every offset and
 // block end fits 32 bits and a placed block packs into one 64-bit word
 // (off << 32 | end), so sorting words sorts by offset.
 //
-// One workgroup of PW waves per ordering.  Placed blocks are kept sorted by
-// offset in two families of lists:
+// One workgroup of PW waves per ordering.  Two families of lists:
 //
-//   ALL    every placed block, with its lifetime: `main` (global, sorted),
-//          `recent` (LDS, sorted) and `pending` (LDS, unsorted, the newest).
-//          Queried by variables that live for more than one step: the sorted
-//          lists are swept alternately, 64 entries per wave step -- blocks that
-//          do not overlap the variable in time are masked, a wave prefix-max of
-//          the remaining ends gives the highest occupied address so far, and
-//          the first entry whose offset leaves a hole of at least `size` above
-//          it ends the sweep ("the first hole that the variable can fit in").
+//   ALL    placed blocks with their lifetimes, sorted by offset: `main` and
+//          `recent` (global memory, two buffers each, merged out of place) and
+//          `pending` (LDS, unsorted, the newest).  Queried by variables that
+//          live for more than one step: all waves sweep a sorted list together,
+//          64 entries per wave step -- blocks that do not overlap the variable
+//          in time are masked, a wave prefix-max of the remaining ends gives the
+//          highest occupied address so far, and the first entry whose offset
+//          leaves a hole of at least `size` above it ends the sweep ("the first
+//          hole that the variable can fit in").
 //   L[t]   (only when the sum of all lifetimes, plus one per step, is at most
 //          CL*N) the FREE address ranges ("holes") at step t, sorted by start,
 //          packed (start << 32 | size), the last one reaching to 2^32-1;
@@ -24,13 +24,17 @@
 //          since and still have to be carved out.  A variable that lives for
 //          exactly one step t only meets blocks live at t, so its first fit is
 //          the first hole of L[t] that is large enough; taking it only shrinks
-//          that hole in place (first fit always starts at a hole's start).
-//          The list is held in registers while a wave works on step t.
+//          that hole in place (a fit always starts at a hole's start), and a hole
+//          that is used up leaves the list.  The wave that works on step t holds
+//          L[t] in its LDS slice.  With these lists in use, one-step blocks never
+//          enter ALL: a multi-step variable asks the hole lists of its steps
+//          instead (steps_fit_pass), in turn with the ALL sweeps, until neither
+//          moves the candidate offset.
 //
 // One-step variables of different steps never interact, so between two
 // multi-step variables of the rank order the waves work in parallel: wave w
-// owns the steps t with t % PW == w.  Multi-step variables are handled by
-// wave 0 between workgroup barriers.  The result is identical to placing the
+// owns the steps t with t % PW == w.  Multi-step variables are handled by all
+// waves between workgroup barriers.  The result is identical to placing the
 // variables one by one in rank order.
 #include "lap_dev.h"
 #include "lap_kernels.h"
@@ -42,7 +46,6 @@ constexpr uint32_t PEND = 512;      // pending (unsorted) entries in LDS
 constexpr uint32_t REC = PLAN_REC;  // recent (sorted) entries per buffer, global memory
 constexpr uint32_t LH = 768;        // entries of a per-step list a wave can hold in LDS
 constexpr uint32_t CL = PLAN_CL;    // per-step lists need sum of lifetimes <= CL * N
-constexpr int UNROLL = 4;           // chunks loaded ahead by a sweep
 
 // orders this wave's earlier LDS / global accesses before its later ones (no barrier)
 __device__ __forceinline__ void wave_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
@@ -158,67 +161,6 @@ __global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_
 // ---------------------------------------------------------------------------
 // sorted lists of packed blocks (global memory or LDS), one wave
 // ---------------------------------------------------------------------------
-
-// Lowest offset >= P at which `s` granules are free with respect to the entries of one
-// sorted list that overlap [a, f) in time (all entries when LIFE is false).  `cursor`:
-// where to start and where the sweep stopped; time-overlapping entries before it end at
-// or below the returned offset, so a later call with a larger P may resume there.
-template <bool LIFE>
-__device__ __forceinline__ uint32_t sweep32(const uint64_t *oe, const uint64_t *life, uint32_t n, uint32_t &cursor,
-                                            uint32_t P, uint32_t s, uint32_t a, uint32_t f)
-{
-    const int l = lane_id();
-    uint32_t i = cursor;
-    for (;;) {
-        uint64_t x[UNROLL], lf[UNROLL];
-#pragma unroll
-        for (int k = 0; k < UNROLL; ++k) {
-            const uint32_t idx = i + k * WAVE + l;
-            x[k] = 0; lf[k] = 0;
-            if (idx < n) {
-                x[k] = oe[idx];
-                if (LIFE) lf[k] = life[idx];
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < UNROLL; ++k) {
-            const uint32_t idx = i + k * WAVE + l;
-            const bool valid = idx < n;
-            const uint32_t o = (uint32_t)(x[k] >> 32);
-            uint32_t e = (uint32_t)x[k];
-            if (LIFE) {
-                const uint32_t ea = (uint32_t)(lf[k] >> 32), ef = (uint32_t)lf[k];
-                if (!(ea < f && a < ef)) e = 0;
-            }
-            if (!valid) e = 0;
-            const uint32_t incl = wave_scan_max32(e);
-            const uint32_t excl = lane_shift_up(incl, 0u);
-            const uint32_t before = max(P, excl);
-            const uint64_t hole = ballot(!valid || (o >= before && o - before >= s));
-            if (hole) {
-                const int first = __ffsll((unsigned long long)hole) - 1;
-                cursor = i + k * WAVE + first;
-                return read_lane(before, first);
-            }
-            P = max(P, read_lane(incl, WAVE - 1));
-        }
-        i += UNROLL * WAVE;
-    }
-}
-
-// number of the first n entries that are < key
-__device__ __forceinline__ uint32_t count_below32(const uint64_t *oe, uint32_t n, uint64_t key)
-{
-    const int l = lane_id();
-    uint32_t p = 0;
-    for (uint32_t base = 0; base < n; base += WAVE) {
-        const uint32_t idx = base + l;
-        const uint64_t m = ballot(idx < n && oe[idx] < key);
-        p += (uint32_t)__popcll(m);
-        if (m != ~0ull) break;
-    }
-    return p;
-}
 
 // insert (x, lf) at position p of a sorted list of n entries; `life` may be null
 __device__ __forceinline__ void insert_at32(uint64_t *oe, uint64_t *life, uint32_t n, uint32_t p, uint64_t x,
@@ -563,7 +505,7 @@ __device__ __forceinline__ void coop_merge(const uint64_t *src_oe, const LT *src
     }
 }
 
-// sweep32 over a long global list with all PW waves: chunk q of a round belongs to wave
+// One sweep over a long sorted list with all PW waves: chunk q of a round belongs to wave
 // q % PW.  Every wave scans its chunks, the chunk maxima are exchanged through LDS, each
 // wave then tests its chunks for the first hole with the right carry, and the lowest hole
 // of the round wins.  Two workgroup barriers per round; the next round's loads are issued

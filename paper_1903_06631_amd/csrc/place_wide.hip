@@ -1,12 +1,13 @@
-// First-fit placement of every variable under many orderings (Section III-C):
-// the 64-bit path, used when byte offsets do not fit 32-bit granules (see
+// Placement of every variable under many orderings (Section III-C), first-fit or
+// best-fit: the 64-bit path, used when byte offsets do not fit 32-bit granules (see
 // place_fast.hip for the common case).
 //
 // One wave (one 64-thread workgroup) per ordering.  Variables are taken in
 // the ordering's rank order; each gets the lowest offset at which its block
 // does not meet the block of any already-placed variable whose lifetime
 // overlaps its own ("the first hole that the variable can fit in", else the
-// pool is extended).
+// pool is extended).  Best-fit walks on from hole to hole (next_overlap gives a
+// hole's end) and keeps the smallest one that fits.
 //
 // Data structure per ordering: the placed blocks kept SORTED BY OFFSET, as
 //   main    (global memory)  off[], end[], life[] (alloc<<32 | free), nm entries
