@@ -221,3 +221,20 @@ def schedule_swaps(tr, link_GBps: float, swap_list, use_gaps=True):
         raise RuntimeError(f"lapo_schedule_swaps rc={rc}")
     return dict(out_start=o[0][:k], out_end=o[1][:k], in_start=o[2][:k], in_end=o[3][:k], load=load,
                 peak=int(peak.value), late_ns=int(late.value))
+
+
+def simulate_swaps(tr, link_GBps: float, swap_list, limit: int, use_gaps=True):
+    lib = _load()
+    sl = _c(swap_list, np.uint32)
+    total, over, peak = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0)
+    forced = C.c_uint32(0)
+    rc = lib.lapo_simulate_swaps(
+        C.c_uint32(tr.n_vars), C.c_uint32(tr.n_steps), _opt(tr.size, np.uint64), _opt(tr.alloc, np.uint32),
+        _opt(tr.free, np.uint32), _opt(tr.gap_lo if use_gaps else None, np.uint32),
+        _opt(tr.gap_hi if use_gaps else None, np.uint32), _opt(tr.step_ns, np.uint64), C.c_double(link_GBps),
+        sl.ctypes.data_as(C.c_void_p), C.c_uint32(len(sl)), C.c_uint64(limit), C.byref(total), C.byref(over),
+        C.byref(peak), C.byref(forced))
+    if rc:
+        raise RuntimeError(f"lapo_simulate_swaps rc={rc}")
+    return dict(total_ns=int(total.value), overhead_ns=int(over.value), peak_resident=int(peak.value),
+                forced=int(forced.value))

@@ -44,6 +44,11 @@
  *                       uniquely; an event-queue re-simulation of the swap-out stream;
  *                       load re-derived with exact fractions).  The stalls of a tight
  *                       limit (the paper's LOAD'') are not modelled.
+ *   lapo_simulate_swaps : pinned (hand-worked example with a delayed Malloc and delayed
+ *                       swap-ins; a tick-by-tick re-simulation; zero overhead when the
+ *                       limit is loose and nothing is late).  The event order at one instant,
+ *                       the issue boundary of a swap-in and the deadlock rule are this build's
+ *                       readings.
  *   lapo_select_swaps : pinned (two hand-worked examples, one where the SWDOA
  *                       order differs from the WDOA order; a dense-matrix
  *                       re-simulation in exact integers; monotone peaks and
@@ -715,4 +720,165 @@ int lapo_schedule_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint
     *late_ns = late;
     free(C); free(q);
     return LAPO_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* the schedule under a memory-load limit (Section IV-E, second half)        */
+/* ------------------------------------------------------------------------ */
+
+/* Section IV-E: with a stringent limit the load would exceed it because variables cannot be
+ * swapped out quickly enough; then the next Malloc is delayed until enough has been swapped out,
+ * and a swap-in can start only after something has been freed.  That is where overhead that
+ * cannot be hidden comes from.  This is a discrete-event simulation of one iteration:
+ *
+ *   compute   runs the steps in order.  Step t may start when the step before it has ended, every
+ *             listed variable with gap_hi == t is back (its swap-in has ended), and -- if the step
+ *             allocates anything -- the resident bytes plus the sizes allocated at step t stay
+ *             within the limit (it is the Malloc that is delayed).
+ *   resident  grows at a step's start by the sizes allocated there and at a swap-in's start;
+ *             shrinks at a step's end by the sizes freed there and at a swap-out's end.
+ *   swap-outs one stream, ascending (gap_lo, index); a job is issued when step gap_lo ends and
+ *             starts when it is issued and the stream is free.
+ *   swap-ins  a second stream, ascending (gap_hi, index); a job is issued when compute reaches the
+ *             step boundary at or before its planned start (lapo_schedule_swaps), not before
+ *             boundary gap_lo+1; it starts when it is issued, the stream is free, its own swap-out
+ *             has ended and resident + size <= limit.
+ *   at one instant: ends first (step, swap-out, swap-in), then starts in the order swap-out,
+ *             step, swap-in.
+ *   deadlock  if nothing runs and the next step cannot start, the limit is overridden once
+ *             (counted in *forced): for the step's allocations if only they are in the way,
+ *             else for the swap-in at the head of its stream.
+ * Listed variables with gap_hi == gap_lo are never swapped.
+ * Outputs: *total_ns end of the last step, *overhead_ns = total - sum of step_ns,
+ * *peak_resident the largest resident value, *forced as above. */
+int lapo_simulate_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                        const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                        const uint64_t *step_ns, double link_GBps, const uint32_t *swap_list, uint32_t k,
+                        uint64_t limit, uint64_t *total_ns, uint64_t *overhead_ns, uint64_t *peak_resident,
+                        uint32_t *forced)
+{
+    if (!size || !alloc || !free_ || !total_ns || !overhead_ns || !peak_resident || !forced) return LAPO_E_NULL;
+    if (k && !swap_list) return LAPO_E_NULL;
+    if (n == 0 || T == 0) return LAPO_E_SIZE;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps)) return LAPO_E_LINK;
+    const uint64_t bpus = (uint64_t)llround(link_GBps * 1000.0);
+    if (bpus == 0) return LAPO_E_LINK;
+    int rc = LAPO_E_NOMEM;
+    int64_t *os = (int64_t *)malloc(((size_t)k + 1) * 8), *oe = (int64_t *)malloc(((size_t)k + 1) * 8);
+    int64_t *is = (int64_t *)malloc(((size_t)k + 1) * 8), *ie = (int64_t *)malloc(((size_t)k + 1) * 8);
+    uint64_t *ld = (uint64_t *)malloc((size_t)T * 8), *C = (uint64_t *)malloc(((size_t)T + 1) * 8);
+    uint64_t *need = (uint64_t *)calloc(T, 8), *rel = (uint64_t *)calloc(T, 8);
+    sched_key *qo = (sched_key *)malloc(((size_t)k + 1) * sizeof(sched_key));
+    sched_key *qi = (sched_key *)malloc(((size_t)k + 1) * sizeof(sched_key));
+    uint32_t *kb = (uint32_t *)malloc(((size_t)k + 1) * 4);       /* issue boundary of each swap-in, by list position */
+    uint8_t *out_done = (uint8_t *)calloc((size_t)k + 1, 1), *back = (uint8_t *)calloc((size_t)k + 1, 1);
+    uint32_t *waiting = (uint32_t *)calloc(T, 4);                 /* listed variables still away that step t needs */
+    if (!os || !oe || !is || !ie || !ld || !C || !need || !rel || !qo || !qi || !kb || !out_done || !back || !waiting)
+        goto done;
+    {
+        uint64_t pk, late;
+        rc = lapo_schedule_swaps(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, swap_list, k, os, oe,
+                                 is, ie, ld, &pk, &late);
+        if (rc) goto done;
+    }
+    C[0] = 0;
+    for (uint32_t t = 0; t < T; ++t) C[t + 1] = C[t] + (step_ns ? step_ns[t] : 1000000u);
+    for (uint32_t i = 0; i < n; ++i) { need[alloc[i]] += size[i]; rel[free_[i] - 1] += size[i]; }
+    uint32_t m = 0;                                               /* jobs: listed variables with an idle gap */
+    for (uint32_t j = 0; j < k; ++j) {
+        const uint32_t v = swap_list[j];
+        const uint32_t tl = gap_lo ? gap_lo[v] : alloc[v], th = gap_hi ? gap_hi[v] : free_[v] - 1;
+        if (th <= tl) continue;
+        qo[m].step = tl; qo[m].var = v; qo[m].pos = j;
+        qi[m].step = th; qi[m].var = v; qi[m].pos = j;
+        ++m;
+        uint32_t b = 0;
+        for (uint32_t t = 0; t <= th; ++t) if ((int64_t)C[t] <= is[j]) b = t;
+        if (b < tl + 1) b = tl + 1;
+        kb[j] = b;
+        waiting[th] += 1;
+    }
+    qsort(qo, m, sizeof(sched_key), cmp_sched);
+    qsort(qi, m, sizeof(sched_key), cmp_sched);
+    {
+        uint64_t now = 0, R = 0, peak = 0;
+        uint32_t t = 0, nforced = 0;                 /* next step to start */
+        int step_running = 0, out_running = 0, in_running = 0;
+        uint64_t step_end = 0, out_end_t = 0, in_end_t = 0;
+        uint32_t o_issued = 0, o_next = 0;           /* swap-outs issued / started so far (in queue order) */
+        uint32_t i_issued = 0, i_next = 0;
+        uint32_t boundary = 0;                       /* step boundaries compute has reached */
+        while (i_issued < m && kb[qi[i_issued].pos] <= boundary) ++i_issued;
+        for (;;) {
+            /* ends at this instant */
+            if (step_running && step_end == now) {
+                step_running = 0;
+                R -= rel[t];
+                while (o_issued < m && qo[o_issued].step == t) ++o_issued;
+                ++t;
+                boundary = t;
+                while (i_issued < m && kb[qi[i_issued].pos] <= boundary) ++i_issued;
+            }
+            if (out_running && out_end_t == now) {
+                out_running = 0;
+                R -= size[qo[o_next].var];
+                out_done[qo[o_next].pos] = 1;
+                ++o_next;
+            }
+            if (in_running && in_end_t == now) {
+                in_running = 0;
+                back[qi[i_next].pos] = 1;
+                waiting[qi[i_next].step] -= 1;
+                ++i_next;
+            }
+            if (t == T && !step_running) break;
+            /* starts: swap-out, step, swap-in */
+            if (!out_running && o_next < o_issued) {
+                const uint32_t v = qo[o_next].var;
+                out_running = 1;
+                out_end_t = now + (size[v] * 1000u + bpus - 1) / bpus;
+            }
+            int step_mem_blocked = 0;
+            if (!step_running && t < T && waiting[t] == 0) {
+                if (need[t] == 0 || R + need[t] <= limit) {
+                    step_running = 1; R += need[t]; step_end = now + (C[t + 1] - C[t]);
+                    if (R > peak) peak = R;
+                } else step_mem_blocked = 1;
+            }
+            int in_mem_blocked = 0;
+            if (!in_running && i_next < i_issued && out_done[qi[i_next].pos]) {
+                const uint32_t v = qi[i_next].var;
+                if (R + size[v] <= limit) {
+                    in_running = 1; R += size[v]; in_end_t = now + (size[v] * 1000u + bpus - 1) / bpus;
+                    if (R > peak) peak = R;
+                } else in_mem_blocked = 1;
+            }
+            if (!step_running && !out_running && !in_running) {
+                /* nothing will ever change by itself: override the limit once */
+                ++nforced;
+                if (step_mem_blocked) {
+                    step_running = 1; R += need[t]; step_end = now + (C[t + 1] - C[t]);
+                } else if (in_mem_blocked) {
+                    const uint32_t v = qi[i_next].var;
+                    in_running = 1; R += size[v]; in_end_t = now + (size[v] * 1000u + bpus - 1) / bpus;
+                } else { rc = LAPO_E_TRACE; goto done; }            /* cannot happen on a valid trace */
+                if (R > peak) peak = R;
+            }
+            /* next instant */
+            uint64_t nx = UINT64_MAX;
+            if (step_running && step_end < nx) nx = step_end;
+            if (out_running && out_end_t < nx) nx = out_end_t;
+            if (in_running && in_end_t < nx) nx = in_end_t;
+            now = nx;
+        }
+        *total_ns = now;
+        *overhead_ns = now - C[T];
+        *peak_resident = peak;
+        *forced = nforced;
+    }
+    rc = LAPO_OK;
+done:
+    free(os); free(oe); free(is); free(ie); free(ld); free(C); free(need); free(rel); free(qo); free(qi); free(kb);
+    free(out_done); free(back); free(waiting);
+    return rc;
 }
