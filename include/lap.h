@@ -18,6 +18,7 @@
  *                     IV-A, IV-B): DOA, AOA, WDOA, and the drop of the peak
  *                     load when the variable is away for its idle gap.
  *   lap_schedule_swaps  the swap-out / swap-in plan of Section IV-E and the load under it.
+ *   lap_simulate_swaps  that plan replayed under a memory-load limit: the time a tight limit costs.
  *   lap_detect_iteration  finds one iteration in a recorded request stream (Section V).
  *   lap_select_swaps  AutoSwap selection (Section IV-D): candidates taken in
  *                     priority order until the peak load is within a limit,
@@ -127,7 +128,8 @@ enum {
     LAP_WS_VALIDATE = 3,
     LAP_WS_SELECT_SWAPS = 4,
     LAP_WS_DETECT_ITERATION = 5,  /* n_vars = number of requests */
-    LAP_WS_SCHEDULE_SWAPS = 6
+    LAP_WS_SCHEDULE_SWAPS = 6,
+    LAP_WS_SIMULATE_SWAPS = 7     /* B = number of runs Q */
 };
 
 /* Bytes of workspace the given call needs.  B is the number of orderings for PLAN_POOL, the
@@ -220,6 +222,30 @@ int lap_schedule_swaps(const lap_trace *trace, double link_GBps, const uint64_t 
                        const uint32_t *swap_list, uint32_t k,
                        int64_t *out_start, int64_t *out_end, int64_t *in_start, int64_t *in_end,
                        uint64_t *load_sched, uint64_t *peak_sched, uint64_t *late_ns,
+                       void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Section IV-E under a memory-load limit: one iteration replayed as a discrete-event machine, Q
+ * runs at once.  Run q swaps the first prefix_len[q] variables of swap_list (those with an idle
+ * gap) under limits[q] bytes.
+ *   compute   runs the steps in order; a step starts when the one before it has ended, every swapped
+ *             variable accessed at that step (gap_hi) is back, and -- if the step allocates -- resident
+ *             bytes + the bytes it allocates <= limit (the delayed Malloc)
+ *   swap-out  one stream, ascending (gap_lo, index); issued when step gap_lo ends
+ *   swap-in   a second stream, ascending (gap_hi, index); issued when compute reaches the step boundary
+ *             at or before its start in the plan of lap_schedule_swaps for these variables (not before
+ *             boundary gap_lo+1); starts when issued, the stream is free, its own swap-out has ended
+ *             and resident + size <= limit
+ *   resident  + at a step's start (its allocations) and a swap-in's start; - at a step's end (its frees)
+ *             and a swap-out's end
+ *   one instant: ends first, then starts in the order swap-out, step, swap-in.  If nothing runs and the
+ *   next step cannot start, the limit is overridden once (counted in forced) for the step's allocations,
+ *   else for the swap-in at the head of its stream.
+ * swap_list [k_max] device, distinct indices; prefix_len, limits [Q] host, Q <= 4096.
+ * Outputs [Q] device: total_ns (end of the last step), overhead_ns = total - sum of step_ns,
+ * peak_resident (largest resident value), forced. */
+int lap_simulate_swaps(const lap_trace *trace, double link_GBps, const uint32_t *swap_list, uint32_t k_max,
+                       const uint32_t *prefix_len, const uint64_t *limits, uint32_t Q,
+                       uint64_t *total_ns, uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced,
                        void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Section V: the requests of the first iterations are recorded in a list, and an iteration has

@@ -770,17 +770,11 @@ int lapo_simulate_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint
     uint64_t *need = (uint64_t *)calloc(T, 8), *rel = (uint64_t *)calloc(T, 8);
     sched_key *qo = (sched_key *)malloc(((size_t)k + 1) * sizeof(sched_key));
     sched_key *qi = (sched_key *)malloc(((size_t)k + 1) * sizeof(sched_key));
-    uint32_t *kb = (uint32_t *)malloc(((size_t)k + 1) * 4);       /* issue boundary of each swap-in, by list position */
+    uint32_t *kb = (uint32_t *)calloc((size_t)k + 1, 4);          /* issue boundary of each swap-in, by list position */
     uint8_t *out_done = (uint8_t *)calloc((size_t)k + 1, 1), *back = (uint8_t *)calloc((size_t)k + 1, 1);
     uint32_t *waiting = (uint32_t *)calloc(T, 4);                 /* listed variables still away that step t needs */
     if (!os || !oe || !is || !ie || !ld || !C || !need || !rel || !qo || !qi || !kb || !out_done || !back || !waiting)
         goto done;
-    {
-        uint64_t pk, late;
-        rc = lapo_schedule_swaps(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, swap_list, k, os, oe,
-                                 is, ie, ld, &pk, &late);
-        if (rc) goto done;
-    }
     C[0] = 0;
     for (uint32_t t = 0; t < T; ++t) C[t + 1] = C[t] + (step_ns ? step_ns[t] : 1000000u);
     for (uint32_t i = 0; i < n; ++i) { need[alloc[i]] += size[i]; rel[free_[i] - 1] += size[i]; }
@@ -789,9 +783,22 @@ int lapo_simulate_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint
         const uint32_t v = swap_list[j];
         const uint32_t tl = gap_lo ? gap_lo[v] : alloc[v], th = gap_hi ? gap_hi[v] : free_[v] - 1;
         if (th <= tl) continue;
-        qo[m].step = tl; qo[m].var = v; qo[m].pos = j;
-        qi[m].step = th; qi[m].var = v; qi[m].pos = j;
+        qo[m].step = tl; qo[m].var = v; qo[m].pos = m;
+        qi[m].step = th; qi[m].var = v; qi[m].pos = m;
+        kb[m] = v;                                                /* for now: the m-th job's variable */
         ++m;
+    }
+    {
+        /* the plan for exactly these jobs gives the swap-in starts */
+        uint64_t pk, late;
+        rc = lapo_schedule_swaps(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, kb, m, os, oe,
+                                 is, ie, ld, &pk, &late);
+        if (rc) goto done;
+        rc = LAPO_E_NOMEM;
+    }
+    for (uint32_t j = 0; j < m; ++j) {
+        const uint32_t v = kb[j];
+        const uint32_t tl = gap_lo ? gap_lo[v] : alloc[v], th = gap_hi ? gap_hi[v] : free_[v] - 1;
         uint32_t b = 0;
         for (uint32_t t = 0; t <= th; ++t) if ((int64_t)C[t] <= is[j]) b = t;
         if (b < tl + 1) b = tl + 1;

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     schedule_swaps,
     score_swaps,
     select_swaps,
+    simulate_swaps,
     status_string,
     validate_trace,
     workspace_bytes,

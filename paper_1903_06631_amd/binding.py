@@ -13,7 +13,7 @@ _lib = None
 
 EXPORTS = [
     "lap_workspace_bytes", "lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
-    "lap_detect_iteration", "lap_schedule_swaps",
+    "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps",
     "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms",
 ]
 
@@ -74,6 +74,10 @@ def load_library():
     lib.lap_schedule_swaps.argtypes = [C.POINTER(_Trace), C.c_double, C.c_void_p, C.c_void_p, C.c_uint32,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lap_simulate_swaps.restype = C.c_int
+    lib.lap_simulate_swaps.argtypes = [C.POINTER(_Trace), C.c_double, C.c_void_p, C.c_uint32, C.c_void_p,
+                                       C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lap_detect_iteration.restype = C.c_int
     lib.lap_detect_iteration.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
@@ -300,6 +304,35 @@ def schedule_swaps(dt: DeviceTrace, link_GBps: float, swap_list, load=None, sync
                                 p(out["peak"]), p(out["late_ns"]), ws.data_ptr(), need, _stream_ptr(dt.device))
     if rc:
         raise LapError(rc, "lap_schedule_swaps")
+    if sync:
+        torch.cuda.current_stream(dt.device).synchronize()
+    return out
+
+
+def simulate_swaps(dt: DeviceTrace, link_GBps: float, swap_list, prefix_len: Sequence[int],
+                   limits: Sequence[int], sync: bool = True):
+    """lap_simulate_swaps: Q = len(limits) runs; returns device tensors total_ns, overhead_ns, peak_resident
+    (int64 bit patterns) and forced (int32), one entry per run."""
+    torch = _torch()
+    lib = load_library()
+    assert swap_list.dtype == torch.int32 and swap_list.is_contiguous()
+    Q = len(limits)
+    assert len(prefix_len) == Q
+    pl = (C.c_uint32 * max(Q, 1))(*[int(x) for x in prefix_len])
+    lm = (C.c_uint64 * max(Q, 1))(*[int(x) for x in limits])
+    out = dict(total_ns=torch.empty(Q, dtype=torch.int64, device=dt.device),
+               overhead_ns=torch.empty(Q, dtype=torch.int64, device=dt.device),
+               peak_resident=torch.empty(Q, dtype=torch.int64, device=dt.device),
+               forced=torch.empty(Q, dtype=torch.int32, device=dt.device))
+    ws, need = dt.workspace(7, Q)
+    tr = dt.c_struct()
+    k = swap_list.numel()
+    rc = lib.lap_simulate_swaps(C.byref(tr), float(link_GBps), swap_list.data_ptr() if k else None, k, pl, lm, Q,
+                                out["total_ns"].data_ptr(), out["overhead_ns"].data_ptr(),
+                                out["peak_resident"].data_ptr(), out["forced"].data_ptr(), ws.data_ptr(), need,
+                                _stream_ptr(dt.device))
+    if rc:
+        raise LapError(rc, "lap_simulate_swaps")
     if sync:
         torch.cuda.current_stream(dt.device).synchronize()
     return out

@@ -9,7 +9,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblap.so")
 SOURCES = ["api.hip", "load_profile.hip", "orderings.hip", "place_fast.hip", "place_wide.hip", "swap_scores.hip",
            "select_swaps.hip", "detect_iteration.hip",
-           "schedule_swaps.hip"]
+           "schedule_swaps.hip", "simulate_swaps.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -78,6 +78,18 @@ size_t ws_schedule(uint32_t n, uint32_t T)
            + 4 * up(N * 4) + 2 * ALIGN;                // posmap, perm_lo, perm_hi, sort scratch; kinds, seeds
 }
 
+constexpr uint32_t SIM_MAX_RUNS = 4096;
+
+size_t ws_simulate(uint32_t n, uint32_t T, uint32_t Q)
+{
+    const size_t t1 = (size_t)T + 1, N = n;
+    return up((size_t)T * 8) + 5 * up(t1 * 8) + 2 * ALIGN          // load, delta, C, S, PM, SM; peak, t_peak
+           + 2 * up((size_t)T * 8)                                 // bytes allocated / freed per step
+           + 6 * up(N * 4) + 3 * ALIGN                             // posmap, perm x2, sort scratch, jobs x2; kinds, seeds, m
+           + up((size_t)SIM_MAX_RUNS * 4) + up((size_t)SIM_MAX_RUNS * 8)   // prefix lengths, limits
+           + (size_t)Q * (up(N * 4) + up(N));                      // per run: issue boundaries, swap-out flags
+}
+
 size_t ws_select(uint32_t n, uint32_t T, uint32_t K)
 {
     const size_t N = n;
@@ -169,6 +181,7 @@ size_t lap_workspace_bytes(int which, uint32_t n_vars, uint32_t n_steps, uint32_
     case LAP_WS_SELECT_SWAPS: return ws_select(n_vars, n_steps, B);
     case LAP_WS_DETECT_ITERATION: return up(((size_t)n_vars + 1) * 8);
     case LAP_WS_SCHEDULE_SWAPS: return ws_schedule(n_vars, n_steps);
+    case LAP_WS_SIMULATE_SWAPS: return ws_simulate(n_vars, n_steps, B);
     default: return 0;
     }
 }
@@ -493,6 +506,82 @@ int lap_schedule_swaps(const lap_trace *tr, double link_GBps, const uint64_t *lo
     LAP_HIP(lap::launch_schedule_swaps(n, T, k, tr->size, step_lo, step_hi, tr->gap_hi ? 0u : 1u, C, perm_lo, perm_hi,
                                        posmap, swap_list, (uint64_t)bpus, out_start, out_end, in_start, in_end, diff,
                                        late_ns, load, load_sched, peak_sched, st));
+    return LAP_OK;
+}
+
+int lap_simulate_swaps(const lap_trace *tr, double link_GBps, const uint32_t *swap_list, uint32_t k_max,
+                       const uint32_t *prefix_len, const uint64_t *limits, uint32_t Q, uint64_t *total_ns,
+                       uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced, void *ws, size_t ws_bytes,
+                       void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!prefix_len || !limits || !total_ns || !overhead_ns || !peak_resident || !forced) return LAP_E_NULL;
+    if (k_max && !swap_list) return LAP_E_NULL;
+    if (Q == 0 || Q > SIM_MAX_RUNS || k_max > tr->n_vars) return LAP_E_SIZE;
+    for (uint32_t q = 0; q < Q; ++q)
+        if (prefix_len[q] > k_max) return LAP_E_SIZE;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps) || link_GBps * 1000.0 >= 9.0e18) return LAP_E_LINK;
+    const long long bpus = llround(link_GBps * 1000.0);
+    if (bpus <= 0) return LAP_E_LINK;
+    const uint32_t n = tr->n_vars, T = tr->n_steps;
+    rc = check_ws(ws, ws_bytes, ws_simulate(n, T, Q));
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t t1 = (size_t)T + 1;
+    Carver c(ws);
+    uint64_t *load_ws = c.take<uint64_t>(T);
+    uint64_t *delta = c.take<uint64_t>(t1);
+    uint64_t *C = c.take<uint64_t>(t1);
+    uint64_t *S = c.take<uint64_t>(t1);
+    uint64_t *PM = c.take<uint64_t>(t1);
+    uint64_t *SM = c.take<uint64_t>(t1);
+    uint64_t *peak = c.take<uint64_t>(1);
+    uint32_t *t_peak = c.take<uint32_t>(1);
+    uint64_t *need = c.take<uint64_t>(T);
+    uint64_t *rel = c.take<uint64_t>(T);
+    uint32_t *posmap = c.take<uint32_t>(n);
+    uint32_t *perm_lo = c.take<uint32_t>(n);
+    uint32_t *perm_hi = c.take<uint32_t>(n);
+    uint32_t *tmp = c.take<uint32_t>(n);
+    uint32_t *jobs_lo = c.take<uint32_t>(n);
+    uint32_t *jobs_hi = c.take<uint32_t>(n);
+    uint32_t *kinds = c.take<uint32_t>(1);
+    uint64_t *seeds = c.take<uint64_t>(1);
+    uint32_t *m = c.take<uint32_t>(1);
+    uint32_t *d_prefix = c.take<uint32_t>(SIM_MAX_RUNS);
+    uint64_t *d_limits = c.take<uint64_t>(SIM_MAX_RUNS);
+    uint32_t *kb = c.take<uint32_t>(0);
+    c.used += (size_t)Q * up((size_t)n * 4);
+    uint8_t *out_done = c.take<uint8_t>(0);
+    c.used += (size_t)Q * up((size_t)n);
+
+    static thread_local std::vector<uint32_t> hp;
+    static thread_local std::vector<uint64_t> hl;
+    hp.assign(prefix_len, prefix_len + Q);
+    hl.assign(limits, limits + Q);
+    LAP_HIP(hipMemcpyAsync(d_prefix, hp.data(), (size_t)Q * 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(hipMemcpyAsync(d_limits, hl.data(), (size_t)Q * 8, hipMemcpyHostToDevice, st));
+    // the step start times come from the same prefix kernel as the scores (it needs a load curve)
+    rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
+    if (rc) return rc;
+    LAP_HIP(lap::launch_swap_prefix(T, load_ws, tr->step_ns, C, S, PM, SM, peak, t_peak, st));
+    static const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
+    LAP_HIP(hipMemcpyAsync(kinds, &h_kind, 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_fill_u64(seeds, 1, 0, st));
+    const uint32_t *step_lo = tr->gap_lo ? tr->gap_lo : tr->alloc;
+    const uint32_t *step_hi = tr->gap_hi ? tr->gap_hi : tr->free_;
+    LAP_HIP(lap::launch_sort_perm(n, 1, tr->size, step_lo, tr->free_, kinds, seeds, perm_lo, tmp, false, st));
+    LAP_HIP(lap::launch_sort_perm(n, 1, tr->size, step_hi, tr->free_, kinds, seeds, perm_hi, tmp, false, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)posmap, ((size_t)n + 1) / 2, ~0ull, st));
+    LAP_HIP(lap::launch_sched_mark(n, k_max, swap_list, posmap, st));
+    LAP_HIP(lap::launch_fill_u64(need, T, 0, st));
+    LAP_HIP(lap::launch_fill_u64(rel, T, 0, st));
+    // the per-run regions use a stride of n entries
+    LAP_HIP(lap::launch_simulate_swaps(n, T, Q, n, tr->size, tr->alloc, tr->free_, step_lo, step_hi,
+                                       tr->gap_hi ? 0u : 1u, C, need, rel, swap_list, perm_lo, perm_hi, posmap,
+                                       jobs_lo, jobs_hi, m, d_prefix, d_limits, kb, out_done, (uint64_t)bpus,
+                                       total_ns, overhead_ns, peak_resident, forced, st));
     return LAP_OK;
 }
 

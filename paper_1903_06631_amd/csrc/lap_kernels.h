@@ -91,6 +91,16 @@ hipError_t launch_schedule_swaps(uint32_t n, uint32_t T, uint32_t k, const uint6
                                  int64_t *in_start, int64_t *in_end, uint64_t *diff, uint64_t *late,
                                  const uint64_t *load, uint64_t *load_sched, uint64_t *peak, hipStream_t st);
 
+hipError_t launch_simulate_swaps(uint32_t n, uint32_t T, uint32_t Q, uint32_t kmax, const uint64_t *size,
+                                 const uint32_t *alloc, const uint32_t *free_, const uint32_t *step_lo,
+                                 const uint32_t *step_hi, uint32_t hi_minus, const uint64_t *C, uint64_t *need,
+                                 uint64_t *rel, const uint32_t *list, const uint32_t *perm_lo,
+                                 const uint32_t *perm_hi, const uint32_t *posmap, uint32_t *jobs_lo,
+                                 uint32_t *jobs_hi, uint32_t *m, const uint32_t *prefix, const uint64_t *limits,
+                                 uint32_t *kb, uint8_t *out_done, uint64_t bpus, uint64_t *total_ns,
+                                 uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced, hipStream_t st);
+hipError_t launch_sched_mark(uint32_t n, uint32_t k, const uint32_t *list, uint32_t *posmap, hipStream_t st);
+
 hipError_t launch_detect_iteration(const uint64_t *tokens, uint32_t M, uint32_t min_period, uint64_t *P,
                                    uint32_t *period, hipStream_t st);
 

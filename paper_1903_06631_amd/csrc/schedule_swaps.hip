@@ -181,6 +181,12 @@ __global__ __launch_bounds__(SC_THREADS) void k_sched_load(uint32_t T, const uin
     }
 }
 
+hipError_t launch_sched_mark(uint32_t n, uint32_t k, const uint32_t *list, uint32_t *posmap, hipStream_t st)
+{
+    if (k) hipLaunchKernelGGL(k_sched_mark, dim3((k + 255) / 256), dim3(256), 0, st, n, k, list, posmap);
+    return hipGetLastError();
+}
+
 hipError_t launch_schedule_swaps(uint32_t n, uint32_t T, uint32_t k, const uint64_t *size, const uint32_t *step_lo,
                                  const uint32_t *step_hi, uint32_t hi_minus, const uint64_t *C,
                                  const uint32_t *perm_lo, const uint32_t *perm_hi, uint32_t *posmap,

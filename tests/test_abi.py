@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(lap):
     hdr = open(os.path.join(ROOT, "include", "lap.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(lap_[a-z_]+)\s*\(", hdr))
-    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps", "lap_detect_iteration", "lap_schedule_swaps",
+    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps", "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps",
             "lap_workspace_bytes",
             "lap_validate_trace", "lap_status_string"} <= declared
     lib = lap.load_library()
@@ -110,6 +110,14 @@ def test_argument_errors(lap):
                                               kw.get("ws", 1 << 30), None)
     assert sch(lst=None) == -1 and sch(load=None) == -1 and sch(k=5) == -2 and sch(link=-1.0) == -5
     assert sch(ws=lap.workspace_bytes(6, 4, 3) - 1) == -3
+    # schedule under a limit
+    pl = (C.c_uint32 * 2)(1, 2)
+    lm = (C.c_uint64 * 2)(10, 20)
+    sim = lambda **kw: lib.lap_simulate_swaps(C.byref(good), kw.get("link", 1.0), fake, kw.get("k", 2), kw.get("pl", pl),
+                                              lm, kw.get("Q", 2), kw.get("out", fake), fake, fake, fake, fake,
+                                              kw.get("ws", 1 << 30), None)
+    assert sim(pl=None) == -1 and sim(out=None) == -1 and sim(Q=0) == -2 and sim(Q=5000) == -2 and sim(k=1) == -2
+    assert sim(link=0.0) == -5 and sim(ws=lap.workspace_bytes(7, 4, 3, 2) - 1) == -3
     # iteration detection
     assert lib.lap_detect_iteration(None, 8, 1, fake, fake, 1 << 20, None) == -1
     assert lib.lap_detect_iteration(fake, 0, 1, fake, fake, 1 << 20, None) == -2
