@@ -160,6 +160,39 @@ def main() -> int:
                                        score_kinds=5, limits=len(limits), candidates=int(sel["n_cand"].item()),
                                        load_min_over_peak=int(u64(sel["load_min"])[0]) / peak,
                                        lowest_peak_over_peak=int(u64(sel["peak_after"])[3, 0]) / peak))
+        # the swap plan for what the selection picked at 60 % of the peak, and that plan replayed
+        # under every limit of the sweep (SWDOA order)
+        row = 3
+        nsel = sel["n_selected"].cpu().numpy().view(np.uint32)[row]
+        order = sel["order"][row].contiguous()
+        k60 = int(nsel[12])
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        plan = lap.schedule_swaps(dt, tr.meta["link_GBps"], order[:k60].contiguous(), load=lp["load"])
+        plan_s = time.perf_counter() - c0
+        c0 = time.perf_counter()
+        sim = lap.simulate_swaps(dt, tr.meta["link_GBps"], order[:int(nsel.max())].contiguous(),
+                                 [int(x) for x in nsel], limits)
+        sim_s = time.perf_counter() - c0
+        ovh = u64(sim["overhead_ns"]).astype(np.float64) / float(u64(sim["total_ns"])[-1])
+        extra["schedule_swaps"] = dict(call_ms=1e3 * plan_s, swapped=k60, limit_over_peak=0.6,
+                                       peak_under_plan_over_peak=int(u64(plan["peak"])[0]) / peak,
+                                       late_ns=int(u64(plan["late_ns"])[0]))
+        extra["simulate_swaps"] = dict(call_ms=1e3 * sim_s, runs=len(limits),
+                                       overhead_over_iteration_by_limit={f"{q * 5}%": round(float(ovh[q]), 4)
+                                                                         for q in range(6, 21, 2)},
+                                       forced_at_60pct=int(sim["forced"].cpu().numpy().view(np.uint32)[12]))
+        # iteration detection on a request stream of two iterations of this trace after a warm-up
+        from traces.requests import iteration_tokens, request_stream
+        it = iteration_tokens(tr)
+        stream = request_stream(it, 2, 1000, 0, seed=1)
+        tok = torch.from_numpy(stream.view(np.int64)).to(dev)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        per = lap.detect_iteration(tok, 64)
+        det_s = time.perf_counter() - c0
+        assert int(per.item()) == len(it)
+        extra["detect_iteration"] = dict(call_ms=1e3 * det_s, requests=len(stream), period=len(it))
         lap.plan_pool(dt, kinds[:1], seeds[:1], want_all=False)      # leave the profile slots on first-fit
 
     # The load-profile kernel on the largest BASELINE trace moves 3.2 MB (launch-latency bound), so

@@ -81,6 +81,32 @@ def test_full_size_best_fit(lap, oracle_mod):
         assert _neighbours_disjoint(tr, u64(all_off[b]), range(tr.n_steps)), f"ordering {b}"
 
 
+def test_full_size_plan_and_replay_of_swaps(lap, oracle_mod):
+    """Config 4 (11 000 candidates, 14 000 steps): the swap plan of the WDOA order's prefixes and its
+    replay under limits, against the oracle."""
+    import torch
+    tr = make_config(4)
+    link, mb = tr.meta["link_GBps"], tr.meta["min_bytes"]
+    dt = lap.DeviceTrace(tr)
+    _, peak, _ = oracle_mod.load_profile(tr)
+    limits = [peak // 2, peak // 4, peak // 20]
+    sel = oracle_mod.select_swaps(tr, link, mb, 2, limits)
+    order = sel["order"]
+    lst = torch.from_numpy(order.astype(np.uint32).view(np.int32)).cuda()
+    k = int(sel["n_selected"][1])
+    got = lap.schedule_swaps(dt, link, lst[:k].contiguous())
+    ref = oracle_mod.schedule_swaps(tr, link, order[:k])
+    for name in ("out_start", "out_end", "in_start", "in_end"):
+        assert np.array_equal(got[name].cpu().numpy(), ref[name]), name
+    assert np.array_equal(u64(got["load"]), ref["load"]) and int(u64(got["late_ns"])[0]) == ref["late_ns"]
+    runs = [(int(sel["n_selected"][q]), limits[q]) for q in range(3)] + [(len(order), 0)]
+    sim = lap.simulate_swaps(dt, link, lst, [r[0] for r in runs], [r[1] for r in runs])
+    for q, (kq, lim) in enumerate(runs):
+        r = oracle_mod.simulate_swaps(tr, link, order[:kq], lim)
+        assert int(u64(sim["total_ns"])[q]) == r["total_ns"] and int(u64(sim["peak_resident"])[q]) == r["peak_resident"]
+        assert int(sim["forced"].cpu().numpy().view(np.uint32)[q]) == r["forced"]
+
+
 def test_full_size_load_and_scores(lap, oracle_mod):
     tr = make_config(4)
     dt = lap.DeviceTrace(tr)
