@@ -238,3 +238,29 @@ def simulate_swaps(tr, link_GBps: float, swap_list, limit: int, use_gaps=True):
         raise RuntimeError(f"lapo_simulate_swaps rc={rc}")
     return dict(total_ns=int(total.value), overhead_ns=int(over.value), peak_resident=int(peak.value),
                 forced=int(forced.value))
+
+
+def evaluate_weights(tr, link_GBps: float, min_bytes: int, weights, limit: int, use_gaps=True):
+    lib = _load()
+    w = _c(weights, np.float64).reshape(-1, 4)
+    W, n = len(w), tr.n_vars
+    order = np.zeros((W, n), np.uint32)
+    n_sel = np.zeros(W, np.uint32)
+    peak_after = np.zeros(W, np.uint64)
+    overhead = np.zeros(W, np.uint64)
+    forced = np.zeros(W, np.uint32)
+    swdoa = np.zeros(n, np.uint64)
+    n_cand, best = C.c_uint32(0), C.c_uint32(0)
+    rc = lib.lapo_evaluate_weights(
+        C.c_uint32(n), C.c_uint32(tr.n_steps), _opt(tr.size, np.uint64), _opt(tr.alloc, np.uint32),
+        _opt(tr.free, np.uint32), _opt(tr.gap_lo if use_gaps else None, np.uint32),
+        _opt(tr.gap_hi if use_gaps else None, np.uint32), _opt(tr.step_ns, np.uint64), C.c_double(link_GBps),
+        C.c_uint64(min_bytes), w.ctypes.data_as(C.c_void_p), C.c_uint32(W), C.c_uint64(limit),
+        order.ctypes.data_as(C.c_void_p), C.byref(n_cand), n_sel.ctypes.data_as(C.c_void_p),
+        peak_after.ctypes.data_as(C.c_void_p), overhead.ctypes.data_as(C.c_void_p),
+        forced.ctypes.data_as(C.c_void_p), C.byref(best), swdoa.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise RuntimeError(f"lapo_evaluate_weights rc={rc}")
+    nc = int(n_cand.value)
+    return dict(order=order[:, :nc], n_cand=nc, n_selected=n_sel, peak_after=peak_after, overhead_ns=overhead,
+                forced=forced, best=int(best.value), swdoa=swdoa)

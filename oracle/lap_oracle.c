@@ -49,6 +49,10 @@
  *                       limit is loose and nothing is late).  The event order at one instant,
  *                       the issue boundary of a swap-in and the deadlock rule are this build's
  *                       readings.
+ *   lapo_evaluate_weights : a composition of the pinned pieces above; pinned as such (unit
+ *                       weight vectors reproduce the four basic orders, scaling by a
+ *                       power of two changes nothing, best = argmin by brute force,
+ *                       hand-worked SWDOA values).
  *   lapo_select_swaps : pinned (two hand-worked examples, one where the SWDOA
  *                       order differs from the WDOA order; a dense-matrix
  *                       re-simulation in exact integers; monotone peaks and
@@ -499,16 +503,21 @@ static void absent_window(uint32_t T, const uint64_t *C, uint32_t tl, uint32_t t
  * the peak reached (all candidates when the limit is out of reach).
  * load_min (Section VI-B1): the peak of the curve with every candidate away on ALL its idle
  * steps gap_lo+1 .. gap_hi-1 (swapped out and in synchronously, transfers not hidden). */
-int lapo_select_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
-                      const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
-                      const uint64_t *step_ns, double link_GBps, uint64_t min_bytes, uint32_t score_kind,
-                      const uint64_t *limits, uint32_t n_limits,
-                      uint32_t *order, uint32_t *rank, uint32_t *n_cand, uint64_t *peaks,
-                      uint32_t *n_selected, uint64_t *peak_after, uint64_t *load_min)
+enum { LAPO_PS_CUSTOM = 5 };
+
+/* score_kind 5 walks by a caller-supplied binary64 score per variable (`custom`); pick_wdoa, if
+ * given, receives for every candidate the WDOA it had on the current curve when it was picked
+ * (for the SWDOA walk that is the value the pick was decided on). */
+static int select_core(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                       const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                       const uint64_t *step_ns, double link_GBps, uint64_t min_bytes, uint32_t score_kind,
+                       const double *custom, const uint64_t *limits, uint32_t n_limits,
+                       uint32_t *order, uint32_t *rank, uint32_t *n_cand, uint64_t *peaks,
+                       uint32_t *n_selected, uint64_t *peak_after, uint64_t *load_min, uint64_t *pick_wdoa)
 {
     if (!order || !rank || !n_cand || !peaks || !load_min) return LAPO_E_NULL;
     if (n_limits && (!limits || !n_selected || !peak_after)) return LAPO_E_NULL;
-    if (score_kind > 4) return LAPO_E_ORDERING;
+    if (score_kind > 5 || (score_kind == 5 && !custom)) return LAPO_E_ORDERING;
     uint8_t *cand = (uint8_t *)malloc(n);
     int64_t *doa = (int64_t *)malloc((size_t)n * 8);
     double *aoa = (double *)malloc((size_t)n * 8);
@@ -576,9 +585,16 @@ int lapo_select_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32
                 case LAPO_PS_DOA: better = doa[i] > doa[best]; break;
                 case LAPO_PS_AOA: better = aoa[i] > aoa[best]; break;
                 case LAPO_PS_PEAK_CUT: better = cut[i] > cut[best]; break;
+                case LAPO_PS_CUSTOM: better = custom[i] > custom[best]; break;
                 default: better = wdoa[i] > wdoa[best]; break;
             }
             if (better) best = i;
+        }
+        if (pick_wdoa) {
+            const uint32_t tl = gap_lo ? gap_lo[best] : alloc[best], th = gap_hi ? gap_hi[best] : free_[best] - 1;
+            uint64_t area = 0;
+            for (uint32_t t = tl + 1; t < th; ++t) area += load[t];
+            pick_wdoa[best] = area;
         }
         taken[best] = 1;
         order[k] = best;
@@ -598,6 +614,18 @@ int lapo_select_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32
 done:
     free(cand); free(doa); free(aoa); free(wdoa); free(cut); free(load); free(C); free(wlo); free(whi); free(taken);
     return rc;
+}
+
+int lapo_select_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                      const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                      const uint64_t *step_ns, double link_GBps, uint64_t min_bytes, uint32_t score_kind,
+                      const uint64_t *limits, uint32_t n_limits,
+                      uint32_t *order, uint32_t *rank, uint32_t *n_cand, uint64_t *peaks,
+                      uint32_t *n_selected, uint64_t *peak_after, uint64_t *load_min)
+{
+    if (score_kind > 4) return LAPO_E_ORDERING;
+    return select_core(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, min_bytes, score_kind, NULL,
+                       limits, n_limits, order, rank, n_cand, peaks, n_selected, peak_after, load_min, NULL);
 }
 
 /* ------------------------------------------------------------------------ */
@@ -887,5 +915,79 @@ int lapo_simulate_swaps(uint32_t n, uint32_t T, const uint64_t *size, const uint
 done:
     free(os); free(oe); free(is); free(ie); free(ld); free(C); free(need); free(rel); free(qo); free(qi); free(kb);
     free(out_done); free(back); free(waiting);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* aggregated priority score (Section IV-C) evaluated for many weight vectors */
+/* ------------------------------------------------------------------------ */
+
+/* Section IV-C (Eq. 3): the aggregated score is a linear combination of the four basic scores,
+ *     BO = a*AOA + b*DOA + c*WDOA + d*SWDOA,
+ * and its weights are tuned against the communication overhead the resulting schedule causes.
+ * Here the weights apply to the RAW scores (standardising a score is an affine map, so for the
+ * order it induces it only rescales that score's weight; the caller folds 1/sigma in), SWDOA_i
+ * is the WDOA variable i had on the reduced curve when the SWDOA walk picked it, the overhead is
+ * the one lapo_simulate_swaps reports, and the optimiser is whoever calls this with weight
+ * vectors: for each of W vectors (a, b, c, d) the candidates are walked by BO (one binary64
+ * expression, evaluated ((a*AOA + b*DOA) + c*WDOA) + d*SWDOA without contraction; ties: lower
+ * index) down to `limit`, and that selection is replayed under the limit.
+ * Outputs per vector: order (row of n, first *n_cand valid), n_selected, peak_after,
+ * overhead_ns, forced; *best = the vector with the least overhead (lowest index on ties);
+ * swdoa[n] = the SWDOA values used (0 for non-candidates). */
+int lapo_evaluate_weights(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+                          const uint32_t *free_, const uint32_t *gap_lo, const uint32_t *gap_hi,
+                          const uint64_t *step_ns, double link_GBps, uint64_t min_bytes,
+                          const double *weights, uint32_t W, uint64_t limit,
+                          uint32_t *order, uint32_t *n_cand, uint32_t *n_selected, uint64_t *peak_after,
+                          uint64_t *overhead_ns, uint32_t *forced, uint32_t *best, uint64_t *swdoa)
+{
+    if (!weights || !order || !n_cand || !n_selected || !peak_after || !overhead_ns || !forced || !best || !swdoa)
+        return LAPO_E_NULL;
+    if (W == 0) return LAPO_E_SIZE;
+    uint8_t *cand = (uint8_t *)malloc(n);
+    int64_t *doa = (int64_t *)malloc((size_t)n * 8);
+    double *aoa = (double *)malloc((size_t)n * 8), *bo = (double *)malloc((size_t)n * 8);
+    uint64_t *wdoa = (uint64_t *)malloc((size_t)n * 8), *cut = (uint64_t *)malloc((size_t)n * 8);
+    uint32_t *rank = (uint32_t *)malloc((size_t)n * 4), *ord = (uint32_t *)malloc((size_t)n * 4);
+    uint64_t *peaks = (uint64_t *)malloc(((size_t)n + 1) * 8);
+    int rc = LAPO_E_NOMEM;
+    if (!cand || !doa || !aoa || !bo || !wdoa || !cut || !rank || !ord || !peaks) goto done;
+    rc = lapo_score_swaps(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, min_bytes, cand, doa, aoa,
+                          wdoa, cut);
+    if (rc) goto done;
+    {
+        uint64_t lm;
+        for (uint32_t i = 0; i < n; ++i) swdoa[i] = 0;
+        rc = select_core(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, min_bytes, LAPO_PS_SWDOA,
+                         NULL, NULL, 0, ord, rank, n_cand, peaks, NULL, NULL, &lm, swdoa);
+        if (rc) goto done;
+    }
+    for (uint32_t w = 0; w < W; ++w) {
+        const double a = weights[4 * w], b = weights[4 * w + 1], c = weights[4 * w + 2], d = weights[4 * w + 3];
+        for (uint32_t i = 0; i < n; ++i) {
+            const double t1 = a * aoa[i], t2 = b * (double)doa[i];
+            const double t3 = t1 + t2, t4 = c * (double)wdoa[i];
+            const double t5 = t3 + t4, t6 = d * (double)swdoa[i];
+            bo[i] = t5 + t6;
+        }
+        uint32_t nc;
+        uint64_t lm;
+        rc = select_core(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps, min_bytes, LAPO_PS_CUSTOM, bo,
+                         &limit, 1, order + (size_t)w * n, rank, &nc, peaks, &n_selected[w], &peak_after[w], &lm,
+                         NULL);
+        if (rc) goto done;
+        uint64_t total, pk;
+        rc = lapo_simulate_swaps(n, T, size, alloc, free_, gap_lo, gap_hi, step_ns, link_GBps,
+                                 order + (size_t)w * n, n_selected[w], limit, &total, &overhead_ns[w], &pk,
+                                 &forced[w]);
+        if (rc) goto done;
+    }
+    *best = 0;
+    for (uint32_t w = 1; w < W; ++w)
+        if (overhead_ns[w] < overhead_ns[*best]) *best = w;
+    rc = LAPO_OK;
+done:
+    free(cand); free(doa); free(aoa); free(bo); free(wdoa); free(cut); free(rank); free(ord); free(peaks);
     return rc;
 }
