@@ -19,6 +19,8 @@
  *                     load when the variable is away for its idle gap.
  *   lap_schedule_swaps  the swap-out / swap-in plan of Section IV-E and the load under it.
  *   lap_simulate_swaps  that plan replayed under a memory-load limit: the time a tight limit costs.
+ *   lap_evaluate_weights  many weight vectors of the aggregated score (Section IV-C), each
+ *                     walked to a limit and replayed: the overhead every vector would cause.
  *   lap_detect_iteration  finds one iteration in a recorded request stream (Section V).
  *   lap_select_swaps  AutoSwap selection (Section IV-D): candidates taken in
  *                     priority order until the peak load is within a limit,
@@ -67,7 +69,7 @@ enum {
     LAP_E_NULL = -1,       /* a required pointer is NULL (or only one of gap_lo/gap_hi given) */
     LAP_E_SIZE = -2,       /* n_vars, n_steps or B is 0, or a size exceeds the supported maximum */
     LAP_E_WORKSPACE = -3,  /* ws is NULL, misaligned or smaller than lap_workspace_bytes() */
-    LAP_E_ORDERING = -4,   /* unknown ordering or score kind, or NULL permutation for LAP_ORD_EXPLICIT */
+    LAP_E_ORDERING = -4,   /* unknown ordering / score kind / fit, NULL explicit permutation, non-finite weight */
     LAP_E_LINK = -5,       /* link_GBps <= 0, not finite, or rounds to 0 bytes per microsecond */
     LAP_E_TRACE = -6,      /* size 0, alloc >= free, free > n_steps, gap outside [alloc, free-1], step_ns 0 */
     LAP_E_RANGE = -7,      /* sum of sizes >= 2^63, a size >= 2^53, sum of step_ns >= 2^53, max size * n_steps >= 2^64 */
@@ -129,7 +131,8 @@ enum {
     LAP_WS_SELECT_SWAPS = 4,
     LAP_WS_DETECT_ITERATION = 5,  /* n_vars = number of requests */
     LAP_WS_SCHEDULE_SWAPS = 6,
-    LAP_WS_SIMULATE_SWAPS = 7     /* B = number of runs Q */
+    LAP_WS_SIMULATE_SWAPS = 7,    /* B = number of runs Q */
+    LAP_WS_EVALUATE_WEIGHTS = 8   /* B = number of weight vectors W */
 };
 
 /* Bytes of workspace the given call needs.  B is the number of orderings for PLAN_POOL, the
@@ -173,7 +176,8 @@ int lap_score_swaps(const lap_trace *trace, double link_GBps, uint64_t min_bytes
                     void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Priority scores a selection can walk by (Section IV-B). */
-enum { LAP_PS_DOA = 0, LAP_PS_AOA = 1, LAP_PS_WDOA = 2, LAP_PS_SWDOA = 3, LAP_PS_PEAK_CUT = 4 };
+enum { LAP_PS_DOA = 0, LAP_PS_AOA = 1, LAP_PS_WDOA = 2, LAP_PS_SWDOA = 3, LAP_PS_PEAK_CUT = 4,
+       LAP_PS_CUSTOM = 5 /* internal: lap_evaluate_weights */ };
 
 /* Section IV-D, for K priority scores and L load limits at once.  The candidates of
  * Section IV-A are put in priority order, highest score first, equal scores by ascending
@@ -247,6 +251,27 @@ int lap_simulate_swaps(const lap_trace *trace, double link_GBps, const uint32_t 
                        const uint32_t *prefix_len, const uint64_t *limits, uint32_t Q,
                        uint64_t *total_ns, uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced,
                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Section IV-C, Eq. 3: the aggregated priority score BO = a*AOA + b*DOA + c*WDOA + d*SWDOA, whose
+ * weights are tuned against the communication overhead of the schedule it leads to.  This call
+ * evaluates W weight vectors at once; the optimiser that proposes them is the caller's.
+ *   weights [W*4] host, rows (a, b, c, d), finite, W <= 64.  They apply to the RAW scores:
+ *           standardising a score is an affine map, so for the induced order it only rescales
+ *           that score's weight (fold 1/sigma into it).
+ *   SWDOA_i = the WDOA variable i had on the reduced curve when the SWDOA walk picked it.
+ *   BO is one binary64 expression, ((a*AOA + b*DOA) + c*WDOA) + d*SWDOA, not contracted.
+ * For every vector: candidates in descending BO (ties: lower index) are selected until the peak
+ * load is <= limit (lap_select_swaps), and that selection is replayed under the limit
+ * (lap_simulate_swaps).
+ *   order      [W*N] out: row w = the vector's priority order (first n_cand entries)
+ *   n_cand [1], n_selected [W], peak_after [W], overhead_ns [W], forced [W] out
+ *   best   [1] out: the vector with the least overhead_ns, the lowest index among equals
+ *   swdoa  [N] out: the SWDOA values (0 for non-candidates) */
+int lap_evaluate_weights(const lap_trace *trace, double link_GBps, uint64_t min_bytes, const uint64_t *load,
+                         const double *weights, uint32_t W, uint64_t limit,
+                         uint32_t *order, uint32_t *n_cand, uint32_t *n_selected, uint64_t *peak_after,
+                         uint64_t *overhead_ns, uint32_t *forced, uint32_t *best, uint64_t *swdoa,
+                         void *ws, size_t ws_bytes, void *hip_stream);
 
 /* Section V: the requests of the first iterations are recorded in a list, and an iteration has
  * been seen once the list ends with two equal consecutive subsequences; that subsequence is one

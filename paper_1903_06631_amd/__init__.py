@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     DeviceTrace,
     LapError,
     detect_iteration,
+    evaluate_weights,
     lib_path,
     load_library,
     load_profile,

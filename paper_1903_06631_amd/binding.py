@@ -13,7 +13,7 @@ _lib = None
 
 EXPORTS = [
     "lap_workspace_bytes", "lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
-    "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps",
+    "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps", "lap_evaluate_weights",
     "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms",
 ]
 
@@ -78,6 +78,9 @@ def load_library():
     lib.lap_simulate_swaps.argtypes = [C.POINTER(_Trace), C.c_double, C.c_void_p, C.c_uint32, C.c_void_p,
                                        C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lap_evaluate_weights.restype = C.c_int
+    lib.lap_evaluate_weights.argtypes = [C.POINTER(_Trace), C.c_double, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32,
+                                         C.c_uint64] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
     lib.lap_detect_iteration.restype = C.c_int
     lib.lap_detect_iteration.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
@@ -333,6 +336,33 @@ def simulate_swaps(dt: DeviceTrace, link_GBps: float, swap_list, prefix_len: Seq
                                 _stream_ptr(dt.device))
     if rc:
         raise LapError(rc, "lap_simulate_swaps")
+    if sync:
+        torch.cuda.current_stream(dt.device).synchronize()
+    return out
+
+
+def evaluate_weights(dt: DeviceTrace, link_GBps: float, min_bytes: int, weights, limit: int, load=None,
+                     sync: bool = True):
+    """lap_evaluate_weights: weights is a (W, 4) array-like of (a, b, c, d).  Returns device tensors order[W,N],
+    n_cand[1], n_selected[W], peak_after[W], overhead_ns[W], forced[W], best[1], swdoa[N]."""
+    torch = _torch()
+    lib = load_library()
+    w = np.ascontiguousarray(weights, dtype=np.float64).reshape(-1, 4)
+    W, n = len(w), dt.n_vars
+    i32 = lambda m: torch.empty(m, dtype=torch.int32, device=dt.device)
+    i64 = lambda m: torch.empty(m, dtype=torch.int64, device=dt.device)
+    out = dict(order=torch.empty((W, n), dtype=torch.int32, device=dt.device), n_cand=i32(1), n_selected=i32(W),
+               peak_after=i64(W), overhead_ns=i64(W), forced=i32(W), best=i32(1), swdoa=i64(n))
+    ws, need = dt.workspace(8, W)
+    tr = dt.c_struct()
+    rc = lib.lap_evaluate_weights(C.byref(tr), float(link_GBps), int(min_bytes),
+                                  None if load is None else load.data_ptr(), w.ctypes.data_as(C.c_void_p), W,
+                                  int(limit), out["order"].data_ptr(), out["n_cand"].data_ptr(),
+                                  out["n_selected"].data_ptr(), out["peak_after"].data_ptr(),
+                                  out["overhead_ns"].data_ptr(), out["forced"].data_ptr(), out["best"].data_ptr(),
+                                  out["swdoa"].data_ptr(), ws.data_ptr(), need, _stream_ptr(dt.device))
+    if rc:
+        raise LapError(rc, "lap_evaluate_weights")
     if sync:
         torch.cuda.current_stream(dt.device).synchronize()
     return out

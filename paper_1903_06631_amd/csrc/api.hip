@@ -90,6 +90,18 @@ size_t ws_simulate(uint32_t n, uint32_t T, uint32_t Q)
            + (size_t)Q * (up(N * 4) + up(N));                      // per run: issue boundaries, swap-out flags
 }
 
+size_t ws_select(uint32_t n, uint32_t T, uint32_t K);
+
+size_t ws_weights(uint32_t n, uint32_t T, uint32_t W)
+{
+    const size_t N = n, w = W;
+    return ws_select(n, T, 0) + up(SELECT_MAX_KINDS * 8) + up(SELECT_MAX_KINDS * 32) + ALIGN
+           + up(w * N * 8) + up(w * N * 4) + up(w * T * 8) + up(w * (N + 1) * 8) + up(w * N * 8)   // walk state, peaks, scores
+           + 2 * up((size_t)T * 8) + 3 * up(N * 4) + 2 * ALIGN                                      // steps, perms
+           + up((w * N + 1) * 4) + 2 * up(w * N * 4) + up(w * 4) + up(w * N * 4) + up(w * N)        // replay state
+           + 2 * up(w * 8);
+}
+
 size_t ws_select(uint32_t n, uint32_t T, uint32_t K)
 {
     const size_t N = n;
@@ -182,6 +194,7 @@ size_t lap_workspace_bytes(int which, uint32_t n_vars, uint32_t n_steps, uint32_
     case LAP_WS_DETECT_ITERATION: return up(((size_t)n_vars + 1) * 8);
     case LAP_WS_SCHEDULE_SWAPS: return ws_schedule(n_vars, n_steps);
     case LAP_WS_SIMULATE_SWAPS: return ws_simulate(n_vars, n_steps, B);
+    case LAP_WS_EVALUATE_WEIGHTS: return ws_weights(n_vars, n_steps, B);
     default: return 0;
     }
 }
@@ -374,7 +387,7 @@ int lap_select_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, 
     if (L && (!limits || !n_selected || !peak_after)) return LAP_E_NULL;
     if (K == 0 || K > SELECT_MAX_KINDS || L > SELECT_MAX_LIMITS) return LAP_E_SIZE;
     for (uint32_t k = 0; k < K; ++k)
-        if (score_kinds[k] > LAP_PS_PEAK_CUT) return LAP_E_ORDERING;
+        if (score_kinds[k] > LAP_PS_PEAK_CUT) return LAP_E_ORDERING;   // the custom kind is internal
     if (!(link_GBps > 0.0) || !isfinite(link_GBps) || link_GBps * 1000.0 >= 9.0e18) return LAP_E_LINK;
     const long long bpus = llround(link_GBps * 1000.0);
     if (bpus <= 0) return LAP_E_LINK;
@@ -443,10 +456,138 @@ int lap_select_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, 
     a.r_score = r_score; a.r_var = r_var; a.l_cur = l_cur;
     a.order = order; a.rank = rank; a.peaks = peaks; a.n_cand = n_cand; a.n_selected = n_selected;
     a.peak_after = peak_after; a.load_min = load_min;
+    a.custom = nullptr; a.pick_wdoa = nullptr;
     {
         ProfScope p(LAP_K_SELECT, st);
-        LAP_HIP(lap::launch_select_swaps(a, st));
+        LAP_HIP(lap::launch_select_swaps(a, true, st));
     }
+    return LAP_OK;
+}
+
+int lap_evaluate_weights(const lap_trace *tr, double link_GBps, uint64_t min_bytes, const uint64_t *load,
+                         const double *weights, uint32_t W, uint64_t limit, uint32_t *order, uint32_t *n_cand,
+                         uint32_t *n_selected, uint64_t *peak_after, uint64_t *overhead_ns, uint32_t *forced,
+                         uint32_t *best, uint64_t *swdoa, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!weights || !order || !n_cand || !n_selected || !peak_after || !overhead_ns || !forced || !best || !swdoa)
+        return LAP_E_NULL;
+    if (W == 0 || W > SELECT_MAX_KINDS) return LAP_E_SIZE;
+    for (uint32_t i = 0; i < 4 * W; ++i)
+        if (!isfinite(weights[i])) return LAP_E_ORDERING;
+    if (!(link_GBps > 0.0) || !isfinite(link_GBps) || link_GBps * 1000.0 >= 9.0e18) return LAP_E_LINK;
+    const long long bpus = llround(link_GBps * 1000.0);
+    if (bpus <= 0) return LAP_E_LINK;
+    const uint32_t n = tr->n_vars, T = tr->n_steps;
+    rc = check_ws(ws, ws_bytes, ws_weights(n, T, W));
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t t1 = (size_t)T + 1, N = n;
+    Carver c(ws);
+    uint64_t *load_ws = c.take<uint64_t>(T);
+    uint64_t *delta = c.take<uint64_t>(t1);
+    uint64_t *C = c.take<uint64_t>(t1);
+    uint64_t *S = c.take<uint64_t>(t1);
+    uint64_t *PM = c.take<uint64_t>(t1);
+    uint64_t *SM = c.take<uint64_t>(t1);
+    const uint32_t levels = table_levels(T);
+    uint64_t *table = c.take<uint64_t>((size_t)levels * T);
+    uint64_t *peak = c.take<uint64_t>(1);
+    uint32_t *t_peak = c.take<uint32_t>(1);
+    uint8_t *cand = c.take<uint8_t>(n);
+    int64_t *doa = c.take<int64_t>(n);
+    double *aoa = c.take<double>(n);
+    uint64_t *wdoa = c.take<uint64_t>(n);
+    uint64_t *cut = c.take<uint64_t>(n);
+    uint32_t *win_lo = c.take<uint32_t>(n);
+    uint32_t *win_hi = c.take<uint32_t>(n);
+    uint32_t *cidx = c.take<uint32_t>(n);
+    uint32_t *c_ilo = c.take<uint32_t>(n);
+    uint32_t *c_ihi = c.take<uint32_t>(n);
+    uint64_t *dmin = c.take<uint64_t>(t1);
+    uint32_t *nc = c.take<uint32_t>(1);
+    uint32_t *d_kinds = c.take<uint32_t>(SELECT_MAX_KINDS);
+    uint64_t *d_limits = c.take<uint64_t>(SELECT_MAX_KINDS);
+    double *d_weights = c.take<double>((size_t)SELECT_MAX_KINDS * 4);
+    uint64_t *load_min = c.take<uint64_t>(1);
+    uint64_t *r_score = c.take<uint64_t>((size_t)W * N);
+    uint32_t *r_var = c.take<uint32_t>((size_t)W * N);
+    uint64_t *l_cur = c.take<uint64_t>((size_t)W * T);
+    uint64_t *peaks = c.take<uint64_t>((size_t)W * (N + 1));
+    double *bo = c.take<double>((size_t)W * N);
+    uint64_t *need = c.take<uint64_t>(T);
+    uint64_t *rel = c.take<uint64_t>(T);
+    uint32_t *perm_lo = c.take<uint32_t>(n);
+    uint32_t *perm_hi = c.take<uint32_t>(n);
+    uint32_t *tmp = c.take<uint32_t>(n);
+    uint32_t *s_kind = c.take<uint32_t>(1);
+    uint64_t *s_seed = c.take<uint64_t>(1);
+    uint32_t *posmap = c.take<uint32_t>((size_t)W * N + 1);
+    uint32_t *jobs_lo = c.take<uint32_t>((size_t)W * N);
+    uint32_t *jobs_hi = c.take<uint32_t>((size_t)W * N);
+    uint32_t *m = c.take<uint32_t>(W);
+    uint32_t *kb = c.take<uint32_t>((size_t)W * N);
+    uint8_t *out_done = c.take<uint8_t>((size_t)W * N);
+    uint64_t *total_ns = c.take<uint64_t>(W);
+    uint64_t *peak_res = c.take<uint64_t>(W);
+
+    static thread_local std::vector<uint32_t> hk;
+    static thread_local std::vector<double> hw;
+    hk.assign(W, (uint32_t)LAP_PS_CUSTOM);
+    hw.assign(weights, weights + 4 * (size_t)W);
+    if (!load) {
+        rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
+        if (rc) return rc;
+        load = load_ws;
+    }
+    LAP_HIP(lap::launch_swap_prefix(T, load, tr->step_ns, C, S, PM, SM, peak, t_peak, st));
+    LAP_HIP(lap::launch_sparse_table(T, load, table, levels, st));
+    LAP_HIP(lap::launch_score(n, T, tr->size, tr->alloc, tr->free_, tr->gap_lo, tr->gap_hi, (uint64_t)bpus, min_bytes,
+                              load, C, S, PM, SM, table, peak, t_peak, cand, doa, aoa, wdoa, cut, win_lo, win_hi, st));
+    LAP_HIP(lap::launch_fill_u64(dmin, t1, 0, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)nc, 1, 0, st));
+    LAP_HIP(lap::launch_fill_u64(swdoa, n, 0, st));
+    LAP_HIP(lap::launch_fill_u64(d_limits, W, limit, st));
+    lap::SelectArgs a;
+    a.n = n; a.T = T; a.K = 1; a.L = 0;
+    a.size = tr->size; a.gap_lo = tr->gap_lo; a.gap_hi = tr->gap_hi; a.alloc = tr->alloc; a.free_ = tr->free_;
+    a.load = load; a.cand = cand; a.doa = doa; a.aoa = aoa; a.wdoa = wdoa; a.cut = cut;
+    a.win_lo = win_lo; a.win_hi = win_hi; a.nc = nc; a.cidx = cidx; a.c_ilo = c_ilo; a.c_ihi = c_ihi; a.dmin = dmin;
+    a.kinds = d_kinds; a.limits = d_limits;
+    a.r_score = r_score; a.r_var = r_var; a.l_cur = l_cur;
+    a.order = order; a.rank = nullptr; a.peaks = peaks; a.n_cand = n_cand; a.n_selected = n_selected;
+    a.peak_after = peak_after; a.load_min = load_min;
+    a.custom = nullptr; a.pick_wdoa = swdoa;
+    // 1. the SWDOA walk, once: the value every candidate is picked at
+    static const uint32_t h_swdoa = LAP_PS_SWDOA;
+    LAP_HIP(hipMemcpyAsync(d_kinds, &h_swdoa, 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_select_swaps(a, true, st));
+    // 2. the aggregated score of every weight vector, 3. its walk down to the limit
+    LAP_HIP(hipMemcpyAsync(d_weights, hw.data(), (size_t)W * 32, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_weighted_scores(n, W, d_weights, aoa, doa, wdoa, swdoa, bo, st));
+    LAP_HIP(hipMemcpyAsync(d_kinds, hk.data(), (size_t)W * 4, hipMemcpyHostToDevice, st));
+    a.K = W; a.L = 1; a.custom = bo; a.pick_wdoa = nullptr;
+    {
+        ProfScope p(LAP_K_SELECT, st);
+        LAP_HIP(lap::launch_select_swaps(a, false, st));
+    }
+    // 4. every selection replayed under the limit, 5. the vector that loses the least time
+    static const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
+    LAP_HIP(hipMemcpyAsync(s_kind, &h_kind, 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_fill_u64(s_seed, 1, 0, st));
+    const uint32_t *step_lo = tr->gap_lo ? tr->gap_lo : tr->alloc;
+    const uint32_t *step_hi = tr->gap_hi ? tr->gap_hi : tr->free_;
+    LAP_HIP(lap::launch_sort_perm(n, 1, tr->size, step_lo, tr->free_, s_kind, s_seed, perm_lo, tmp, false, st));
+    LAP_HIP(lap::launch_sort_perm(n, 1, tr->size, step_hi, tr->free_, s_kind, s_seed, perm_hi, tmp, false, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)posmap, ((size_t)W * N + 1) / 2, ~0ull, st));
+    LAP_HIP(lap::launch_fill_u64(need, T, 0, st));
+    LAP_HIP(lap::launch_fill_u64(rel, T, 0, st));
+    LAP_HIP(lap::launch_simulate_swaps(n, T, W, n, tr->size, tr->alloc, tr->free_, step_lo, step_hi,
+                                       tr->gap_hi ? 0u : 1u, C, need, rel, order, perm_lo, perm_hi, posmap, jobs_lo,
+                                       jobs_hi, m, n_selected, d_limits, kb, out_done, (uint64_t)bpus, total_ns,
+                                       overhead_ns, peak_res, forced, st, W, n_cand));
+    LAP_HIP(lap::launch_argmin_u64(W, overhead_ns, best, st));
     return LAP_OK;
 }
 

@@ -81,8 +81,14 @@ struct SelectArgs {
     uint32_t *n_selected;      // [K][L]
     uint64_t *peak_after;      // [K][L]
     uint64_t *load_min;        // [1]
+    const double *custom;      // [K][n] score of kind 5 (custom), row = position in kinds; else null
+    uint64_t *pick_wdoa;       // [n] or null: for a SWDOA walk, the score a variable had when it was picked
 };
-hipError_t launch_select_swaps(const SelectArgs &a, hipStream_t st);
+// gather = build the candidate slots and load_min first (once per trace and candidate filter)
+hipError_t launch_select_swaps(const SelectArgs &a, bool gather, hipStream_t st);
+hipError_t launch_weighted_scores(uint32_t n, uint32_t W, const double *weights, const double *aoa, const int64_t *doa,
+                                  const uint64_t *wdoa, const uint64_t *swdoa, double *bo, hipStream_t st);
+hipError_t launch_argmin_u64(uint32_t n, const uint64_t *v, uint32_t *best, hipStream_t st);
 
 hipError_t launch_schedule_swaps(uint32_t n, uint32_t T, uint32_t k, const uint64_t *size, const uint32_t *step_lo,
                                  const uint32_t *step_hi, uint32_t hi_minus, const uint64_t *C,
@@ -98,7 +104,8 @@ hipError_t launch_simulate_swaps(uint32_t n, uint32_t T, uint32_t Q, uint32_t km
                                  const uint32_t *perm_hi, const uint32_t *posmap, uint32_t *jobs_lo,
                                  uint32_t *jobs_hi, uint32_t *m, const uint32_t *prefix, const uint64_t *limits,
                                  uint32_t *kb, uint8_t *out_done, uint64_t bpus, uint64_t *total_ns,
-                                 uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced, hipStream_t st);
+                                 uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced, hipStream_t st,
+                                 uint32_t n_lists = 1, const uint32_t *n_listed = nullptr);
 hipError_t launch_sched_mark(uint32_t n, uint32_t k, const uint32_t *list, uint32_t *posmap, hipStream_t st);
 
 hipError_t launch_detect_iteration(const uint64_t *tokens, uint32_t M, uint32_t min_period, uint64_t *P,

@@ -49,6 +49,12 @@ __device__ __forceinline__ uint64_t score_key(const SelectArgs &a, uint32_t kind
     }
 }
 
+__device__ __forceinline__ uint64_t custom_key(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    return (b >> 63) ? ~b : (b | (1ull << 63));
+}
+
 struct Best {
     uint64_t score;
     uint32_t var, slot;
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_walk(SelectArgs a)
     for (uint32_t c = tid; c < nc; c += SEL_THREADS) {
         const uint32_t v = a.cidx[c];
         rv[c] = v;
-        rs[c] = score_key(a, kind, v);
+        rs[c] = kind == 5 ? custom_key(a.custom[(size_t)ks * n + v]) : score_key(a, kind, v);
     }
     for (uint32_t t = tid; t < T; t += SEL_THREADS) lc[t] = a.load[t];
     if (rank)
@@ -127,7 +133,11 @@ __global__ __launch_bounds__(SEL_THREADS) void k_sel_walk(SelectArgs a)
         }
         if (tid == 0) {
             peaks[k] = mx;
-            if (b.var != NONE) { order[k] = b.var; if (rank) rank[b.var] = k; }
+            if (b.var != NONE) {
+                order[k] = b.var;
+                if (rank) rank[b.var] = k;
+                if (kind == 3 && a.pick_wdoa) a.pick_wdoa[b.var] = b.score;
+            }
         }
         if (b.var == NONE) break;        // k == nc: nothing left
         has_w = true;
@@ -181,11 +191,54 @@ __global__ __launch_bounds__(SEL_THREADS) void k_load_min(uint32_t T, const uint
     }
 }
 
-hipError_t launch_select_swaps(const SelectArgs &a, hipStream_t st)
+hipError_t launch_select_swaps(const SelectArgs &a, bool gather, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_sel_gather, dim3((a.n + 255) / 256), dim3(256), 0, st, a);
-    hipLaunchKernelGGL(k_load_min, dim3(1), dim3(SEL_THREADS), 0, st, a.T, a.load, a.dmin, a.load_min);
+    if (gather) {
+        hipLaunchKernelGGL(k_sel_gather, dim3((a.n + 255) / 256), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(k_load_min, dim3(1), dim3(SEL_THREADS), 0, st, a.T, a.load, a.dmin, a.load_min);
+    }
     hipLaunchKernelGGL(k_sel_walk, dim3(a.K), dim3(SEL_THREADS), 0, st, a);
+    return hipGetLastError();
+}
+
+// Section IV-C, Eq. 3 on the raw scores: one binary64 expression per (weight vector, variable),
+// evaluated left to right without contraction
+__global__ __launch_bounds__(256) void k_weighted_scores(uint32_t n, uint32_t W, const double *__restrict__ weights,
+                                                         const double *__restrict__ aoa,
+                                                         const int64_t *__restrict__ doa,
+                                                         const uint64_t *__restrict__ wdoa,
+                                                         const uint64_t *__restrict__ swdoa, double *__restrict__ bo)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x, w = blockIdx.y;
+    if (i >= n) return;
+    const double a = weights[4 * w], b = weights[4 * w + 1], c = weights[4 * w + 2], d = weights[4 * w + 3];
+    const double t1 = a * aoa[i], t2 = b * (double)doa[i];
+    const double t3 = t1 + t2, t4 = c * (double)wdoa[i];
+    const double t5 = t3 + t4, t6 = d * (double)swdoa[i];
+    bo[(size_t)w * n + i] = t5 + t6;
+}
+
+hipError_t launch_weighted_scores(uint32_t n, uint32_t W, const double *weights, const double *aoa, const int64_t *doa,
+                                  const uint64_t *wdoa, const uint64_t *swdoa, double *bo, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_weighted_scores, dim3((n + 255) / 256, W), dim3(256), 0, st, n, W, weights, aoa, doa, wdoa,
+                       swdoa, bo);
+    return hipGetLastError();
+}
+
+// index of the smallest of n values, the lowest index among equals (n is small)
+__global__ __launch_bounds__(WAVE) void k_argmin_u64(uint32_t n, const uint64_t *__restrict__ v, uint32_t *best)
+{
+    if (threadIdx.x != 0) return;
+    uint32_t b = 0;
+    for (uint32_t i = 1; i < n; ++i)
+        if (v[i] < v[b]) b = i;
+    *best = b;
+}
+
+hipError_t launch_argmin_u64(uint32_t n, const uint64_t *v, uint32_t *best, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_argmin_u64, dim3(1), dim3(WAVE), 0, st, n, v, best);
     return hipGetLastError();
 }
 

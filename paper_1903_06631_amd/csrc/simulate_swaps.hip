@@ -28,14 +28,29 @@ __global__ __launch_bounds__(256) void k_sim_steps(uint32_t n, const uint64_t *_
     atomicAdd(&rel[free_[i] - 1], (unsigned long long)size[i]);
 }
 
-// jobs[0..m) = list positions of the listed variables that have an idle gap, in the order of perm
+// several lists, one row of n entries each: position map of list r = row r.  Row r lists the first
+// n_listed[0] entries of its row of `lists`.
+__global__ __launch_bounds__(256) void k_sim_mark_rows(uint32_t n, const uint32_t *__restrict__ lists,
+                                                       const uint32_t *__restrict__ n_listed,
+                                                       uint32_t *__restrict__ posmap)
+{
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x, r = blockIdx.y;
+    if (j < *n_listed) posmap[(size_t)r * n + min(lists[(size_t)r * n + j], n - 1)] = j;
+}
+
+// jobs[0..m) = list positions of the listed variables that have an idle gap, in the order of perm;
+// one workgroup per list (rows of n entries of posmap and jobs, one count each)
 __global__ __launch_bounds__(SIM_THREADS) void k_sim_jobs(uint32_t n, const uint32_t *__restrict__ perm,
-                                                          const uint32_t *__restrict__ posmap,
+                                                          const uint32_t *__restrict__ posmap_all,
                                                           const uint32_t *__restrict__ step_lo,
                                                           const uint32_t *__restrict__ step_hi, uint32_t hi_minus,
-                                                          uint32_t *__restrict__ jobs, uint32_t *__restrict__ m_out)
+                                                          uint32_t *__restrict__ jobs_all,
+                                                          uint32_t *__restrict__ m_all)
 {
     __shared__ uint32_t wsum[SIM_WAVES];
+    const uint32_t *posmap = posmap_all + (size_t)blockIdx.x * n;
+    uint32_t *jobs = jobs_all + (size_t)blockIdx.x * n;
+    uint32_t *m_out = m_all + blockIdx.x;
     const uint32_t tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     uint32_t carry = 0;
     for (uint32_t base = 0; base < n; base += SIM_THREADS) {
@@ -72,6 +87,7 @@ struct SimArgs {
     const uint64_t *limits;            // [Q]
     uint32_t *kb;                      // [Q][kmax] issue boundary of a swap-in, by list position
     uint8_t *out_done;                 // [Q][kmax]
+    uint32_t per_run_lists;            // 1: run q has its own list (row q of list / jobs / m), 0: all share row 0
     uint64_t bpus;
     uint64_t *total_ns, *overhead_ns, *peak_resident;
     uint32_t *forced;
@@ -81,7 +97,11 @@ __global__ __launch_bounds__(WAVE) void k_sim_run(SimArgs A)
 {
     if (threadIdx.x != 0) return;
     const uint32_t q = blockIdx.x;
-    const uint32_t k = A.prefix[q], m = *A.m, T = A.T;
+    const size_t row = A.per_run_lists ? (size_t)q * A.n : 0;
+    A.list += row;
+    A.jobs_lo += row;
+    A.jobs_hi += row;
+    const uint32_t k = A.prefix[q], m = A.m[A.per_run_lists ? q : 0], T = A.T;
     const uint64_t limit = A.limits[q];
     uint32_t *kb = A.kb + (size_t)q * A.kmax;
     uint8_t *odone = A.out_done + (size_t)q * A.kmax;
@@ -195,16 +215,23 @@ hipError_t launch_simulate_swaps(uint32_t n, uint32_t T, uint32_t Q, uint32_t km
                                  const uint32_t *perm_hi, const uint32_t *posmap, uint32_t *jobs_lo,
                                  uint32_t *jobs_hi, uint32_t *m, const uint32_t *prefix, const uint64_t *limits,
                                  uint32_t *kb, uint8_t *out_done, uint64_t bpus, uint64_t *total_ns,
-                                 uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced, hipStream_t st)
+                                 uint64_t *overhead_ns, uint64_t *peak_resident, uint32_t *forced, hipStream_t st,
+                                 uint32_t n_lists, const uint32_t *n_listed)
 {
+    // n_listed given: run q replays row q of `list` (n_lists rows of n entries, *n_listed valid entries
+    // each); the caller has cleared the n_lists position maps, they are filled here
+    if (n_listed)
+        hipLaunchKernelGGL(k_sim_mark_rows, dim3((n + 255) / 256, n_lists), dim3(256), 0, st, n, list, n_listed,
+                           const_cast<uint32_t *>(posmap));
     hipLaunchKernelGGL(k_sim_steps, dim3((n + 255) / 256), dim3(256), 0, st, n, size, alloc, free_,
                        (unsigned long long *)need, (unsigned long long *)rel);
-    hipLaunchKernelGGL(k_sim_jobs, dim3(1), dim3(SIM_THREADS), 0, st, n, perm_lo, posmap, step_lo, step_hi, hi_minus,
-                       jobs_lo, m);
-    hipLaunchKernelGGL(k_sim_jobs, dim3(1), dim3(SIM_THREADS), 0, st, n, perm_hi, posmap, step_lo, step_hi, hi_minus,
-                       jobs_hi, m);
+    hipLaunchKernelGGL(k_sim_jobs, dim3(n_lists), dim3(SIM_THREADS), 0, st, n, perm_lo, posmap, step_lo, step_hi,
+                       hi_minus, jobs_lo, m);
+    hipLaunchKernelGGL(k_sim_jobs, dim3(n_lists), dim3(SIM_THREADS), 0, st, n, perm_hi, posmap, step_lo, step_hi,
+                       hi_minus, jobs_hi, m);
     SimArgs A{n, T, Q, kmax, size, step_lo, step_hi, hi_minus, C, (const unsigned long long *)need,
-              (const unsigned long long *)rel, list, jobs_lo, jobs_hi, m, prefix, limits, kb, out_done, bpus,
+              (const unsigned long long *)rel, list, jobs_lo, jobs_hi, m, prefix, limits, kb, out_done,
+              n_listed ? 1u : 0u, bpus,
               total_ns, overhead_ns, peak_resident, forced};
     hipLaunchKernelGGL(k_sim_run, dim3(Q), dim3(WAVE), 0, st, A);
     return hipGetLastError();

@@ -24,7 +24,7 @@ def test_every_declared_symbol_is_exported(lap):
     hdr = open(os.path.join(ROOT, "include", "lap.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(lap_[a-z_]+)\s*\(", hdr))
-    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps", "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps",
+    assert {"lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps", "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps", "lap_evaluate_weights",
             "lap_workspace_bytes",
             "lap_validate_trace", "lap_status_string"} <= declared
     lib = lap.load_library()
@@ -118,6 +118,14 @@ def test_argument_errors(lap):
                                               kw.get("ws", 1 << 30), None)
     assert sim(pl=None) == -1 and sim(out=None) == -1 and sim(Q=0) == -2 and sim(Q=5000) == -2 and sim(k=1) == -2
     assert sim(link=0.0) == -5 and sim(ws=lap.workspace_bytes(7, 4, 3, 2) - 1) == -3
+    # weight vectors
+    wv = (C.c_double * 8)(1, 0, 0, 0, 0, 1, 0, 0)
+    ew = lambda **kw: lib.lap_evaluate_weights(C.byref(good), kw.get("link", 1.0), 1, None, kw.get("wv", wv), kw.get("W", 2),
+                                               5, kw.get("order", fake), fake, fake, fake, fake, fake, fake, fake, fake,
+                                               kw.get("ws", 1 << 30), None)
+    assert ew(wv=None) == -1 and ew(order=None) == -1 and ew(W=0) == -2 and ew(W=65) == -2 and ew(link=0.0) == -5
+    assert ew(wv=(C.c_double * 8)(1, 0, 0, float("inf"), 0, 1, 0, 0)) == -4
+    assert ew(ws=lap.workspace_bytes(8, 4, 3, 2) - 1) == -3
     # iteration detection
     assert lib.lap_detect_iteration(None, 8, 1, fake, fake, 1 << 20, None) == -1
     assert lib.lap_detect_iteration(fake, 0, 1, fake, fake, 1 << 20, None) == -2
