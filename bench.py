@@ -34,7 +34,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=5, help="BASELINE config 1..5 (5 = transformer-shaped, the largest trace)")
+    ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (5 = transformer-shaped, the largest trace)")
     ap.add_argument("--orderings", type=int, default=0, help="override B (0 = the config's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stress", action="store_true",
@@ -44,7 +44,7 @@ def main() -> int:
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build plans on ONE GPU (orderings would shard across GPUs, see DESIGN.md); "
+        print("bench.py: this build plans on ONE GPU (the orderings are what would shard across GPUs); "
               "run with --gpus 1", file=sys.stderr)
         return 2
 
@@ -195,7 +195,7 @@ def main() -> int:
         extra["detect_iteration"] = dict(call_ms=1e3 * det_s, requests=len(stream), period=len(it))
         lap.plan_pool(dt, kinds[:1], seeds[:1], want_all=False)      # leave the profile slots on first-fit
 
-    # The load-profile kernel on the largest BASELINE trace moves 3.2 MB (launch-latency bound), so
+    # The load-profile kernel on the largest benchmark trace moves 3.2 MB (launch-latency bound), so
     # its HBM fraction is also measured on the same trace repeated along time until the SoA is ~2 GiB.
     lp_small_ms = lap.profile_last_ms(lap.K_LOAD_SCATTER)
     stress = None
@@ -214,7 +214,7 @@ def main() -> int:
         k_ms, call_ms = float(np.median(ms_k[1:])), float(np.median(ms_call[1:]))
         # same curve every iteration: the tiled profile repeats the single-iteration one
         assert np.array_equal(u64(blp["load"])[:T], u64(lp["load"])) and int(u64(blp["peak"])[0]) == peak
-        stress = dict(workload="configs[4] repeated 670x along time (not a BASELINE config)", n_vars=big.n_vars,
+        stress = dict(workload="configs[4] repeated 670x along time (not one of the benchmark configurations)", n_vars=big.n_vars,
                       n_steps=big.n_steps, algorithmic_bytes=nbytes, kernel="k_delta_window", kernel_ms=k_ms,
                       kernel_GBps=nbytes / k_ms / 1e6, kernel_frac=nbytes / k_ms / 1e6 / HBM_PEAK_GBPS,
                       call_ms=call_ms, call_GBps=nbytes / call_ms / 1e6, call_frac=nbytes / call_ms / 1e6 / HBM_PEAK_GBPS)

@@ -1,4 +1,4 @@
-"""Parity at BASELINE's full sizes, in the launch configuration bench.py times: every ordering is
+"""Parity at the benchmark configurations' full sizes, in the launch configuration bench.py times: every ordering is
 planned on the GPU; a sample of orderings is recomputed by the oracle and compared offset by offset,
 and properties that hold for any ordering are checked on all of them."""
 import numpy as np

@@ -288,7 +288,7 @@ _SPECS = {
 
 
 def make_config(cfg: int) -> Trace:
-    """Trace of BASELINE config `cfg` (1..5).  Deterministic."""
+    """Trace of benchmark configuration `cfg` (1..5).  Deterministic."""
     ops_fn, n_total, n_orderings, draw_ws, draw_tmp, score, ns_range = _SPECS[cfg]
     rng = CounterRng(TRACE_SEED_BASE + cfg)
     ops = ops_fn()
