@@ -19,7 +19,7 @@ constexpr uint32_t PLAN_CL = 6;
 hipError_t launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st);
 hipError_t launch_delta(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                         uint64_t *delta, hipStream_t st);
-hipError_t launch_scan_peak(uint32_t T, const uint64_t *delta, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
+hipError_t launch_scan_peak(uint32_t T, uint64_t *delta, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
                             hipStream_t st);
 hipError_t launch_validate(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                            const uint32_t *gap_lo, const uint32_t *gap_hi, const uint64_t *step_ns, uint64_t *out8,

@@ -188,6 +188,122 @@ __global__ __launch_bounds__(SCAN_THREADS) void k_scan_peak(uint32_t T, const ui
     }
 }
 
+// Long time lines: the same scan in four small launches, tiles of SCAN_THREADS * SCAN_ITEMS steps.
+//   1  every tile scans itself into load[] (the last entry of a tile is the tile's total)
+//   2  one workgroup turns the tile totals into tile offsets; delta[] is no longer needed as input
+//      and takes them (delta[0 .. nb))
+//   3  every tile adds its offset and notes its largest value and the earliest step that has it
+//      (delta[nb .. 2nb) and delta[2nb .. 3nb))
+//   4  one workgroup reduces those to the peak and the peak step
+constexpr uint32_t SCAN_TILE = SCAN_THREADS * SCAN_ITEMS;
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_tile_local(uint32_t T, const uint64_t *__restrict__ delta,
+                                                                  uint64_t *__restrict__ load)
+{
+    __shared__ uint64_t wsum[SCAN_THREADS / WAVE];
+    const int tid = threadIdx.x, l = tid & (WAVE - 1), w = tid / WAVE;
+    const uint32_t t0 = blockIdx.x * SCAN_TILE + tid * SCAN_ITEMS;
+    uint64_t v[SCAN_ITEMS], sum = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        v[k] = (t0 + k < T) ? delta[t0 + k] : 0;
+        sum += v[k];
+    }
+    const uint64_t incl = wave_scan_add(sum);
+    if (l == WAVE - 1) wsum[w] = incl;
+    __syncthreads();
+    uint64_t run = incl - sum;
+    for (int k = 0; k < w; ++k) run += wsum[k];
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        run += v[k];
+        if (t0 + k < T) load[t0 + k] = run;
+    }
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_tile_offsets(uint32_t T, uint32_t nb,
+                                                                    const uint64_t *__restrict__ load,
+                                                                    uint64_t *__restrict__ offs)
+{
+    __shared__ uint64_t wsum[SCAN_THREADS / WAVE];
+    const int tid = threadIdx.x, l = tid & (WAVE - 1), w = tid / WAVE;
+    uint64_t carry = 0;
+    for (uint32_t base = 0; base < nb; base += SCAN_THREADS) {
+        const uint32_t j = base + tid;
+        const uint64_t tot = j < nb ? load[min(T, (j + 1) * SCAN_TILE) - 1] : 0;
+        const uint64_t incl = wave_scan_add(tot);
+        if (l == WAVE - 1) wsum[w] = incl;
+        __syncthreads();
+        uint64_t pre = carry, all = 0;
+        for (int k = 0; k < SCAN_THREADS / WAVE; ++k) { if (k < w) pre += wsum[k]; all += wsum[k]; }
+        if (j < nb) offs[j] = pre + incl - tot;
+        carry += all;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_tile_apply(uint32_t T, uint32_t nb, uint64_t *__restrict__ load,
+                                                                  uint64_t *scratch)
+{
+    __shared__ uint64_t wmax[SCAN_THREADS / WAVE];
+    __shared__ uint32_t warg[SCAN_THREADS / WAVE];
+    const int tid = threadIdx.x, l = tid & (WAVE - 1), w = tid / WAVE;
+    const uint32_t b = blockIdx.x, t0 = b * SCAN_TILE + tid * SCAN_ITEMS;
+    const uint64_t off = scratch[b];
+    uint64_t best = 0;
+    uint32_t best_t = 0xFFFFFFFFu;
+#pragma unroll
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        if (t0 + k < T) {
+            const uint64_t x = load[t0 + k] + off;
+            load[t0 + k] = x;
+            if (best_t == 0xFFFFFFFFu || x > best) { best = x; best_t = t0 + k; }
+        }
+    }
+    for (int m = WAVE / 2; m > 0; m >>= 1) {
+        const uint64_t ov = shfl_xor64(best, m);
+        const uint32_t ot = (uint32_t)__shfl_xor(best_t, m, WAVE);
+        if (ov > best || (ov == best && ot < best_t)) { best = ov; best_t = ot; }
+    }
+    if (l == 0) { wmax[w] = best; warg[w] = best_t; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int k = 1; k < SCAN_THREADS / WAVE; ++k)
+            if (wmax[k] > best || (wmax[k] == best && warg[k] < best_t)) { best = wmax[k]; best_t = warg[k]; }
+        scratch[nb + b] = best;
+        scratch[2 * nb + b] = best_t;
+    }
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void k_scan_tile_peak(uint32_t nb, const uint64_t *__restrict__ scratch,
+                                                                 uint64_t *__restrict__ peak,
+                                                                 uint32_t *__restrict__ t_peak)
+{
+    __shared__ uint64_t wmax[SCAN_THREADS / WAVE];
+    __shared__ uint32_t warg[SCAN_THREADS / WAVE];
+    const int tid = threadIdx.x, l = tid & (WAVE - 1), w = tid / WAVE;
+    uint64_t best = 0;
+    uint32_t best_t = 0xFFFFFFFFu;
+    for (uint32_t j = tid; j < nb; j += SCAN_THREADS) {
+        const uint64_t x = scratch[nb + j];
+        const uint32_t at = (uint32_t)scratch[2 * nb + j];
+        if (x > best || (x == best && at < best_t)) { best = x; best_t = at; }
+    }
+    for (int m = WAVE / 2; m > 0; m >>= 1) {
+        const uint64_t ov = shfl_xor64(best, m);
+        const uint32_t ot = (uint32_t)__shfl_xor(best_t, m, WAVE);
+        if (ov > best || (ov == best && ot < best_t)) { best = ov; best_t = ot; }
+    }
+    if (l == 0) { wmax[w] = best; warg[w] = best_t; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int k = 1; k < SCAN_THREADS / WAVE; ++k)
+            if (wmax[k] > best || (wmax[k] == best && warg[k] < best_t)) { best = wmax[k]; best_t = warg[k]; }
+        *peak = best;
+        *t_peak = best_t;
+    }
+}
+
 // Trace content checks (flags[0] = trace error, flags[1] = a size >= 2^53),
 // and the sums the range checks need: sizes split in 32-bit halves so that
 // neither partial sum can overflow, max size, and the same for step_ns.
@@ -261,10 +377,19 @@ hipError_t launch_delta(uint32_t n, uint32_t T, const uint64_t *size, const uint
     return hipGetLastError();
 }
 
-hipError_t launch_scan_peak(uint32_t T, const uint64_t *delta, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
+hipError_t launch_scan_peak(uint32_t T, uint64_t *delta, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
                             hipStream_t st)
 {
-    hipLaunchKernelGGL(k_scan_peak, dim3(1), dim3(SCAN_THREADS), 0, st, T, delta, load, peak, t_peak);
+    const uint32_t nb = (T + SCAN_TILE - 1) / SCAN_TILE;
+    if (nb < 8) {
+        hipLaunchKernelGGL(k_scan_peak, dim3(1), dim3(SCAN_THREADS), 0, st, T, delta, load, peak, t_peak);
+        return hipGetLastError();
+    }
+    // 3 * nb <= T + 1 entries of delta serve as scratch once the tiles have been read
+    hipLaunchKernelGGL(k_scan_tile_local, dim3(nb), dim3(SCAN_THREADS), 0, st, T, delta, load);
+    hipLaunchKernelGGL(k_scan_tile_offsets, dim3(1), dim3(SCAN_THREADS), 0, st, T, nb, load, delta);
+    hipLaunchKernelGGL(k_scan_tile_apply, dim3(nb), dim3(SCAN_THREADS), 0, st, T, nb, load, delta);
+    hipLaunchKernelGGL(k_scan_tile_peak, dim3(1), dim3(SCAN_THREADS), 0, st, nb, delta, peak, t_peak);
     return hipGetLastError();
 }
 

@@ -47,6 +47,21 @@ def test_load_profile_tiled_long_timeline(lap, oracle_mod):
     _check_load(lap, oracle_mod, tr)
 
 
+@pytest.mark.parametrize("T", [32767, 32768, 32769, 100003, 4096 * 31 + 1])
+def test_load_profile_long_time_lines(lap, oracle_mod, T):
+    """time lines of 8 or more scan tiles take the multi-launch scan; equal peaks in different tiles"""
+    tr = random_trace(40 + T % 7, 20000, T, max_life=T // 3)
+    _check_load(lap, oracle_mod, tr)
+    n = 40
+    starts = [(k * (T - 2)) // (n - 1) for k in range(n)]                 # the same load at n far-apart steps
+    tr = mk_trace([4096] * n, starts, [s + 1 for s in starts], T=T)
+    dt, got = _check_load(lap, oracle_mod, tr)
+    assert int(got["t_peak"].item()) == 0
+    tr = mk_trace([4096] * n + [1], starts + [T - 1], [s + 1 for s in starts] + [T], T=T)
+    tr.size[n // 2] += 512                                                # a single higher peak in the middle
+    _check_load(lap, oracle_mod, tr)
+
+
 def test_load_profile_peak_ties_and_extremes(lap, oracle_mod):
     tr = mk_trace([512, 512, 512], [0, 2, 4], [1, 3, 5], T=6)          # three equal peaks -> earliest
     _check_load(lap, oracle_mod, tr)
