@@ -812,8 +812,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 auto fit_from = [&](uint32_t from) -> uint32_t {
                     uint32_t o = from;
                     for (;;) {
-                        const uint32_t o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax,
-                                                       s_hq, s_hans);
+                        uint32_t o1 = o;
+                        if (nm) o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax, s_hq, s_hans);
+                        else __syncthreads();      // (keeps this pass's exchange slots apart from the last one's)
                         uint32_t o2 = o1;
                         if (nr)
                             o2 = coop_sweep(r_oe[rb], r_life[rb], nr, cr, o1, vs, va, vf, wave, s_cmax, s_hq, s_hans);
