@@ -676,7 +676,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     __shared__ uint32_t s_np, s_bc;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
-    __shared__ uint32_t s_sf[PW];
+    __shared__ uint32_t s_sf[2][PW];
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
     const uint32_t b = blockIdx.x;
@@ -811,7 +811,10 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 // none of them moves the candidate
                 auto fit_from = [&](uint32_t from) -> uint32_t {
                     uint32_t o = from;
+                    bool steps_hold = false;         // the hole lists have confirmed the current candidate
+                    uint32_t flip = 0;
                     for (;;) {
+                        // the block lists: lowest offset >= o that is free of their time-overlapping entries
                         uint32_t o1 = o;
                         if (nm) o1 = coop_sweep(m_oe[mb], m_life[mb], nm, cm, o, vs, va, vf, wave, s_cmax, s_hq, s_hans);
                         else __syncthreads();      // (keeps this pass's exchange slots apart from the last one's)
@@ -823,17 +826,31 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                             if (l == 0) s_bc = o2;
                         }
                         __syncthreads();
-                        o = s_bc;
-                        if (mode1) {
-                            // one-step variables are not in ALL: the hole lists of the steps it lives
-                            // through stand for them
-                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, o, vs);
-                            c = wave_reduce_max32(c);
-                            if (l == 0) s_sf[wave] = c;
-                            __syncthreads();
-                            o = max(max(s_sf[0], s_sf[1]), max(s_sf[2], s_sf[3]));
+                        o2 = s_bc;
+                        if (!mode1) {
+                            if (o2 == o1) return o2;             // recent and pending agree with main's answer
+                            o = o2;
+                            continue;
                         }
-                        if (o == o1) return o;
+                        if (o2 == o && steps_hold) return o;     // nothing moved since the hole lists agreed
+                        // one-step variables are not in ALL: the hole lists of the steps it lives through
+                        // stand for them.  Passes repeat until no step moves the candidate.
+                        uint32_t os = o2;
+                        for (;;) {
+                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs);
+                            c = wave_reduce_max32(c);
+                            if (l == 0) s_sf[flip][wave] = c;
+                            __syncthreads();
+                            c = max(max(s_sf[flip][0], s_sf[flip][1]), max(s_sf[flip][2], s_sf[flip][3]));
+                            flip ^= 1;
+                            if (c == os) break;
+                            os = c;
+                        }
+                        // o2 == o1: recent and pending left main's answer alone, so all block lists accept o2;
+                        // os == o2: so do the hole lists
+                        if (os == o2 && o2 == o1) return os;
+                        o = os;
+                        steps_hold = true;
                     }
                 };
                 uint32_t o;
@@ -862,9 +879,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         }
                         if (mode1) c = min(c, steps_extent_pass(L, A.lstart, l_ns, va, vf, pp));
                         c = ~wave_reduce_max32(~c);
-                        if (l == 0) s_sf[wave] = c;
+                        if (l == 0) s_sf[0][wave] = c;
                         __syncthreads();
-                        e = min(e, min(min(s_sf[0], s_sf[1]), min(s_sf[2], s_sf[3])));
+                        e = min(e, min(min(s_sf[0][0], s_sf[0][1]), min(s_sf[0][2], s_sf[0][3])));
                         __syncthreads();
                         if (e == NONE32) { o = best_gap == NONE32 ? pp : best_off; break; }
                         const uint32_t gap = e - pp;
