@@ -119,7 +119,11 @@ def main() -> int:
                 traffic = int(ln.split(":")[1])
     roofline = dict(bound="hbm", kernel="k_place_fast", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
                     frac=achieved / HBM_PEAK_GBPS, traffic=traffic, kernel_ms=k_ms, algorithmic_bytes=alg_bytes,
-                    sort_kernel_ms=float(np.mean(sort_ms)))
+                    sort_kernel_ms=float(np.mean(sort_ms)),
+                    note="achieved = algorithmic bytes (every overlapping pair read once) / kernel time; the kernel "
+                         "moves fewer bytes than that (see traffic): per-step hole lists summarise the one-step "
+                         "neighbours, so frac can exceed 1 and says how far the kernel is ahead of a pair-by-pair "
+                         "kernel running at the HBM peak")
 
     cpu = None
     if not args.no_cpu_baseline:
