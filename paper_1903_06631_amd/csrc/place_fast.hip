@@ -673,7 +673,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     __shared__ uint64_t p_oe[PEND];
     __shared__ LT p_life[PEND];
     __shared__ uint64_t s_h[PW][LH];         // per-wave hole list
-    __shared__ uint32_t s_np, s_bc;
+    __shared__ uint32_t s_np;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
     __shared__ uint32_t s_sf[2][PW];
@@ -821,12 +821,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         uint32_t o2 = o1;
                         if (nr)
                             o2 = coop_sweep(r_oe[rb], r_life[rb], nr, cr, o1, vs, va, vf, wave, s_cmax, s_hq, s_hans);
-                        if (wave == 0) {
-                            if (np) o2 = fit_unsorted(p_oe, p_life, np, o2, vs, va, vf);
-                            if (l == 0) s_bc = o2;
-                        }
-                        __syncthreads();
-                        o2 = s_bc;
+                        // the few pending entries: every wave checks them by itself (same data, same answer)
+                        if (np) o2 = fit_unsorted(p_oe, p_life, np, o2, vs, va, vf);
                         if (!mode1) {
                             if (o2 == o1) return o2;             // recent and pending agree with main's answer
                             o = o2;
