@@ -42,7 +42,8 @@
 namespace lap {
 
 constexpr int PW = 4;               // waves per ordering
-constexpr uint32_t PEND = 512;      // pending (unsorted) entries in LDS
+constexpr uint32_t PEND = 128;      // room for the pending (unsorted) entries in LDS
+constexpr uint32_t PEND_FLUSH = 32; // pending entries at which they are sorted into `recent`
 constexpr uint32_t REC = PLAN_REC;  // recent (sorted) entries per buffer, global memory
 constexpr uint32_t LH = 768;        // entries of a per-step list a wave can hold in LDS
 constexpr uint32_t CL = PLAN_CL;    // per-step lists need sum of lifetimes <= CL * N
@@ -673,7 +674,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     __shared__ uint64_t p_oe[PEND];
     __shared__ LT p_life[PEND];
     __shared__ uint64_t s_h[PW][LH];         // per-wave hole list
-    __shared__ uint32_t s_np;
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
     __shared__ uint32_t s_sf[2][PW];
@@ -702,9 +702,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     uint32_t multi_left = mode1 ? A.hdr->n_multi : n;
     // ALL list state, identical in every wave: main / recent buffer in use, their counts
     uint32_t mb = 0, rb = 0, nm = 0, nr = 0;
-    uint32_t np_multi = 0;      // pending entries that came from ALL queries (they tend to stack)
+    uint32_t np_multi = 0;      // pending entries (they come from ALL queries and tend to stack)
     uint32_t fp = 0;
-    if (threadIdx.x == 0) s_np = 0;
     if (mode1) {
         // every step starts with one hole covering the whole address space
         for (uint32_t t = threadIdx.x; t < T; t += PW * WAVE) {
@@ -750,7 +749,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         uint32_t m = WAVE;
         while (m < np) m <<= 1;
         for (uint32_t i = np + threadIdx.x; i < m; i += PW * WAVE) { p_oe[i] = U64_MAX; p_life[i] = 0; }
-        if (threadIdx.x == 0) s_np = 0;
         __syncthreads();
         bitonic_sort(p_oe, p_life, m);
         coop_merge(r_oe[rb], r_life[rb], nr, LdsList<LT>{p_oe, p_life}, np, r_oe[rb ^ 1], r_life[rb ^ 1], wave);
@@ -798,9 +796,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
                 // pending stays unsorted and is checked directly, unless many of its entries come
                 // from ALL queries: those stack on each other and would be climbed one by one
-                uint32_t np = s_np;
-                if (np_multi >= 32) {
-                    __syncthreads();
+                uint32_t np = np_multi;             // every pending entry comes from a query like this one
+                if (np >= PEND_FLUSH) {
                     flush(np);
                     np = 0;
                 }
@@ -894,7 +891,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     if (multi_left > 1) {               // someone will still query ALL
                         p_oe[np] = pk(o, en);
                         p_life[np] = Life<LT>::mk(va, vf);
-                        s_np = np + 1;
                     }
                 }
                 if (multi_left > 1) ++np_multi;
@@ -1029,14 +1025,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 p = q;
             }
         }
-        __syncthreads();
-        // keep room for the next window's placements (every wave reads the count before
-        // it may be reset)
-        const uint32_t np_now = s_np;
-        __syncthreads();
-        PROBE_T(t6);
-        if (np_now + WAVE > PEND) flush(np_now);
-        PROBE_ACC(4, t6);
+        __syncthreads();            // the next window reads the list counts this one has written
     }
 #ifdef LAP_PROBE
     pc[7] = clock64() - t_begin;
