@@ -96,12 +96,20 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
         const int shift = pass * 8;
         for (int k = l; k < 256; k += WAVE) hist[w][k] = 0;
         wave_lds_sync();
-        for (uint32_t base = lo; base < hi; base += WAVE) {
-            const uint32_t r = base + l;
-            if (r < hi) {
-                const uint32_t i = cur ? cur[r] : r;
-                const uint32_t d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
-                atomicAdd(&hist[w][d], 1u);
+        for (uint32_t base = lo; base < hi; base += 4 * WAVE) {       // four tiles at a time: independent loads
+            uint32_t iv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t r = base + u * WAVE + l;
+                iv[u] = r < hi ? (cur ? cur[r] : r) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t r = base + u * WAVE + l;
+                if (r < hi) {
+                    const uint32_t d = (uint32_t)(order_key(kind, seed, iv[u], size, alloc, free_) >> shift) & 255u;
+                    atomicAdd(&hist[w][d], 1u);
+                }
             }
         }
         __syncthreads();
@@ -133,14 +141,14 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
         __syncthreads();
         if (s_skip) { __syncthreads(); continue; }
         // stable scatter of this wave's quarter, one tile of 64 ranks at a time
+        uint32_t i_next = lo + l < hi ? (cur ? cur[lo + l] : lo + l) : 0u;       // the next tile is fetched ahead
         for (uint32_t base = lo; base < hi; base += WAVE) {
             const uint32_t r = base + l;
             const bool act = r < hi;
-            uint32_t i = 0, d = 0;
-            if (act) {
-                i = cur ? cur[r] : r;
-                d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
-            }
+            const uint32_t i = i_next;
+            i_next = r + WAVE < hi ? (cur ? cur[r + WAVE] : r + WAVE) : 0u;
+            uint32_t d = 0;
+            if (act) d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
             uint64_t same = ballot(act);
 #pragma unroll
             for (int bit = 0; bit < 8; ++bit) {
