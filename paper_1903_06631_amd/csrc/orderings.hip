@@ -56,10 +56,15 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
-// Wave w sorts the contiguous quarter [w*n/4, (w+1)*n/4) of the rank array: it counts its own
-// digits, the workgroup turns the 4 x 256 counts into per-wave output positions (digit-major,
-// wave-minor, which keeps the sort stable), and each wave scatters its quarter tile by tile
-// with its private positions -- no workgroup barrier inside the scatter loop.
+constexpr uint32_t TS = 4096;            // ranks per tile of a scatter pass
+constexpr int SUB = TS / (SW * WAVE);    // 64-rank sub-tiles per wave and tile
+
+// One radix pass = a histogram of the digit over all ranks, then tile after tile of TS ranks:
+// every wave counts the digits of its quarter of the tile, the workgroup turns the 4 x 256 counts
+// into positions inside the tile (digit-major, wave-minor, sub-tile order within a wave: stable),
+// the waves put their indices there in an LDS staging area, and the staged tile -- now grouped by
+// digit -- is written out, so that equal digits go to consecutive addresses instead of one
+// 4-byte store per cache line.
 __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64_t *__restrict__ size,
                                                         const uint32_t *__restrict__ alloc,
                                                         const uint32_t *__restrict__ free_,
@@ -68,10 +73,13 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
                                                         uint32_t *perm_all, uint32_t *tmp_all)
 {
     __shared__ uint32_t hist[SW][256];
+    __shared__ uint32_t gbase[256], tile_off[256];
+    __shared__ uint32_t stage[TS];
+    __shared__ uint32_t wtot[SW];
     __shared__ uint32_t s_skip;
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
-    const uint32_t w = threadIdx.x / WAVE;
+    const uint32_t tid = threadIdx.x, w = tid / WAVE;
     const uint32_t kind = kinds[b];
     const uint64_t seed = seeds[b];
     uint32_t *perm = perm_all + (size_t)b * n;
@@ -81,12 +89,26 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
         // caller-supplied permutation: copy.  Indices are clamped so that a malformed
         // array can never cause an out-of-range access downstream.
         const uint32_t *src = (const uint32_t *)(uintptr_t)seed;
-        for (uint32_t i = threadIdx.x; i < n; i += SW * WAVE) perm[i] = min(src[i], n - 1);
+        for (uint32_t i = tid; i < n; i += SW * WAVE) perm[i] = min(src[i], n - 1);
         return;
     }
 
-    const uint32_t seg = (n + SW - 1) / SW;
-    const uint32_t lo = min(n, w * seg), hi = min(n, lo + seg);
+    // exclusive scan over the 256 digit owners (thread d owns digit d); returns the value before d
+    auto scan256 = [&](uint32_t v) -> uint32_t {
+        uint32_t incl = v;
+#pragma unroll
+        for (int dlt = 1; dlt < WAVE; dlt <<= 1) {
+            const uint32_t t = __shfl_up(incl, dlt, WAVE);
+            if (l >= dlt) incl += t;
+        }
+        if (l == WAVE - 1) wtot[w] = incl;
+        __syncthreads();
+        uint32_t run = incl - v;
+        for (uint32_t k = 0; k < w; ++k) run += wtot[k];
+        __syncthreads();
+        return run;
+    };
+
     // cur == nullptr means the identity (no buffer read yet)
     const uint32_t *cur = nullptr;
     uint32_t *dst = perm;
@@ -94,77 +116,97 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     const int first_pass = (kind == 4) ? (n <= (1u << 22) ? 5 : 4) : (kind == 6) ? 4 : 0;
     for (int pass = first_pass; pass < 8; ++pass) {
         const int shift = pass * 8;
-        for (int k = l; k < 256; k += WAVE) hist[w][k] = 0;
-        wave_lds_sync();
-        for (uint32_t base = lo; base < hi; base += 4 * WAVE) {       // four tiles at a time: independent loads
+        // ---- histogram of this pass's digit over all ranks (thread-strided, independent loads)
+        hist[w][l] = 0; hist[w][l + 64] = 0; hist[w][l + 128] = 0; hist[w][l + 192] = 0;
+        __syncthreads();
+        for (uint32_t base = 0; base < n; base += 4 * SW * WAVE) {
             uint32_t iv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const uint32_t r = base + u * WAVE + l;
-                iv[u] = r < hi ? (cur ? cur[r] : r) : 0u;
+                const uint32_t r = base + u * SW * WAVE + tid;
+                iv[u] = r < n ? (cur ? cur[r] : r) : 0u;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const uint32_t r = base + u * WAVE + l;
-                if (r < hi) {
+                const uint32_t r = base + u * SW * WAVE + tid;
+                if (r < n) {
                     const uint32_t d = (uint32_t)(order_key(kind, seed, iv[u], size, alloc, free_) >> shift) & 255u;
                     atomicAdd(&hist[w][d], 1u);
                 }
             }
         }
         __syncthreads();
-        // thread t owns digit t: its total over the waves, an exclusive scan over the digits,
-        // then the start of every wave's share
-        {
-            const uint32_t d = threadIdx.x;
-            uint32_t c[SW], tot = 0;
+        uint32_t tot = 0;
 #pragma unroll
-            for (int k = 0; k < SW; ++k) { c[k] = hist[k][d]; tot += c[k]; }
-            if (d == 0) s_skip = 0;
-            __syncthreads();
-            if (tot == n) s_skip = 1;                 // every key has this digit: nothing moves
-            // exclusive scan of tot over 256 threads: wave scan + wave totals through hist[0]
-            uint32_t incl = tot;
-#pragma unroll
-            for (int dlt = 1; dlt < WAVE; dlt <<= 1) {
-                const uint32_t t = __shfl_up(incl, dlt, WAVE);
-                if (l >= dlt) incl += t;
-            }
-            __shared__ uint32_t wtot[SW];
-            if (l == WAVE - 1) wtot[w] = incl;
-            __syncthreads();
-            uint32_t run = incl - tot;
-            for (uint32_t k = 0; k < w; ++k) run += wtot[k];
-#pragma unroll
-            for (int k = 0; k < SW; ++k) { hist[k][d] = run; run += c[k]; }
-        }
+        for (int k = 0; k < SW; ++k) tot += hist[k][tid];
+        if (tid == 0) s_skip = 0;
         __syncthreads();
-        if (s_skip) { __syncthreads(); continue; }
-        // stable scatter of this wave's quarter, one tile of 64 ranks at a time
-        uint32_t i_next = lo + l < hi ? (cur ? cur[lo + l] : lo + l) : 0u;       // the next tile is fetched ahead
-        for (uint32_t base = lo; base < hi; base += WAVE) {
-            const uint32_t r = base + l;
-            const bool act = r < hi;
-            const uint32_t i = i_next;
-            i_next = r + WAVE < hi ? (cur ? cur[r + WAVE] : r + WAVE) : 0u;
-            uint32_t d = 0;
-            if (act) d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
-            uint64_t same = ballot(act);
-#pragma unroll
-            for (int bit = 0; bit < 8; ++bit) {
-                const uint64_t m = ballot(act && ((d >> bit) & 1u));
-                same &= ((d >> bit) & 1u) ? m : ~m;
-            }
-            const uint32_t rank = (uint32_t)__popcll(same & lt_mask);
-            const uint32_t cnt = (uint32_t)__popcll(same);
-            uint32_t pos = 0;
-            if (act) pos = hist[w][d] + rank;
-            wave_lds_sync();
-            if (act && rank == 0) hist[w][d] += cnt;
-            wave_lds_sync();
-            if (act) dst[pos] = i;
-        }
+        if (tot == n) s_skip = 1;                     // every key has this digit: nothing moves
+        gbase[tid] = scan256(tot);
         __syncthreads();
+        if (s_skip) continue;
+
+        // ---- tiles
+        for (uint32_t tb = 0; tb < n; tb += TS) {
+            hist[w][l] = 0; hist[w][l + 64] = 0; hist[w][l + 128] = 0; hist[w][l + 192] = 0;
+            wave_lds_sync();
+            uint32_t iv[SUB], dv[SUB];
+#pragma unroll
+            for (int k = 0; k < SUB; ++k) {
+                const uint32_t r = tb + (w * SUB + k) * WAVE + l;
+                iv[k] = r < n ? (cur ? cur[r] : r) : 0u;
+            }
+#pragma unroll
+            for (int k = 0; k < SUB; ++k) {
+                const uint32_t r = tb + (w * SUB + k) * WAVE + l;
+                dv[k] = 256u;
+                if (r < n) {
+                    dv[k] = (uint32_t)(order_key(kind, seed, iv[k], size, alloc, free_) >> shift) & 255u;
+                    atomicAdd(&hist[w][dv[k]], 1u);
+                }
+            }
+            __syncthreads();
+            // digit owner: where the tile's entries of this digit start, per wave
+            uint32_t c[SW], ttot = 0;
+#pragma unroll
+            for (int k = 0; k < SW; ++k) { c[k] = hist[k][tid]; ttot += c[k]; }
+            uint32_t run = scan256(ttot);
+            tile_off[tid] = run;
+#pragma unroll
+            for (int k = 0; k < SW; ++k) { hist[k][tid] = run; run += c[k]; }
+            __syncthreads();
+            // stable placement of this wave's sub-tiles into the staging area
+#pragma unroll
+            for (int k = 0; k < SUB; ++k) {
+                const uint32_t d = dv[k];
+                const bool act = d < 256u;
+                uint64_t same = ballot(act);
+#pragma unroll
+                for (int bit = 0; bit < 8; ++bit) {
+                    const uint64_t m = ballot(act && ((d >> bit) & 1u));
+                    same &= ((d >> bit) & 1u) ? m : ~m;
+                }
+                const uint32_t rank = (uint32_t)__popcll(same & lt_mask);
+                const uint32_t cnt = (uint32_t)__popcll(same);
+                uint32_t pos = 0;
+                if (act) pos = hist[w][d] + rank;
+                wave_lds_sync();
+                if (act && rank == 0) hist[w][d] += cnt;
+                wave_lds_sync();
+                if (act) stage[pos] = iv[k];
+            }
+            __syncthreads();
+            // the staged tile, grouped by digit, goes out: equal digits to consecutive addresses
+            const uint32_t tn = min(TS, n - tb);
+            for (uint32_t p = tid; p < tn; p += SW * WAVE) {
+                const uint32_t i = stage[p];
+                const uint32_t d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
+                dst[gbase[d] + (p - tile_off[d])] = i;
+            }
+            __syncthreads();
+            gbase[tid] += ttot;
+            __syncthreads();
+        }
         cur = dst;
         dst = (dst == perm) ? tmp : perm;
     }
