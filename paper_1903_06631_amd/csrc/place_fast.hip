@@ -590,26 +590,70 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const LT *lif
 // thread's steps.  Only the sorted part of a list (the holes) is read: blocks still waiting
 // in a list's tail belong to multi-step variables, which the ALL list covers.  The topmost
 // hole of every list is unbounded, so every search ends.
+// Passes over unchanged lists with a rising o (first = false after the first of them) reuse
+// what the last search of a step found, kept for the thread's first FIT_MEMO steps: its
+// answer m_at and the end m_end of the hole it lies in.  An answer at or above the new o
+// still stands; below it, the same hole may still hold [o, o + s); only otherwise is the
+// list searched again.  Most passes of a variable end this way without a load.
+constexpr int FIT_MEMO = 3;
 __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ L, const uint32_t *__restrict__ lstart,
                                                    const uint32_t *l_ns, uint32_t a, uint32_t f, uint32_t o,
-                                                   uint32_t s)
+                                                   uint32_t s, bool first, uint32_t (&m_at)[FIT_MEMO],
+                                                   uint32_t (&m_end)[FIT_MEMO], uint32_t (&m_lo)[FIT_MEMO])
 {
     uint32_t best = o;
     const uint32_t need = o + s;
-    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE) {
+    // from: holes below this index are known to end below o + s; gallop: the answer is
+    // expected close above `from` (doubling steps first, then the binary search between)
+    auto search = [&](uint32_t t, uint32_t from_idx, bool gallop, uint32_t &hole_idx, uint32_t &hole_end) -> uint32_t {
         const uint64_t *Lt = L + lstart[t];
-        uint32_t lo = 0, hi = max(l_ns[t], 1u) - 1;
+        const uint32_t top = max(l_ns[t], 1u) - 1;
+        uint32_t lo = min(from_idx, top), hi = top;
+        uint64_t xhi = 0;               // entry hi, once a probe has set hi
+        bool have = false;
+        if (gallop) {
+            uint32_t step = 1;
+            while (lo < hi) {
+                const uint32_t p = min(lo + step - 1, hi - 1);
+                const uint64_t x = Lt[p];
+                if ((uint32_t)(x >> 32) + (uint32_t)x >= need) { hi = p; xhi = x; have = true; break; }
+                lo = p + 1;
+                step <<= 1;
+            }
+        }
         while (lo < hi) {
             const uint32_t mid = (lo + hi) >> 1;
             const uint64_t x = Lt[mid];
-            if ((uint32_t)(x >> 32) + (uint32_t)x >= need) hi = mid; else lo = mid + 1;
+            if ((uint32_t)(x >> 32) + (uint32_t)x >= need) { hi = mid; xhi = x; have = true; } else lo = mid + 1;
         }
+        // lo == hi: the first hole that ends high enough (or the top one); walk up from it to
+        // the first that fits
+        uint64_t x = have ? xhi : Lt[lo];
         for (;;) {
-            const uint64_t x = Lt[lo];
             const uint32_t st = (uint32_t)(x >> 32), from = max(o, st);
-            if (st + (uint32_t)x - from >= s) { best = max(best, from); break; }
+            if (st + (uint32_t)x - from >= s) {
+                hole_idx = lo;
+                hole_end = lo >= top ? NONE32 : st + (uint32_t)x;
+                return from;
+            }
             ++lo;
+            x = Lt[lo];
         }
+    };
+    uint32_t t = a + threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < FIT_MEMO; ++k, t += PW * WAVE) {
+        if (t >= f) continue;
+        if (!first) {
+            if (m_at[k] >= o) { best = max(best, m_at[k]); continue; }
+            if (m_end[k] >= need) continue;            // fits at o itself
+        }
+        m_at[k] = search(t, first ? 0u : m_lo[k] + 1, !first, m_lo[k], m_end[k]);
+        best = max(best, m_at[k]);
+    }
+    for (; t < f; t += PW * WAVE) {
+        uint32_t e, i;
+        best = max(best, search(t, 0u, false, i, e));
     }
     return best;
 }
@@ -829,8 +873,11 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         // one-step variables are not in ALL: the hole lists of the steps it lives through
                         // stand for them.  Passes repeat until no step moves the candidate.
                         uint32_t os = o2;
+                        uint32_t m_at[FIT_MEMO], m_end[FIT_MEMO], m_lo[FIT_MEMO];
+                        bool first = true;
                         for (;;) {
-                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs);
+                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs, first, m_at, m_end, m_lo);
+                            first = false;
                             c = wave_reduce_max32(c);
                             if (l == 0) s_sf[flip][wave] = c;
                             __syncthreads();
