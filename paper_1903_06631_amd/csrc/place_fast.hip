@@ -591,15 +591,17 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const LT *lif
 // in a list's tail belong to multi-step variables, which the ALL list covers.  The topmost
 // hole of every list is unbounded, so every search ends.
 // Passes over unchanged lists with a rising o (first = false after the first of them) reuse
-// what the last search of a step found, kept for the thread's first FIT_MEMO steps: its
-// answer m_at and the end m_end of the hole it lies in.  An answer at or above the new o
-// still stands; below it, the same hole may still hold [o, o + s); only otherwise is the
-// list searched again.  Most passes of a variable end this way without a load.
-constexpr int FIT_MEMO = 3;
+// what the last search of a step found, kept for the thread's first FIT_MEMO steps in the
+// wave's LDS slice `memo` (3 words per step, lane-interleaved; the slice holds no hole list
+// while a multi-step variable is being placed): its answer, the end of the hole it lies in
+// and that hole's index.  An answer at or above the new o still stands; below it, the same
+// hole may still hold [o, o + s); otherwise the search resumes just above that hole, where
+// the next answer is usually a few holes away.
+constexpr uint32_t FIT_MEMO = 8;
+static_assert(FIT_MEMO * 3 * WAVE * sizeof(uint32_t) <= LH * sizeof(uint64_t), "the memo must fit the wave's list slice");
 __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ L, const uint32_t *__restrict__ lstart,
                                                    const uint32_t *l_ns, uint32_t a, uint32_t f, uint32_t o,
-                                                   uint32_t s, bool first, uint32_t (&m_at)[FIT_MEMO],
-                                                   uint32_t (&m_end)[FIT_MEMO], uint32_t (&m_lo)[FIT_MEMO])
+                                                   uint32_t s, bool first, uint32_t *memo)
 {
     uint32_t best = o;
     const uint32_t need = o + s;
@@ -640,33 +642,43 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
             x = Lt[lo];
         }
     };
-    uint32_t t = a + threadIdx.x;
-#pragma unroll
-    for (int k = 0; k < FIT_MEMO; ++k, t += PW * WAVE) {
-        if (t >= f) continue;
-        if (!first) {
-            if (m_at[k] >= o) { best = max(best, m_at[k]); continue; }
-            if (m_end[k] >= need) continue;            // fits at o itself
+    uint32_t *mm = memo + lane_id();
+    uint32_t k = 0;
+    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE, ++k) {
+        const bool kept = k < FIT_MEMO;
+        uint32_t *mk = mm + k * 3 * WAVE;
+        uint32_t from_idx = 0;
+        if (kept && !first) {
+            const uint32_t m_at = mk[0], m_end = mk[WAVE], m_lo = mk[2 * WAVE];
+            if (m_at >= o) { best = max(best, m_at); continue; }
+            if (m_end >= need) continue;                 // fits at o itself
+            from_idx = m_lo + 1;
         }
-        m_at[k] = search(t, first ? 0u : m_lo[k] + 1, !first, m_lo[k], m_end[k]);
-        best = max(best, m_at[k]);
-    }
-    for (; t < f; t += PW * WAVE) {
-        uint32_t e, i;
-        best = max(best, search(t, 0u, false, i, e));
+        uint32_t idx, end;
+        const uint32_t at = search(t, from_idx, from_idx != 0, idx, end);
+        best = max(best, at);
+        if (kept) { mk[0] = at; mk[WAVE] = end; mk[2 * WAVE] = idx; }
     }
     return best;
 }
 
 // Best-fit needs the size of the hole that starts at a feasible offset p.  In the hole lists:
-// every thread takes its steps of [a, f), finds the hole that holds p (the first whose end lies
-// above p) and returns the lowest such end over its steps (0xFFFFFFFF = unbounded).
+// the lowest end, over the steps of [a, f), of the hole that holds p (0xFFFFFFFF = unbounded).
+// p comes from a fixed point of steps_fit_pass, whose last pass found, for every step, the
+// hole that holds [p, p + s): its end is still in `memo` for the thread's first FIT_MEMO
+// steps; later steps look their hole up (the first whose end lies above p).
 __device__ __forceinline__ uint32_t steps_extent_pass(const uint64_t *__restrict__ L,
                                                       const uint32_t *__restrict__ lstart, const uint32_t *l_ns,
-                                                      uint32_t a, uint32_t f, uint32_t p)
+                                                      uint32_t a, uint32_t f, uint32_t p, const uint32_t *memo)
 {
     uint32_t e = NONE32;
-    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE) {
+    const uint32_t *mm = memo + lane_id();
+    uint32_t k = 0;
+    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE, ++k) {
+        if (k < FIT_MEMO) {
+            e = min(e, mm[(k * 3 + 1) * WAVE]);
+            continue;
+        }
         const uint64_t *Lt = L + lstart[t];
         uint32_t lo = 0, hi = max(l_ns[t], 1u) - 1;
         while (lo < hi) {
@@ -847,6 +859,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 }
                 PROBE_ACC(0, t2); PROBE_T(t3);
                 uint32_t cm = 0, cr = 0;
+                // no hole-list pass yet for this variable (the lists do not change and the candidate
+                // only rises while it is being placed, so later passes may build on earlier ones)
+                bool first = true;
                 // lowest offset >= `from` that is free of every neighbour: the sorted lists, the
                 // pending entries and (with per-step lists) the hole lists are asked in turn until
                 // none of them moves the candidate
@@ -873,10 +888,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         // one-step variables are not in ALL: the hole lists of the steps it lives through
                         // stand for them.  Passes repeat until no step moves the candidate.
                         uint32_t os = o2;
-                        uint32_t m_at[FIT_MEMO], m_end[FIT_MEMO], m_lo[FIT_MEMO];
-                        bool first = true;
                         for (;;) {
-                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs, first, m_at, m_end, m_lo);
+                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs, first, (uint32_t *)hl);
                             first = false;
                             c = wave_reduce_max32(c);
                             if (l == 0) s_sf[flip][wave] = c;
@@ -917,7 +930,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                                 if (Life<LT>::a(lf) < vf && va < Life<LT>::f(lf) && po >= pp) c = min(c, po);
                             }
                         }
-                        if (mode1) c = min(c, steps_extent_pass(L, A.lstart, l_ns, va, vf, pp));
+                        if (mode1) c = min(c, steps_extent_pass(L, A.lstart, l_ns, va, vf, pp, (const uint32_t *)hl));
                         c = ~wave_reduce_max32(~c);
                         if (l == 0) s_sf[0][wave] = c;
                         __syncthreads();
