@@ -772,7 +772,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     // this wave's register-resident per-step list: step, entries, hole count, range of
     // indices not yet written back; wmask remembers (hashed) which lists were stored since
     // the last fence
-    uint32_t cur_t = NONE32, cnt = 0, wb_from = NONE32, wb_to = 0;
+    uint32_t cur_t = NONE32, cur_base = 0, cnt = 0, wb_from = NONE32, wb_to = 0;
     uint64_t wmask = 0;
     // per lane, for the one-step variable of this lane's rank: list start, sorted and
     // unsorted entry counts of its step (kept current by the code below)
@@ -780,7 +780,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 
     auto writeback = [&](uint32_t a_lane) {
         if (cur_t != NONE32 && wb_from != NONE32) {
-            uint64_t *Lt = L + A.lstart[cur_t];
+            uint64_t *Lt = L + cur_base;
             for (uint32_t idx = wb_from + l; idx < wb_to; idx += WAVE) Lt[idx] = hl[idx];
             if (l == 0) { l_ns[cur_t] = cnt; l_nu[cur_t] = 0; }
             wmask |= 1ull << ((cur_t / PW) & 63);
@@ -975,6 +975,10 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 const uint32_t run = (~rest == 0ull) ? 64u : (uint32_t)(__ffsll((unsigned long long)~rest) - 1);
                 const uint32_t q = p + run;
                 uint64_t mine = ballot((uint32_t)l >= p && (uint32_t)l < q && (a % PW) == wave);
+                // results stay in the lane of their rank until the run ends: one store then, none
+                // in flight while the next list is waited for
+                const bool my_rank = (mine >> l) & 1ull;
+                uint32_t res = 0;
                 // the list of the NEXT variable of this wave is fetched into registers while the
                 // current one is being placed
                 uint64_t pf[LH / WAVE];
@@ -984,7 +988,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 while (mine) {
                     const int j = __ffsll((unsigned long long)mine) - 1;
                     mine &= mine - 1;
-                    const uint32_t vv = read_lane(v, j), t = read_lane(a, j), vs = read_lane(s, j);
+                    const uint32_t t = read_lane(a, j), vs = read_lane(s, j);
                     uint32_t o;
                     if (t != cur_t) PROBE_CNT(5, 1);
                     if (t != cur_t) {
@@ -1014,6 +1018,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                                 nh = h_carve(hl, nh, nt - 1, (uint32_t)(x >> 32), (uint32_t)x, wb_from, wb_to);
                             }
                             cur_t = t;
+                            cur_base = base;
                             cnt = nh;
                         }
                     }
@@ -1079,8 +1084,9 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         if (one_step && a == t) { pns = nh; pnu = 0; }
                     }
                     fp = max(fp, o + vs);
-                    if (l == 0) offs[vv] = (uint64_t)o << sh;
+                    if (l == j) res = o;
                 }
+                if (my_rank) offs[v] = (uint64_t)res << sh;
                 PROBE_ACC(3, t5);
                 p = q;
             }
