@@ -839,7 +839,8 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         const uint64_t mm = ballot(in && (!mode1 || f - a > 1));
         const uint32_t wn = (uint32_t)__popcll(im);
         const bool one_step = in && mode1 && f - a == 1;
-        if (one_step) { plb = A.lstart[a]; pns = l_ns[a]; pnu = l_nu[a]; }
+        const bool own = one_step && (a % PW) == wave;       // only the owner of a step looks at its list
+        if (own) { plb = A.lstart[a]; pns = l_ns[a]; pnu = l_nu[a]; }
         if (cur_t != NONE32 && one_step && a == cur_t) { pns = cnt; pnu = 0; }   // the cached list is newer
         uint32_t p = 0;
         while (p < wn) {
@@ -966,7 +967,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 --multi_left;
                 __syncthreads();
                 // the tails of the steps it covers grew: refresh the counts of the ranks to come
-                if (one_step && (uint32_t)l > p && a >= va && a < vf) pnu = l_nu[a];
+                if (own && (uint32_t)l > p && a >= va && a < vf) pnu = l_nu[a];
                 ++p;
             } else {
                 // ---- a run of one-step variables: each wave takes the steps it owns --------
