@@ -1092,7 +1092,11 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 p = q;
             }
         }
-        __syncthreads();            // the next window reads the list counts this one has written
+        // No barrier between windows: a wave reads, for the next window, only the counts of the
+        // steps it owns, which no other wave writes outside the barriers of a multi-step
+        // variable; its own stores to them are complete after this fence.  The waves drift
+        // apart until the next multi-step variable brings them together.
+        wave_fence();
     }
 #ifdef LAP_PROBE
     pc[7] = clock64() - t_begin;
