@@ -724,6 +724,32 @@ __device__ __forceinline__ uint32_t coop_next_overlap(const uint64_t *oe, const 
     return NONE32;
 }
 
+// A list of `tot` entries moves between global memory, registers (entry i in register i / 64
+// of lane i % 64) and LDS in chunks of 64; the chain of tests ends at the first chunk that
+// lies beyond the list, so a short list costs few branches.
+template <int C>
+__device__ __forceinline__ void regs_from_global(uint64_t (&r)[LH / WAVE], const uint64_t *src, uint32_t tot, int l)
+{
+    if constexpr (C < (int)(LH / WAVE)) {
+        if ((uint32_t)C * WAVE < tot) {
+            const uint32_t idx = C * WAVE + l;
+            r[C] = idx < tot ? src[idx] : 0ull;
+            regs_from_global<C + 1>(r, src, tot, l);
+        }
+    }
+}
+template <int C>
+__device__ __forceinline__ void lds_from_regs(uint64_t *hl, const uint64_t (&r)[LH / WAVE], uint32_t tot, int l)
+{
+    if constexpr (C < (int)(LH / WAVE)) {
+        if ((uint32_t)C * WAVE < tot) {
+            const uint32_t idx = C * WAVE + l;
+            if (idx < tot) hl[idx] = r[C];
+            lds_from_regs<C + 1>(hl, r, tot, l);
+        }
+    }
+}
+
 template <class LT, bool BEST>
 __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 {
@@ -1000,11 +1026,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         if (pf_t != t && (wmask & (1ull << ((t / PW) & 63)))) { wave_fence(); wmask = 0; }
                         if (tot + 1 <= LH) {
                             if (pf_t == t) {
-#pragma unroll
-                                for (int c = 0; c < (int)(LH / WAVE); ++c) {
-                                    const uint32_t idx = c * WAVE + l;
-                                    if ((uint32_t)c * WAVE < tot && idx < tot) hl[idx] = pf[c];
-                                }
+                                lds_from_regs<0>(hl, pf, tot, l);
                             } else {
                                 const uint64_t *Lt = L + base;
                                 for (uint32_t idx = l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
@@ -1029,12 +1051,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         const uint32_t tn = read_lane(a, jn);
                         const uint32_t totn = read_lane(pns, jn) + read_lane(pnu, jn);
                         if (tn != t && totn + 1 <= LH && !(wmask & (1ull << ((tn / PW) & 63)))) {
-                            const uint64_t *Ln = L + read_lane(plb, jn);
-#pragma unroll
-                            for (int c = 0; c < (int)(LH / WAVE); ++c) {
-                                const uint32_t idx = c * WAVE + l;
-                                pf[c] = ((uint32_t)c * WAVE < totn && idx < totn) ? Ln[idx] : 0ull;
-                            }
+                            regs_from_global<0>(pf, L + read_lane(plb, jn), totn, l);
                             pf_t = tn;
                         }
                     }
