@@ -272,17 +272,22 @@ __device__ __forceinline__ uint32_t h_best_fit(const uint64_t *hl, uint32_t nh, 
     return best == U64_MAX ? nh - 1 : (uint32_t)best;
 }
 
-// index of the hole that contains address o (start <= o < start + size)
-__device__ __forceinline__ uint32_t h_find_hole(const uint64_t *hl, uint32_t nh, uint32_t o)
+// index of the hole that contains address o (start <= o < start + size); x receives the hole
+__device__ __forceinline__ uint32_t h_find_hole(const uint64_t *hl, uint32_t nh, uint32_t o, uint64_t &x)
 {
     const int l = lane_id();
     for (uint32_t base = 0; base < nh; base += WAVE) {
         const uint32_t idx = base + l;
-        const uint64_t x = idx < nh ? hl[idx] : 0ull;
-        const uint32_t st = (uint32_t)(x >> 32), sz = (uint32_t)x;
+        const uint64_t y = idx < nh ? hl[idx] : 0ull;
+        const uint32_t st = (uint32_t)(y >> 32), sz = (uint32_t)y;
         const uint64_t m = ballot(st <= o && o - st < sz);
-        if (m) return base + __ffsll((unsigned long long)m) - 1;
+        if (m) {
+            const int j = __ffsll((unsigned long long)m) - 1;
+            x = read_lane64(y, j);
+            return base + j;
+        }
     }
+    x = hl[nh - 1];
     return nh - 1;
 }
 
@@ -319,21 +324,20 @@ __device__ __forceinline__ void h_delete(uint64_t *hl, uint32_t n, uint32_t p)
     }
 }
 
-// Remove the block [o, en) from the free ranges: it lies inside exactly one hole.  The list
-// holds nh holes followed by ntail other entries (which move up if a hole is split).  Returns
-// the number of holes afterwards; [lo, hi) is extended to the entries that changed.
-__device__ __forceinline__ uint32_t h_carve(uint64_t *hl, uint32_t nh, uint32_t ntail, uint32_t o, uint32_t en,
-                                            uint32_t &lo, uint32_t &hi)
+// Remove the block [o, en) from the nh free ranges in hl: it lies inside exactly one hole.
+// Returns the number of holes afterwards; [lo, hi) is extended to the entries that changed.
+__device__ __forceinline__ uint32_t h_carve(uint64_t *hl, uint32_t nh, uint32_t o, uint32_t en, uint32_t &lo,
+                                            uint32_t &hi)
 {
     const int l = lane_id();
-    const uint32_t h = h_find_hole(hl, nh, o);
-    const uint64_t x = hl[h];
+    uint64_t x;
+    const uint32_t h = h_find_hole(hl, nh, o, x);
     const uint32_t st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
     lo = min(lo, h);
     lds_sync();
     if (o == st && en == hend) {         // the hole is used up: it leaves the list
-        h_delete(hl, nh + ntail, h);
-        hi = max(hi, nh + ntail - 1);
+        h_delete(hl, nh, h);
+        hi = max(hi, nh - 1);
         return nh - 1;
     }
     if (o == st) {                       // block at the hole's start: the hole shrinks from below
@@ -345,8 +349,8 @@ __device__ __forceinline__ uint32_t h_carve(uint64_t *hl, uint32_t nh, uint32_t 
     if (l == 0) hl[h] = pk(st, o - st);  // lower part stays
     lds_sync();
     if (en == hend) { hi = max(hi, h + 1); return nh; }
-    h_insert(hl, nh + ntail, h + 1, pk(en, hend - en));   // upper part: a new hole after it
-    hi = max(hi, nh + ntail + 1);
+    h_insert(hl, nh, h + 1, pk(en, hend - en));   // upper part: a new hole after it
+    hi = max(hi, nh + 1);
     return nh + 1;
 }
 
@@ -1033,12 +1037,19 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                             }
                             lds_sync();
                             PROBE_CNT(6, tot - ns);
-                            // carve the multi-step blocks that arrived since out of the holes, last
-                            // tail entry first (a split moves the rest of the tail up with it)
+                            // carve the multi-step blocks that arrived since out of the holes.  The tail
+                            // is taken into registers 64 entries at a time (lane i holds entry i); the
+                            // holes may then grow over its place: k blocks add at most k holes, and
+                            // the next 64 start 64 entries further up.
                             uint32_t nh = ns;
-                            for (uint32_t nt = nu; nt > 0; --nt) {
-                                const uint64_t x = hl[nh + nt - 1];
-                                nh = h_carve(hl, nh, nt - 1, (uint32_t)(x >> 32), (uint32_t)x, wb_from, wb_to);
+                            for (uint32_t tb = 0; tb < nu; tb += WAVE) {
+                                const uint32_t m = min(nu - tb, (uint32_t)WAVE);
+                                const uint64_t te = (uint32_t)l < m ? hl[ns + tb + l] : 0ull;
+                                lds_sync();
+                                for (uint32_t i = 0; i < m; ++i) {
+                                    const uint64_t x = read_lane64(te, (int)i);
+                                    nh = h_carve(hl, nh, (uint32_t)(x >> 32), (uint32_t)x, wb_from, wb_to);
+                                }
                             }
                             cur_t = t;
                             cur_base = base;
