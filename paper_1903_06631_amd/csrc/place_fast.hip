@@ -60,6 +60,15 @@ __device__ __forceinline__ void lds_sync()
 
 __device__ __forceinline__ uint64_t pk(uint32_t off, uint32_t end) { return ((uint64_t)off << 32) | end; }
 
+// A value every lane holds alike (all read the same address, or reduced it together), moved to
+// scalar registers: what is computed from it, loop bounds and branch conditions above all,
+// is then known to be the same in all lanes.
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint64_t uniform64(uint64_t v)
+{
+    return ((uint64_t)uniform((uint32_t)(v >> 32)) << 32) | uniform((uint32_t)v);
+}
+
 // A block's lifetime [alloc, free) next to its packed addresses: 64 bits in general, 32 bits
 // (16 + 16) when the time line has at most 65535 steps -- a quarter less list traffic.
 template <class LT> struct Life;
@@ -269,7 +278,7 @@ __device__ __forceinline__ uint32_t h_best_fit(const uint64_t *hl, uint32_t nh, 
     }
 #pragma unroll
     for (int m = WAVE / 2; m > 0; m >>= 1) best = umin64(best, shfl_xor64(best, m));
-    return best == U64_MAX ? nh - 1 : (uint32_t)best;
+    return uniform(best == U64_MAX ? nh - 1 : (uint32_t)best);
 }
 
 // index of the hole that contains address o (start <= o < start + size); x receives the hole
@@ -287,7 +296,7 @@ __device__ __forceinline__ uint32_t h_find_hole(const uint64_t *hl, uint32_t nh,
             return base + j;
         }
     }
-    x = hl[nh - 1];
+    x = uniform64(hl[nh - 1]);
     return nh - 1;
 }
 
@@ -1068,7 +1077,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     }
                     if (cur_t == t) {
                         const uint32_t h = BEST ? h_best_fit(hl, cnt, vs) : h_first_fit(hl, cnt, vs);
-                        const uint64_t x = hl[h];
+                        const uint64_t x = uniform64(hl[h]);
                         o = (uint32_t)(x >> 32);
                         lds_sync();
                         wb_from = min(wb_from, h);
