@@ -13,6 +13,8 @@ struct PlanHeader {
     uint32_t shift;                // log2 of the offset granule: ctz(or_sizes)
     uint32_t fast;                 // 1: sum_sizes >> shift fits 32 bits -> packed 32-bit path
     uint32_t mode1;                // 1: per-step lists are in use (sum of lifetimes <= PLAN_CL * N)
+    uint32_t part[2];              // placement workgroups that have started, per fit policy
+    uint32_t progress[2];          // their progress, in units of 512 ranks, summed
 };
 constexpr uint32_t PLAN_CL = 6;
 
@@ -32,7 +34,7 @@ hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const 
                             const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st);
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,
-                             bool any_best, const PlanHeader *hdr,
+                             bool any_best, PlanHeader *hdr,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,

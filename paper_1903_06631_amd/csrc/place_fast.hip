@@ -45,6 +45,7 @@ constexpr int PW = 4;               // waves per ordering
 constexpr uint32_t PEND = 128;      // room for the pending (unsorted) entries in LDS
 constexpr uint32_t PEND_FLUSH = 32; // pending entries at which they are sorted into `recent`
 constexpr uint32_t REC = PLAN_REC;  // recent (sorted) entries per buffer, global memory
+constexpr uint32_t PACE_RANKS = 512; // a workgroup reports its progress every this many ranks (power of two)
 constexpr uint32_t LH = 768;        // entries of a per-step list a wave can hold in LDS
 constexpr uint32_t CL = PLAN_CL;    // per-step lists need sum of lifetimes <= CL * N
 
@@ -373,7 +374,7 @@ struct FastArgs {
     const uint32_t *alloc, *free_;
     const uint32_t *perm;        // [B][n]
     const uint32_t *fits;        // [B] 0 = first-fit, 1 = best-fit
-    const PlanHeader *hdr;
+    PlanHeader *hdr;
     const uint32_t *lstart;      // [T+1]
     uint64_t *m_oe[2];           // [B][n] x 2  ALL main list, two buffers (merges ping-pong)
     void *m_life[2];             //             lifetimes of its entries (32- or 64-bit words)
@@ -772,6 +773,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     __shared__ uint32_t s_fp[PW], s_hq[PW], s_hans[PW];
     __shared__ uint32_t s_cmax[ROUND_CH];
     __shared__ uint32_t s_sf[2][PW];
+    __shared__ uint32_t s_prio;              // wave priority in force for this workgroup
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
     const uint32_t b = blockIdx.x;
@@ -799,6 +801,18 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     uint32_t mb = 0, rb = 0, nm = 0, nr = 0;
     uint32_t np_multi = 0;      // pending entries (they come from ALL queries and tend to stack)
     uint32_t fp = 0;
+    // Pacing.  The launch ends with its slowest ordering, and orderings differ: by what they
+    // hold (some need more passes), and by where their workgroup sits (the hardware issues
+    // older waves first, so the workgroup that reached a CU last runs about a tenth slower).
+    // Every 512 ranks a workgroup adds one to a global count and compares its own progress
+    // with the mean over all: behind the mean it raises the issue priority of its waves,
+    // ahead of it it lowers it.  That evens out the second effect; the first remains (pausing
+    // the orderings that are ahead does not speed up the ones behind).
+    uint32_t *g_part = &A.hdr->part[BEST ? 1 : 0], *g_prog = &A.hdr->progress[BEST ? 1 : 0];
+    if (threadIdx.x == 0) {
+        atomicAdd(g_part, 1u);
+        s_prio = 1;
+    }
     if (mode1) {
         // every step starts with one hole covering the whole address space
         for (uint32_t t = threadIdx.x; t < T; t += PW * WAVE) {
@@ -864,7 +878,25 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 #define PROBE_ACC(k, v)
 #define PROBE_CNT(k, x)
 #endif
+    uint32_t prio_now = 1;
+    __builtin_amdgcn_s_setprio(1);
     for (uint32_t r0 = 0; r0 < n; r0 += WAVE) {
+        if (r0 && (r0 & (PACE_RANKS - 1)) == 0) {
+            if (threadIdx.x == 0) {
+                const uint32_t done = atomicAdd(g_prog, 1u) + 1u;
+                const uint32_t started = max(*(volatile uint32_t *)g_part, 1u);
+                const int lag = (int)(done / started) - (int)(r0 / PACE_RANKS);
+                *(volatile uint32_t *)&s_prio = lag >= 2 ? 3u : lag >= 0 ? 2u : lag >= -2 ? 1u : 0u;
+            }
+            const uint32_t want = uniform(*(volatile uint32_t *)&s_prio);
+            if (want != prio_now) {
+                prio_now = want;
+                if (want == 0) __builtin_amdgcn_s_setprio(0);
+                else if (want == 1) __builtin_amdgcn_s_setprio(1);
+                else if (want == 2) __builtin_amdgcn_s_setprio(2);
+                else __builtin_amdgcn_s_setprio(3);
+            }
+        }
         const uint32_t ridx = r0 + l;
         const bool in = ridx < n;
         uint32_t v = 0, a = 0, f = 1, s = 0;
@@ -1164,7 +1196,7 @@ hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const 
 
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,
-                             bool any_best, const PlanHeader *hdr,
+                             bool any_best, PlanHeader *hdr,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,
