@@ -617,11 +617,11 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
                                                    const uint32_t *l_ns, uint32_t a, uint32_t f, uint32_t o,
                                                    uint32_t s, bool first, uint32_t *memo)
 {
-    uint32_t best = o;
-    const uint32_t need = o + s;
-    // from: holes below this index are known to end below o + s; gallop: the answer is
-    // expected close above `from` (doubling steps first, then the binary search between)
-    auto search = [&](uint32_t t, uint32_t from_idx, bool gallop, uint32_t &hole_idx, uint32_t &hole_end) -> uint32_t {
+    // oq: the offset asked for, need = oq + s; from: holes below this index are known to end
+    // below need; gallop: the answer is expected close above `from` (doubling steps first, then
+    // the binary search between)
+    auto search = [&](uint32_t t, uint32_t oq, uint32_t need, uint32_t from_idx, bool gallop, uint32_t &hole_idx,
+                      uint32_t &hole_end) -> uint32_t {
         const uint64_t *Lt = L + lstart[t];
         const uint32_t top = max(l_ns[t], 1u) - 1;
         uint32_t lo = min(from_idx, top), hi = top;
@@ -646,7 +646,7 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
         // the first that fits
         uint64_t x = have ? xhi : Lt[lo];
         for (;;) {
-            const uint32_t st = (uint32_t)(x >> 32), from = max(o, st);
+            const uint32_t st = (uint32_t)(x >> 32), from = max(oq, st);
             if (st + (uint32_t)x - from >= s) {
                 hole_idx = lo;
                 hole_end = lo >= top ? NONE32 : st + (uint32_t)x;
@@ -656,22 +656,35 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
             x = Lt[lo];
         }
     };
+    // The thread's steps are taken in rounds of 256 steps (64 per wave); after each round the
+    // wave's highest answer becomes the offset asked for in the next, so that a pass over a long
+    // lifetime climbs as far as two or three passes over a short one.  (Any offset up to the
+    // pass's result is a valid question: the final answer lies at or above it.)
+    uint32_t best = o;
     uint32_t *mm = memo + lane_id();
-    uint32_t k = 0;
-    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE, ++k) {
-        const bool kept = k < FIT_MEMO;
-        uint32_t *mk = mm + k * 3 * WAVE;
-        uint32_t from_idx = 0;
-        if (kept && !first) {
-            const uint32_t m_at = mk[0], m_end = mk[WAVE], m_lo = mk[2 * WAVE];
-            if (m_at >= o) { best = max(best, m_at); continue; }
-            if (m_end >= need) continue;                 // fits at o itself
-            from_idx = m_lo + 1;
+    const uint32_t rounds = (f - a + PW * WAVE - 1) / (PW * WAVE);
+    for (uint32_t k = 0; k < rounds; ++k) {
+        const uint32_t t = a + threadIdx.x + k * PW * WAVE;
+        uint32_t at = best;
+        if (t < f) {
+            const uint32_t oq = best, need = oq + s;
+            const bool kept = k < FIT_MEMO;
+            uint32_t *mk = mm + k * 3 * WAVE;
+            uint32_t from_idx = 0;
+            bool done = false;
+            if (kept && !first) {
+                const uint32_t m_at = mk[0], m_end = mk[WAVE], m_lo = mk[2 * WAVE];
+                if (m_at >= oq) { at = m_at; done = true; }
+                else if (m_end >= need) done = true;        // fits at oq itself
+                else from_idx = m_lo + 1;
+            }
+            if (!done) {
+                uint32_t idx, end;
+                at = search(t, oq, need, from_idx, from_idx != 0, idx, end);
+                if (kept) { mk[0] = at; mk[WAVE] = end; mk[2 * WAVE] = idx; }
+            }
         }
-        uint32_t idx, end;
-        const uint32_t at = search(t, from_idx, from_idx != 0, idx, end);
-        best = max(best, at);
-        if (kept) { mk[0] = at; mk[WAVE] = end; mk[2 * WAVE] = idx; }
+        best = wave_reduce_max32(at);
     }
     return best;
 }
