@@ -663,6 +663,10 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
     uint32_t best = o;
     uint32_t *mm = memo + lane_id();
     const uint32_t rounds = (f - a + PW * WAVE - 1) / (PW * WAVE);
+    // ... and the wave goes over its own steps again until they all accept its answer: an offset
+    // that fails among 64 * rounds steps is dropped without asking the other three quarters.
+    for (;;) {
+    const uint32_t sweep_from = best;
     for (uint32_t k = 0; k < rounds; ++k) {
         const uint32_t t = a + threadIdx.x + k * PW * WAVE;
         uint32_t at = best;
@@ -685,6 +689,9 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
             }
         }
         best = wave_reduce_max32(at);
+    }
+    if (best == sweep_from) break;
+    first = false;
     }
     return best;
 }
