@@ -606,13 +606,15 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const LT *lif
 // hole of every list is unbounded, so every search ends.
 // Passes over unchanged lists with a rising o (first = false after the first of them) reuse
 // what the last search of a step found, kept for the thread's first FIT_MEMO steps in the
-// wave's LDS slice `memo` (3 words per step, lane-interleaved; the slice holds no hole list
-// while a multi-step variable is being placed): its answer, the end of the hole it lies in
-// and that hole's index.  An answer at or above the new o still stands; below it, the same
+// wave's LDS slice `memo` (5 words per step, lane-interleaved; the slice holds no hole list
+// while a multi-step variable is being placed): its answer, the end of the hole it lies in,
+// that hole's index, and where the step's list starts and ends (so that a later search goes
+// straight to the holes).  An answer at or above the new o still stands; below it, the same
 // hole may still hold [o, o + s); otherwise the search resumes just above that hole, where
 // the next answer is usually a few holes away.
-constexpr uint32_t FIT_MEMO = 8;
-static_assert(FIT_MEMO * 3 * WAVE * sizeof(uint32_t) <= LH * sizeof(uint64_t), "the memo must fit the wave's list slice");
+constexpr uint32_t FIT_MEMO = 4;
+constexpr uint32_t FIT_WORDS = 5;   // per step: answer, end of its hole, its index, list start, index of the top hole
+static_assert(FIT_MEMO * FIT_WORDS * WAVE * sizeof(uint32_t) <= LH * sizeof(uint64_t), "the memo must fit the wave's list slice");
 __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ L, const uint32_t *__restrict__ lstart,
                                                    const uint32_t *l_ns, uint32_t a, uint32_t f, uint32_t o,
                                                    uint32_t s, bool first, uint32_t *memo)
@@ -620,10 +622,9 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
     // oq: the offset asked for, need = oq + s; from: holes below this index are known to end
     // below need; gallop: the answer is expected close above `from` (doubling steps first, then
     // the binary search between)
-    auto search = [&](uint32_t t, uint32_t oq, uint32_t need, uint32_t from_idx, bool gallop, uint32_t &hole_idx,
-                      uint32_t &hole_end) -> uint32_t {
-        const uint64_t *Lt = L + lstart[t];
-        const uint32_t top = max(l_ns[t], 1u) - 1;
+    auto search = [&](uint32_t base, uint32_t top, uint32_t oq, uint32_t need, uint32_t from_idx, bool gallop,
+                      uint32_t &hole_idx, uint32_t &hole_end) -> uint32_t {
+        const uint64_t *Lt = L + base;
         uint32_t lo = min(from_idx, top), hi = top;
         uint64_t xhi = 0;               // entry hi, once a probe has set hi
         bool have = false;
@@ -673,18 +674,23 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
         if (t < f) {
             const uint32_t oq = best, need = oq + s;
             const bool kept = k < FIT_MEMO;
-            uint32_t *mk = mm + k * 3 * WAVE;
-            uint32_t from_idx = 0;
+            uint32_t *mk = mm + k * FIT_WORDS * WAVE;
+            uint32_t from_idx = 0, base, top;
             bool done = false;
             if (kept && !first) {
                 const uint32_t m_at = mk[0], m_end = mk[WAVE], m_lo = mk[2 * WAVE];
                 if (m_at >= oq) { at = m_at; done = true; }
                 else if (m_end >= need) done = true;        // fits at oq itself
-                else from_idx = m_lo + 1;
+                else { from_idx = m_lo + 1; base = mk[3 * WAVE]; top = mk[4 * WAVE]; }
             }
             if (!done) {
+                if (from_idx == 0) {
+                    base = lstart[t];
+                    top = max(l_ns[t], 1u) - 1;
+                    if (kept) { mk[3 * WAVE] = base; mk[4 * WAVE] = top; }
+                }
                 uint32_t idx, end;
-                at = search(t, oq, need, from_idx, from_idx != 0, idx, end);
+                at = search(base, top, oq, need, from_idx, from_idx != 0, idx, end);
                 if (kept) { mk[0] = at; mk[WAVE] = end; mk[2 * WAVE] = idx; }
             }
         }
@@ -710,7 +716,7 @@ __device__ __forceinline__ uint32_t steps_extent_pass(const uint64_t *__restrict
     uint32_t k = 0;
     for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE, ++k) {
         if (k < FIT_MEMO) {
-            e = min(e, mm[(k * 3 + 1) * WAVE]);
+            e = min(e, mm[(k * FIT_WORDS + 1) * WAVE]);
             continue;
         }
         const uint64_t *Lt = L + lstart[t];
