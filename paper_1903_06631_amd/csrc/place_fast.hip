@@ -282,11 +282,13 @@ __device__ __forceinline__ uint32_t h_best_fit(const uint64_t *hl, uint32_t nh, 
     return uniform(best == U64_MAX ? nh - 1 : (uint32_t)best);
 }
 
-// index of the hole that contains address o (start <= o < start + size); x receives the hole
+// index of the hole that contains address o (start <= o < start + size); x receives the hole.
+// Searched from the top chunk down: the blocks carved out of a list are those of multi-step
+// variables, which mostly sit high.
 __device__ __forceinline__ uint32_t h_find_hole(const uint64_t *hl, uint32_t nh, uint32_t o, uint64_t &x)
 {
     const int l = lane_id();
-    for (uint32_t base = 0; base < nh; base += WAVE) {
+    for (uint32_t base = (nh - 1) & ~(uint32_t)(WAVE - 1);; base -= WAVE) {
         const uint32_t idx = base + l;
         const uint64_t y = idx < nh ? hl[idx] : 0ull;
         const uint32_t st = (uint32_t)(y >> 32), sz = (uint32_t)y;
@@ -296,6 +298,7 @@ __device__ __forceinline__ uint32_t h_find_hole(const uint64_t *hl, uint32_t nh,
             x = read_lane64(y, j);
             return base + j;
         }
+        if (base == 0) break;
     }
     x = uniform64(hl[nh - 1]);
     return nh - 1;
