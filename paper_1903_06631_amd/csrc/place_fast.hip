@@ -855,21 +855,29 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     // indices not yet written back; wmask remembers (hashed) which lists were stored since
     // the last fence
     uint32_t cur_t = NONE32, cur_base = 0, cnt = 0, wb_from = NONE32, wb_to = 0;
+    // one more changed entry outside that range: a hole shrunk low in the list, while the range
+    // covers what carving changed high up (one range over both would rewrite the whole list)
+    uint32_t wb_one = NONE32;
     uint64_t wmask = 0;
     // per lane, for the one-step variable of this lane's rank: list start, sorted and
     // unsorted entry counts of its step (kept current by the code below)
     uint32_t plb = 0, pns = 0, pnu = 0;
 
     auto writeback = [&](uint32_t a_lane) {
-        if (cur_t != NONE32 && wb_from != NONE32) {
+        if (cur_t != NONE32 && (wb_from != NONE32 || wb_one != NONE32)) {
             uint64_t *Lt = L + cur_base;
             for (uint32_t idx = wb_from + l; idx < wb_to; idx += WAVE) Lt[idx] = hl[idx];
-            if (l == 0) { l_ns[cur_t] = cnt; l_nu[cur_t] = 0; }
+            if (l == 0) {
+                if (wb_one != NONE32 && (wb_one < wb_from || wb_one >= wb_to)) Lt[wb_one] = hl[wb_one];
+                l_ns[cur_t] = cnt;
+                l_nu[cur_t] = 0;
+            }
             wmask |= 1ull << ((cur_t / PW) & 63);
         }
         if (cur_t != NONE32 && a_lane == cur_t) { pns = cnt; pnu = 0; }
         wb_from = NONE32;
         wb_to = 0;
+        wb_one = NONE32;
     };
 
     // pending -> recent, and recent -> main when recent cannot take it (all waves call it)
@@ -1141,15 +1149,23 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         const uint64_t x = uniform64(hl[h]);
                         o = (uint32_t)(x >> 32);
                         lds_sync();
-                        wb_from = min(wb_from, h);
                         if ((uint32_t)x == vs) {         // used up: the hole leaves the list
                             h_delete(hl, cnt, h);
                             --cnt;
+                            wb_from = min(wb_from, h);   // (a lone entry above h moved down: now inside)
                             wb_to = max(wb_to, cnt);
                         } else {
                             if (l == 0) hl[h] = pk(o + vs, (uint32_t)x - vs);
                             lds_sync();
-                            wb_to = max(wb_to, h + 1);
+                            if (h >= wb_from && h < wb_to) {
+                                // inside the range already
+                            } else if (wb_one == NONE32 || wb_one == h) {
+                                wb_one = h;
+                            } else {                     // a second lone entry: widen the range over both
+                                wb_from = min(wb_from, min(h, wb_one));
+                                wb_to = max(wb_to, max(h, wb_one) + 1);
+                                wb_one = NONE32;
+                            }
                         }
                     } else {
                         // list too long for the LDS area: same steps directly in global memory
