@@ -52,6 +52,7 @@ size_t ws_plan(uint32_t n, uint32_t T, uint32_t B)
            + 2 * up((size_t)B * 4) + up((size_t)B * 8)                // kinds, fit policies, seeds
            + 2 * up(bn * 4)                                            // perm, sort scratch
            + up((size_t)B * 8)                                         // footprints
+           + up((size_t)n * 16)                                        // packed variable records
            + up(bn * 8)                                                // offsets of every ordering
            + ws_plan_lists(n, T, B);
 }
@@ -276,6 +277,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint32_t *perm = c.take<uint32_t>(bn);
     uint32_t *tmp = c.take<uint32_t>(bn);
     uint64_t *fps_ws = c.take<uint64_t>(B);
+    uint64_t *vrec = c.take<uint64_t>((size_t)n * 2);
     uint64_t *offs_ws = c.take<uint64_t>(bn);
     // the two placement kernels never both run: their lists share one region
     Carver cw((char *)ws + c.used), cf((char *)ws + c.used);
@@ -317,13 +319,13 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     static_assert(sizeof(lap::PlanHeader) % 8 == 0, "header is cleared in 64-bit words");
     LAP_HIP(lap::launch_fill_u64((uint64_t *)hdr, sizeof(lap::PlanHeader) / 8, 0, st));
     LAP_HIP(lap::launch_fill_u64((uint64_t *)cntd, ((size_t)T + 2) / 2, 0, st));
-    LAP_HIP(lap::launch_plan_prep(n, T, tr->size, tr->alloc, tr->free_, cntd, lstart, hdr, st));
+    LAP_HIP(lap::launch_plan_prep(n, T, tr->size, tr->alloc, tr->free_, cntd, lstart, hdr, vrec, st));
     // per-step entry counts start at zero (cleared as 64-bit words, the regions are padded)
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_ns, ((size_t)B * T + 1) / 2, 0, st));
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_nu, ((size_t)B * T + 1) / 2, 0, st));
     {
         ProfScope p(LAP_K_PLACE, st);
-        LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, fits, any_first, any_best, hdr,
+        LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, fits, any_first, any_best, hdr, vrec,
                                        lstart, f_oe, f_life, f_oe2,
                                        f_life2, f_roe, f_rlife, f_roe2, f_rlife2, f_L, capL, l_ns, l_nu, offs, fps, st));
         LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, fits, hdr, m_off, m_end, m_life, offs,

@@ -31,10 +31,11 @@ hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const 
                             const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
                             bool any_explicit, hipStream_t st);
 hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
-                            const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st);
+                            const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, void *vrec,
+                            hipStream_t st);
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,
-                             bool any_best, PlanHeader *hdr,
+                             bool any_best, PlanHeader *hdr, const void *vrec,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,

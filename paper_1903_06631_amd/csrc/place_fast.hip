@@ -169,6 +169,20 @@ __global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_
     }
 }
 
+// What the placement kernel reads of a variable, in one 16-byte record (one gather per rank
+// instead of three): first step, end of life, size in granules.  Only meaningful on the
+// 32-bit path (size >> shift fits 32 bits there).
+__global__ __launch_bounds__(256) void k_plan_pack(uint32_t n, const uint64_t *__restrict__ size,
+                                                   const uint32_t *__restrict__ alloc,
+                                                   const uint32_t *__restrict__ free_, const PlanHeader *hdr,
+                                                   uint4 *__restrict__ vrec)
+{
+    if (!hdr->fast) return;
+    const uint32_t sh = hdr->shift;
+    for (uint32_t v = blockIdx.x * 256 + threadIdx.x; v < n; v += gridDim.x * 256)
+        vrec[v] = make_uint4(alloc[v], free_[v], (uint32_t)(size[v] >> sh), 0u);
+}
+
 // ---------------------------------------------------------------------------
 // sorted lists of packed blocks (global memory or LDS), one wave
 // ---------------------------------------------------------------------------
@@ -375,6 +389,7 @@ struct FastArgs {
     uint32_t n, T;
     const uint64_t *size;
     const uint32_t *alloc, *free_;
+    const uint4 *vrec;           // [n] (first step, end of life, size in granules, -)
     const uint32_t *perm;        // [B][n]
     const uint32_t *fits;        // [B] 0 = first-fit, 1 = best-fit
     PlanHeader *hdr;
@@ -939,9 +954,10 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         uint32_t v = 0, a = 0, f = 1, s = 0;
         if (in) {
             v = perm[ridx];
-            a = A.alloc[v];
-            f = A.free_[v];
-            s = (uint32_t)(A.size[v] >> sh);
+            const uint4 rec = A.vrec[v];
+            a = rec.x;
+            f = rec.y;
+            s = rec.z;
         }
         const uint64_t im = ballot(in);
         const uint64_t mm = ballot(in && (!mode1 || f - a > 1));
@@ -1230,24 +1246,26 @@ static unsigned long long *g_probe = nullptr;
 extern "C" void lap_debug_set_probe(void *dev) { g_probe = (unsigned long long *)dev; }
 
 hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
-                            const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, hipStream_t st)
+                            const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, void *vrec,
+                            hipStream_t st)
 {
     uint32_t blocks = (n + 255) / 256;
     blocks = blocks > 1024 ? 1024 : blocks;
     hipLaunchKernelGGL(k_plan_prep1, dim3(blocks), dim3(256), 0, st, n, size, alloc, free_, cntd, hdr);
     hipLaunchKernelGGL(k_plan_prep2, dim3(1), dim3(PREP_THREADS), 0, st, n, T, cntd, lstart, hdr);
+    hipLaunchKernelGGL(k_plan_pack, dim3(blocks), dim3(256), 0, st, n, size, alloc, free_, hdr, (uint4 *)vrec);
     return hipGetLastError();
 }
 
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,
-                             bool any_best, PlanHeader *hdr,
+                             bool any_best, PlanHeader *hdr, const void *vrec,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,
                              uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st)
 {
-    FastArgs A{n, T, size, alloc, free_, perm, fits, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, {r_oe, r_oe2}, {r_life, r_life2},
+    FastArgs A{n, T, size, alloc, free_, (const uint4 *)vrec, perm, fits, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, {r_oe, r_oe2}, {r_life, r_life2},
                L, l_ns,
                l_nu, capL,
                offs, fps, g_probe};
