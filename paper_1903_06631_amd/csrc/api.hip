@@ -311,7 +311,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     LAP_HIP(hipMemcpyAsync(seeds, hs.data(), (size_t)B * 8, hipMemcpyHostToDevice, st));
 
     uint64_t *fps = footprints ? footprints : fps_ws;
-    uint64_t *offs = all_offsets ? all_offsets : offs_ws;
+    uint64_t *offs = offs_ws;       // in rank order; the outputs are un-permuted from it
     {
         ProfScope p(LAP_K_SORT, st);
         LAP_HIP(lap::launch_sort_perm(n, B, tr->size, tr->alloc, tr->free_, kinds, seeds, perm, tmp, any_explicit, st));
@@ -331,7 +331,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
         LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, fits, hdr, m_off, m_end, m_life, offs,
                                        fps, st));
     }
-    LAP_HIP(lap::launch_select(n, B, fps, offs, best_footprint, best_ordering, best_offsets, st));
+    LAP_HIP(lap::launch_select(n, B, fps, offs, perm, best_footprint, best_ordering, best_offsets, all_offsets, st));
     return LAP_OK;
 }
 

@@ -45,8 +45,9 @@ hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits,
                              const PlanHeader *hdr, uint64_t *m_off,
                              uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st);
-hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs, uint64_t *best_fp,
-                         uint32_t *best_idx, uint64_t *best_offsets, hipStream_t st);
+hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs_rank, const uint32_t *perm,
+                         uint64_t *best_fp, uint32_t *best_idx, uint64_t *best_offsets, uint64_t *all_offsets,
+                         hipStream_t st);
 
 hipError_t launch_swap_prefix(uint32_t T, const uint64_t *load, const uint64_t *step_ns, uint64_t *C, uint64_t *S,
                               uint64_t *PM, uint64_t *SM, uint64_t *peak, uint32_t *t_peak, hipStream_t st);

@@ -401,7 +401,7 @@ struct FastArgs {
     uint64_t *L;                 // [B][capL]   per-step lists, packed blocks
     uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts
     uint64_t capL;
-    uint64_t *offs;              // [B][n]
+    uint64_t *offs;              // [B][n] in rank order
     uint64_t *fps;               // [B]
     unsigned long long *probe;   // optional per-wave cycle counters (instrumented builds only)
 };
@@ -973,7 +973,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 PROBE_T(t2);
                 if (cur_t != NONE32) { writeback(one_step ? a : NONE32); cur_t = NONE32; }
                 __syncthreads();
-                const uint32_t vv = __shfl(v, (int)p, WAVE), va = __shfl(a, (int)p, WAVE);
+                const uint32_t va = __shfl(a, (int)p, WAVE);
                 const uint32_t vf = __shfl(f, (int)p, WAVE), vs = __shfl(s, (int)p, WAVE);
                 // pending stays unsorted and is checked directly, unless many of its entries come
                 // from ALL queries: those stack on each other and would be climbed one by one
@@ -1072,7 +1072,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 const uint32_t en = o + vs;
                 fp = max(fp, en);
                 if (threadIdx.x == 0) {
-                    offs[vv] = (uint64_t)o << sh;
+                    offs[r0 + p] = (uint64_t)o << sh;        // offsets are kept in rank order
                     if (multi_left > 1) {               // someone will still query ALL
                         p_oe[np] = pk(o, en);
                         p_life[np] = Life<LT>::mk(va, vf);
@@ -1217,7 +1217,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     fp = max(fp, o + vs);
                     if (l == j) res = o;
                 }
-                if (my_rank) offs[v] = (uint64_t)res << sh;
+                if (my_rank) offs[ridx] = (uint64_t)res << sh;
                 PROBE_ACC(3, t5);
                 p = q;
             }

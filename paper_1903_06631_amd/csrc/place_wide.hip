@@ -222,7 +222,7 @@ __global__ __launch_bounds__(64) void k_place_wide(uint32_t n, const uint64_t *_
             o = e;
         }
 
-        if (l == 0) offs[v] = o;
+        if (l == 0) offs[r] = o;                 // by rank: the result arrays are un-permuted afterwards
         fp = umax64(fp, o + s);
 
         const uint32_t p = count_below(r_off, nr, o);
@@ -264,13 +264,30 @@ __global__ __launch_bounds__(256) void k_select(uint32_t B, const uint64_t *__re
     if (threadIdx.x == 0) { *best_fp = sv[0]; *best_idx = si[0]; }
 }
 
-__global__ __launch_bounds__(256) void k_copy_best(uint32_t n, const uint64_t *__restrict__ offs_all,
+// The placement kernels leave their offsets in rank order (entry r belongs to variable
+// perm[r]): stores of neighbouring ranks fall into the same cache lines.  The results asked for
+// are put in variable order here: the best ordering's, and all B when the caller wants them.
+__global__ __launch_bounds__(256) void k_copy_best(uint32_t n, const uint64_t *__restrict__ offs_rank,
+                                                   const uint32_t *__restrict__ perm_all,
                                                    const uint32_t *__restrict__ best_idx,
                                                    uint64_t *__restrict__ best_offsets)
 {
-    const uint64_t *src = offs_all + (size_t)(*best_idx) * n;
+    const uint64_t *src = offs_rank + (size_t)(*best_idx) * n;
+    const uint32_t *perm = perm_all + (size_t)(*best_idx) * n;
     const uint32_t stride = gridDim.x * blockDim.x;
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) best_offsets[i] = src[i];
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) best_offsets[perm[i]] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_unpermute(uint32_t n, const uint64_t *__restrict__ offs_rank,
+                                                   const uint32_t *__restrict__ perm_all,
+                                                   uint64_t *__restrict__ all_offsets)
+{
+    const size_t b = blockIdx.y;
+    const uint64_t *src = offs_rank + b * n;
+    const uint32_t *perm = perm_all + b * n;
+    uint64_t *dst = all_offsets + b * n;
+    const uint32_t stride = gridDim.x * blockDim.x;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[perm[i]] = src[i];
 }
 
 hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
@@ -282,13 +299,18 @@ hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const
     return hipGetLastError();
 }
 
-hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs, uint64_t *best_fp,
-                         uint32_t *best_idx, uint64_t *best_offsets, hipStream_t st)
+hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs_rank, const uint32_t *perm,
+                         uint64_t *best_fp, uint32_t *best_idx, uint64_t *best_offsets, uint64_t *all_offsets,
+                         hipStream_t st)
 {
     hipLaunchKernelGGL(k_select, dim3(1), dim3(256), 0, st, B, fps, best_fp, best_idx);
     uint32_t blocks = (n + 255) / 256;
     blocks = blocks > 1024 ? 1024 : blocks;
-    hipLaunchKernelGGL(k_copy_best, dim3(blocks), dim3(256), 0, st, n, offs, best_idx, best_offsets);
+    hipLaunchKernelGGL(k_copy_best, dim3(blocks), dim3(256), 0, st, n, offs_rank, perm, best_idx, best_offsets);
+    if (all_offsets) {
+        blocks = blocks > 64 ? 64 : blocks;
+        hipLaunchKernelGGL(k_unpermute, dim3(blocks, B), dim3(256), 0, st, n, offs_rank, perm, all_offsets);
+    }
     return hipGetLastError();
 }
 
