@@ -353,10 +353,46 @@ __device__ __forceinline__ void h_delete(uint64_t *hl, uint32_t n, uint32_t p)
 
 // Remove the block [o, en) from the nh free ranges in hl: it lies inside exactly one hole.
 // Returns the number of holes afterwards; [lo, hi) is extended to the entries that changed.
+// The top 64 holes are looked at first (multi-step blocks sit high); if the hole is among
+// them, everything that has to move is already in registers: one LDS read in all.
 __device__ __forceinline__ uint32_t h_carve(uint64_t *hl, uint32_t nh, uint32_t o, uint32_t en, uint32_t &lo,
                                             uint32_t &hi)
 {
     const int l = lane_id();
+    {
+        const uint32_t base = (nh - 1) & ~(uint32_t)(WAVE - 1);
+        const uint32_t idx = base + l;
+        const uint64_t y = idx < nh ? hl[idx] : 0ull;
+        const uint32_t yst = (uint32_t)(y >> 32), ysz = (uint32_t)y;
+        const uint64_t m = ballot(yst <= o && o - yst < ysz);
+        if (m) {
+            const int j = __ffsll((unsigned long long)m) - 1;
+            const uint64_t x = read_lane64(y, j);
+            const uint32_t h = base + j, st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
+            lo = min(lo, h);
+            uint32_t left;
+            if (o == st && en == hend) {            // used up: the holes above move down
+                if (idx > h && idx < nh) hl[idx - 1] = y;
+                hi = max(hi, nh - 1);
+                left = nh - 1;
+            } else if (o == st) {                   // shrinks from below
+                if (l == j) hl[h] = pk(en, hend - en);
+                hi = max(hi, h + 1);
+                left = nh;
+            } else if (en == hend) {                // shrinks from above
+                if (l == j) hl[h] = pk(st, o - st);
+                hi = max(hi, h + 1);
+                left = nh;
+            } else {                                // split: the holes above move up
+                if (idx > h && idx < nh) hl[idx + 1] = y;
+                if (l == j) { hl[h] = pk(st, o - st); hl[h + 1] = pk(en, hend - en); }
+                hi = max(hi, nh + 1);
+                left = nh + 1;
+            }
+            lds_sync();
+            return left;
+        }
+    }
     uint64_t x;
     const uint32_t h = h_find_hole(hl, nh, o, x);
     const uint32_t st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
