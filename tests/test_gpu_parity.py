@@ -113,6 +113,7 @@ def test_plan_pool_random(lap, oracle_mod, seed, n, T):
     (6, 5000, 3, 0.45, 3),        # > 1000 multi-step blocks per step: hole lists too long for registers
     (7, 3000, 9, 0.50, 3),        # many splits: multi-step blocks land inside holes
     (8, 30000, 70000, 0.98, 50),  # more than 65535 steps: 64-bit lifetime words with per-step lists
+    (9, 30000, 3000, 0.999, 3000),  # lifetimes of thousands of steps: more steps per thread than the kernel keeps notes for
 ])
 def test_plan_pool_per_step_lists(lap, oracle_mod, seed, n, T, frac, max_life):
     """Traces whose lifetimes sum to at most 6N steps take the per-step-list path."""
@@ -219,7 +220,8 @@ def test_best_fit_random(lap, oracle_mod, seed, n, T):
 
 @pytest.mark.parametrize("seed,n,T,frac,max_life", [
     (0, 3000, 40, 0.9, 6), (1, 8000, 100, 0.95, 30), (2, 20000, 64, 0.98, 64), (3, 6000, 500, 0.8, 4),
-    (4, 5000, 12, 0.99, 12), (5, 9000, 70000, 0.9, 3)])
+    (4, 5000, 12, 0.99, 12), (5, 9000, 70000, 0.9, 3),
+    (6, 30000, 3000, 0.999, 3000)])      # lifetimes beyond the steps a thread keeps notes for
 def test_best_fit_per_step_lists(lap, oracle_mod, seed, n, T, frac, max_life):
     """mostly one-step variables (hole lists in use), a few long-lived ones that walk the holes"""
     tr = random_trace(1300 + seed, n, T, max_life=max_life, one_step_frac=frac)
