@@ -658,7 +658,8 @@ __device__ __forceinline__ uint32_t coop_sweep(const uint64_t *oe, const LT *lif
 // thread's steps.  Only the sorted part of a list (the holes) is read: blocks still waiting
 // in a list's tail belong to multi-step variables, which the ALL list covers.  The topmost
 // hole of every list is unbounded, so every search ends.
-// Passes over unchanged lists with a rising o (first = false after the first of them) reuse
+// Passes over unchanged lists with a rising o (valid0 / valid_rest say whether the thread's first
+// step / its other steps have been asked before for this variable) reuse
 // what the last search of a step found, kept for the thread's first FIT_MEMO steps in the
 // wave's LDS slice `memo` (5 words per step, lane-interleaved; the slice holds no hole list
 // while a multi-step variable is being placed): its answer, the end of the hole it lies in,
@@ -671,7 +672,7 @@ constexpr uint32_t FIT_WORDS = 5;   // per step: answer, end of its hole, its in
 static_assert(FIT_MEMO * FIT_WORDS * WAVE * sizeof(uint32_t) <= LH * sizeof(uint64_t), "the memo must fit the wave's list slice");
 __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ L, const uint32_t *__restrict__ lstart,
                                                    const uint32_t *l_ns, uint32_t a, uint32_t f, uint32_t o,
-                                                   uint32_t s, bool first, uint32_t *memo)
+                                                   uint32_t s, bool &valid0, bool &valid_rest, uint32_t *memo)
 {
     // oq: the offset asked for, need = oq + s; from: holes below this index are known to end
     // below need; gallop: the answer is expected close above `from` (doubling steps first, then
@@ -720,10 +721,15 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
     const uint32_t rounds = (f - a + PW * WAVE - 1) / (PW * WAVE);
     // ... and the wave goes over its own steps again until they all accept its answer: an offset
     // that fails among 64 * rounds steps is dropped without asking the other three quarters.
+    // A thread's steps are neighbours (step a + tid * rounds + k in round k), so round 0 alone
+    // is a sample of the whole lifetime, every rounds-th step: the wave first settles on an
+    // offset among those (a lower bound that is cheap to raise, and for a small variable that
+    // lives long it takes dozens of sweeps to raise it), then among all its steps.
+    for (uint32_t kmax = rounds > 1 ? 1 : rounds; ; kmax = rounds) {
     for (;;) {
     const uint32_t sweep_from = best;
-    for (uint32_t k = 0; k < rounds; ++k) {
-        const uint32_t t = a + threadIdx.x + k * PW * WAVE;
+    for (uint32_t k = 0; k < kmax; ++k) {
+        const uint32_t t = a + threadIdx.x * rounds + k;
         uint32_t at = best;
         if (t < f) {
             const uint32_t oq = best, need = oq + s;
@@ -731,7 +737,7 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
             uint32_t *mk = mm + k * FIT_WORDS * WAVE;
             uint32_t from_idx = 0, base, top;
             bool done = false;
-            if (kept && !first) {
+            if (kept && (k == 0 ? valid0 : valid_rest)) {
                 const uint32_t m_at = mk[0], m_end = mk[WAVE], m_lo = mk[2 * WAVE];
                 if (m_at >= oq) { at = m_at; done = true; }
                 else if (m_end >= need) done = true;        // fits at oq itself
@@ -750,8 +756,11 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
         }
         best = wave_reduce_max32(at);
     }
+    valid0 = true;                          // the notes of the steps just asked now hold
+    if (kmax == rounds) valid_rest = true;
     if (best == sweep_from) break;
-    first = false;
+    }
+    if (kmax == rounds) break;
     }
     return best;
 }
@@ -767,8 +776,10 @@ __device__ __forceinline__ uint32_t steps_extent_pass(const uint64_t *__restrict
 {
     uint32_t e = NONE32;
     const uint32_t *mm = memo + lane_id();
-    uint32_t k = 0;
-    for (uint32_t t = a + threadIdx.x; t < f; t += PW * WAVE, ++k) {
+    const uint32_t rounds = (f - a + PW * WAVE - 1) / (PW * WAVE);     // same steps per thread as steps_fit_pass
+    for (uint32_t k = 0; k < rounds; ++k) {
+        const uint32_t t = a + threadIdx.x * rounds + k;
+        if (t >= f) break;
         if (k < FIT_MEMO) {
             e = min(e, mm[(k * FIT_WORDS + 1) * WAVE]);
             continue;
@@ -1022,7 +1033,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 uint32_t cm = 0, cr = 0;
                 // no hole-list pass yet for this variable (the lists do not change and the candidate
                 // only rises while it is being placed, so later passes may build on earlier ones)
-                bool first = true;
+                bool valid0 = false, valid_rest = false;   // (per thread: of its first step, of its other steps)
                 // lowest offset >= `from` that is free of every neighbour: the sorted lists, the
                 // pending entries and (with per-step lists) the hole lists are asked in turn until
                 // none of them moves the candidate
@@ -1050,8 +1061,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         // stand for them.  Passes repeat until no step moves the candidate.
                         uint32_t os = o2;
                         for (;;) {
-                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs, first, (uint32_t *)hl);
-                            first = false;
+                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs, valid0, valid_rest, (uint32_t *)hl);
                             c = wave_reduce_max32(c);
                             if (l == 0) s_sf[flip][wave] = c;
                             __syncthreads();
