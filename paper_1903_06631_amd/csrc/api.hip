@@ -34,13 +34,16 @@ inline uint32_t table_levels(uint32_t T)
 
 size_t ws_load(uint32_t T) { return up(((size_t)T + 1) * 8); }
 
+// entries of the per-step lists of one ordering: PLAN_CL per variable, a whole number of 128-byte lines
+inline uint64_t plan_list_cap(uint32_t n) { return ((uint64_t)n * lap::PLAN_CL + 15) & ~15ull; }
+
 // block lists of the placement kernels: the 64-bit path needs off/end/life per ordering, the
 // packed 32-bit path a packed main list with lifetimes, the per-step lists and their counters
 size_t ws_plan_lists(uint32_t n, uint32_t T, uint32_t B)
 {
     const size_t bn = (size_t)B * n;
     const size_t wide = 3 * up(bn * 8);
-    const size_t fast = 4 * up(bn * 8) + 4 * up((size_t)B * lap::PLAN_REC * 8) + up(bn * lap::PLAN_CL * 8) +
+    const size_t fast = 4 * up(bn * 8) + 4 * up((size_t)B * lap::PLAN_REC * 8) + up((size_t)B * plan_list_cap(n) * 8) +
                         2 * up((size_t)B * T * 4);
     return wide > fast ? wide : fast;
 }
@@ -292,7 +295,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint64_t *f_rlife = cf.take<uint64_t>((size_t)B * lap::PLAN_REC);
     uint64_t *f_roe2 = cf.take<uint64_t>((size_t)B * lap::PLAN_REC);
     uint64_t *f_rlife2 = cf.take<uint64_t>((size_t)B * lap::PLAN_REC);
-    const uint64_t capL = (uint64_t)n * lap::PLAN_CL;
+    const uint64_t capL = plan_list_cap(n);
     uint64_t *f_L = cf.take<uint64_t>((size_t)B * capL);
     uint32_t *l_ns = cf.take<uint32_t>((size_t)B * T);
     uint32_t *l_nu = cf.take<uint32_t>((size_t)B * T);

@@ -152,7 +152,9 @@ __global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_
         const bool in = t < T;
         const uint64_t d = in ? (uint64_t)(int64_t)(int32_t)cntd[t] : 0;     // signed delta
         const uint64_t live = c1 + prep_block_scan(d, wtmp, tot); c1 += tot;
-        const uint64_t lv = in ? live + 1 : 0;                // room for the holes: blocks + 1
+        // room for the holes: blocks + 1, rounded up to 16 entries so that every list starts on a
+        // 128-byte line (a fetch of n entries then touches ceil(n / 16) lines, not one more)
+        const uint64_t lv = in ? ((live + 1 + 15) & ~15ull) : 0;
         const uint64_t incl = c2 + prep_block_scan(lv, wtmp, tot);
         if (in) lstart[t] = (uint32_t)(incl - lv);
         c2 += tot;
