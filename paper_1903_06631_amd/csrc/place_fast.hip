@@ -981,6 +981,14 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
 #endif
     uint32_t prio_now = 1;
     __builtin_amdgcn_s_setprio(1);
+    // The variables of a window come through two dependent loads (rank -> variable -> record).
+    // They are fetched ahead: while a window is worked on, the records of the next one and the
+    // variable numbers of the one after are on their way, so a window starts with its records
+    // in registers.
+    uint4 rec_next = make_uint4(0u, 1u, 0u, 0u);
+    uint32_t v_next = 0;
+    if ((uint32_t)l < n) rec_next = A.vrec[perm[l]];
+    if ((uint32_t)l + WAVE < n) v_next = perm[l + WAVE];
     for (uint32_t r0 = 0; r0 < n; r0 += WAVE) {
         if (r0 && (r0 & (PACE_RANKS - 1)) == 0) {
             if (threadIdx.x == 0) {
@@ -1000,14 +1008,14 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         }
         const uint32_t ridx = r0 + l;
         const bool in = ridx < n;
-        uint32_t v = 0, a = 0, f = 1, s = 0;
+        uint32_t a = 0, f = 1, s = 0;
         if (in) {
-            v = perm[ridx];
-            const uint4 rec = A.vrec[v];
-            a = rec.x;
-            f = rec.y;
-            s = rec.z;
+            a = rec_next.x;
+            f = rec_next.y;
+            s = rec_next.z;
         }
+        if (ridx + WAVE < n) rec_next = A.vrec[v_next];
+        if (ridx + 2 * WAVE < n) v_next = perm[ridx + 2 * WAVE];
         const uint64_t im = ballot(in);
         const uint64_t mm = ballot(in && (!mode1 || f - a > 1));
         const uint32_t wn = (uint32_t)__popcll(im);
