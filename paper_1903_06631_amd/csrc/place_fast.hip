@@ -1182,8 +1182,25 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                             if (pf_t == t) {
                                 lds_from_regs<0>(hl, pf, tot, l);
                             } else {
+                                // not fetched ahead (the first of a run, mostly): all its chunks are
+                                // asked for before the first is waited for
                                 const uint64_t *Lt = L + base;
-                                for (uint32_t idx = l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
+                                uint32_t done = 0;
+                                if (tot <= 4 * WAVE) {
+                                    uint64_t y[4];
+#pragma unroll
+                                    for (int c = 0; c < 4; ++c) {
+                                        const uint32_t idx = c * WAVE + l;
+                                        y[c] = idx < tot ? Lt[idx] : 0ull;
+                                    }
+#pragma unroll
+                                    for (int c = 0; c < 4; ++c) {
+                                        const uint32_t idx = c * WAVE + l;
+                                        if (idx < tot) hl[idx] = y[c];
+                                    }
+                                    done = tot;
+                                }
+                                for (uint32_t idx = done + l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
                             }
                             lds_sync();
                             PROBE_CNT(6, tot - ns);
