@@ -15,8 +15,8 @@
 //          64 entries per wave step -- blocks that do not overlap the variable
 //          in time are masked, a wave prefix-max of the remaining ends gives the
 //          highest occupied address so far, and the first entry whose offset
-//          leaves a hole of at least `size` above it ends the sweep ("the first
-//          hole that the variable can fit in").
+//          leaves a hole of at least `size` above it ends the sweep (first-fit,
+//          Section III-C: the lowest hole that is large enough).
 //   L[t]   (only when the sum of all lifetimes, plus one per step, is at most
 //          CL*N) the FREE address ranges ("holes") at step t, sorted by start,
 //          packed (start << 32 | size), the last one reaching to 2^32-1;
@@ -441,7 +441,6 @@ struct FastArgs {
     uint64_t capL;
     uint64_t *offs;              // [B][n] in rank order
     uint64_t *fps;               // [B]
-    unsigned long long *probe;   // optional per-wave cycle counters (instrumented builds only)
 };
 
 constexpr int COOP_U = 4;                    // chunks per wave in one cooperative round
@@ -968,17 +967,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         __syncthreads();
     };
 
-#ifdef LAP_PROBE
-    uint64_t pc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#define PROBE_T(v) const uint64_t v = clock64()
-#define PROBE_ACC(k, v) pc[k] += clock64() - v
-#define PROBE_CNT(k, x) pc[k] += (x)
-    const uint64_t t_begin = clock64();
-#else
-#define PROBE_T(v)
-#define PROBE_ACC(k, v)
-#define PROBE_CNT(k, x)
-#endif
     uint32_t prio_now = 1;
     __builtin_amdgcn_s_setprio(1);
     // The variables of a window come through two dependent loads (rank -> variable -> record).
@@ -1027,7 +1015,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         while (p < wn) {
             if ((mm >> p) & 1ull) {
                 // ---- a variable that queries ALL: every wave sweeps, wave 0 keeps recent ----
-                PROBE_T(t2);
                 if (cur_t != NONE32) { writeback(one_step ? a : NONE32); cur_t = NONE32; }
                 __syncthreads();
                 const uint32_t va = __shfl(a, (int)p, WAVE);
@@ -1039,7 +1026,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     flush(np);
                     np = 0;
                 }
-                PROBE_ACC(0, t2); PROBE_T(t3);
                 uint32_t cm = 0, cr = 0;
                 // no hole-list pass yet for this variable (the lists do not change and the candidate
                 // only rises while it is being placed, so later passes may build on earlier ones)
@@ -1124,7 +1110,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         from = e;
                     }
                 }
-                PROBE_ACC(1, t3); PROBE_T(t4);
                 const uint32_t en = o + vs;
                 fp = max(fp, en);
                 if (threadIdx.x == 0) {
@@ -1143,7 +1128,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         l_nu[t] = l_nu[t] + 1;
                     }
                 }
-                PROBE_ACC(2, t4);
                 --multi_left;
                 __syncthreads();
                 // the tails of the steps it covers grew: refresh the counts of the ranks to come
@@ -1151,7 +1135,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 ++p;
             } else {
                 // ---- a run of one-step variables: each wave takes the steps it owns --------
-                PROBE_T(t5);
                 const uint64_t rest = (~mm & im) >> p;
                 const uint32_t run = (~rest == 0ull) ? 64u : (uint32_t)(__ffsll((unsigned long long)~rest) - 1);
                 const uint32_t q = p + run;
@@ -1171,7 +1154,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     mine &= mine - 1;
                     const uint32_t t = read_lane(a, j), vs = read_lane(s, j);
                     uint32_t o;
-                    if (t != cur_t) PROBE_CNT(5, 1);
                     if (t != cur_t) {
                         writeback(one_step ? a : NONE32);
                         cur_t = NONE32;
@@ -1203,7 +1185,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                                 for (uint32_t idx = done + l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
                             }
                             lds_sync();
-                            PROBE_CNT(6, tot - ns);
                             // carve the multi-step blocks that arrived since out of the holes.  The tail
                             // is taken into registers 64 entries at a time (lane i holds entry i); the
                             // holes may then grow over its place: k blocks add at most k holes, and
@@ -1291,7 +1272,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     if (l == j) res = o;
                 }
                 if (my_rank) offs[ridx] = (uint64_t)res << sh;
-                PROBE_ACC(3, t5);
                 p = q;
             }
         }
@@ -1301,10 +1281,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         // apart until the next multi-step variable brings them together.
         wave_fence();
     }
-#ifdef LAP_PROBE
-    pc[7] = clock64() - t_begin;
-    if (l == 0 && A.probe) for (int k = 0; k < 8; ++k) A.probe[((size_t)b * PW + wave) * 8 + k] = pc[k];
-#endif
     if (l == 0) s_fp[wave] = fp;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -1313,10 +1289,6 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         A.fps[b] = (uint64_t)m << sh;
     }
 }
-
-static unsigned long long *g_probe = nullptr;
-// instrumented builds: device buffer of B * PW * 8 counters, or null
-extern "C" void lap_debug_set_probe(void *dev) { g_probe = (unsigned long long *)dev; }
 
 hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
                             const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, void *vrec,
@@ -1341,7 +1313,7 @@ hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t 
     FastArgs A{n, T, size, alloc, free_, (const uint4 *)vrec, perm, fits, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, {r_oe, r_oe2}, {r_life, r_life2},
                L, l_ns,
                l_nu, capL,
-               offs, fps, g_probe};
+               offs, fps};
     // each instantiation leaves the orderings of the other policy alone
     if (T <= 0xFFFFu) {
         if (any_first) hipLaunchKernelGGL((k_place_fast<uint32_t, false>), dim3(B), dim3(PW * WAVE), 0, st, A);

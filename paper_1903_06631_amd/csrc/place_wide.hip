@@ -5,8 +5,8 @@
 // One wave (one 64-thread workgroup) per ordering.  Variables are taken in
 // the ordering's rank order; each gets the lowest offset at which its block
 // does not meet the block of any already-placed variable whose lifetime
-// overlaps its own ("the first hole that the variable can fit in", else the
-// pool is extended).  Best-fit walks on from hole to hole (next_overlap gives a
+// overlaps its own (first-fit: the lowest hole that is large enough, else
+// above the highest neighbour, Section III-C).  Best-fit walks on from hole to hole (next_overlap gives a
 // hole's end) and keeps the smallest one that fits.
 //
 // Data structure per ordering: the placed blocks kept SORTED BY OFFSET, as
