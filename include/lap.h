@@ -40,8 +40,11 @@
  * Memory and ownership
  *   - Every pointer inside lap_trace and every output / workspace pointer is
  *     a DEVICE pointer owned by the caller.  The library never allocates or
- *     frees device memory.  The lap_trace struct itself and the lap_ordering
- *     array are HOST memory and are read before the call returns.
+ *     frees device memory.  The lap_trace struct itself and every array marked
+ *     "host" (orderings, score kinds, limits, weights, prefix lengths) are HOST
+ *     memory; they are read before the call returns and reach the device inside
+ *     kernel arguments, so the caller may reuse them at once and no call waits
+ *     for such a copy.
  *   - Work is enqueued on the given HIP stream (a hipStream_t passed as
  *     void*; NULL = the default stream) and the call returns without waiting.
  *     Outputs, including the scalar ones, are valid once the stream has been

@@ -300,18 +300,16 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint32_t *l_ns = cf.take<uint32_t>((size_t)B * T);
     uint32_t *l_nu = cf.take<uint32_t>((size_t)B * T);
 
-    // The descriptors are split into two arrays and copied from pageable host memory: the
-    // runtime stages such a copy before it returns.  The staging vectors live for the
-    // thread's lifetime all the same.
-    static thread_local std::vector<uint32_t> hk, hf;
-    static thread_local std::vector<uint64_t> hs;
-    hk.resize(B);
-    hf.resize(B);
-    hs.resize(B);
-    for (uint32_t b = 0; b < B; ++b) { hk[b] = ords[b].kind; hf[b] = ords[b].fit; hs[b] = ords[b].seed; }
-    LAP_HIP(hipMemcpyAsync(kinds, hk.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
-    LAP_HIP(hipMemcpyAsync(fits, hf.data(), (size_t)B * 4, hipMemcpyHostToDevice, st));
-    LAP_HIP(hipMemcpyAsync(seeds, hs.data(), (size_t)B * 8, hipMemcpyHostToDevice, st));
+    // The descriptors are split into three arrays; they reach the device inside kernel arguments,
+    // so nothing on the host has to outlive this call and nothing waits.
+    {
+        std::vector<uint32_t> hk(B), hf(B);
+        std::vector<uint64_t> hs(B);
+        for (uint32_t b = 0; b < B; ++b) { hk[b] = ords[b].kind; hf[b] = ords[b].fit; hs[b] = ords[b].seed; }
+        LAP_HIP(lap::launch_put_words(kinds, hk.data(), B, st));
+        LAP_HIP(lap::launch_put_words(fits, hf.data(), B, st));
+        LAP_HIP(lap::launch_put_words(seeds, hs.data(), (size_t)B * 2, st));
+    }
 
     uint64_t *fps = footprints ? footprints : fps_ws;
     uint64_t *offs = offs_ws;       // in rank order; the outputs are un-permuted from it
@@ -433,12 +431,8 @@ int lap_select_swaps(const lap_trace *tr, double link_GBps, uint64_t min_bytes, 
     uint64_t *l_cur = c.take<uint64_t>(0);
     c.used += (size_t)K * up((size_t)T * 8);
 
-    static thread_local std::vector<uint32_t> hk;
-    static thread_local std::vector<uint64_t> hl;
-    hk.assign(score_kinds, score_kinds + K);
-    hl.assign(limits, limits + L);
-    LAP_HIP(hipMemcpyAsync(d_kinds, hk.data(), (size_t)K * 4, hipMemcpyHostToDevice, st));
-    if (L) LAP_HIP(hipMemcpyAsync(d_limits, hl.data(), (size_t)L * 8, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_put_words(d_kinds, score_kinds, K, st));
+    if (L) LAP_HIP(lap::launch_put_words(d_limits, limits, (size_t)L * 2, st));
 
     if (!load) {
         rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
@@ -537,10 +531,7 @@ int lap_evaluate_weights(const lap_trace *tr, double link_GBps, uint64_t min_byt
     uint64_t *total_ns = c.take<uint64_t>(W);
     uint64_t *peak_res = c.take<uint64_t>(W);
 
-    static thread_local std::vector<uint32_t> hk;
-    static thread_local std::vector<double> hw;
-    hk.assign(W, (uint32_t)LAP_PS_CUSTOM);
-    hw.assign(weights, weights + 4 * (size_t)W);
+    const std::vector<uint32_t> hk(W, (uint32_t)LAP_PS_CUSTOM);
     if (!load) {
         rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
         if (rc) return rc;
@@ -565,21 +556,21 @@ int lap_evaluate_weights(const lap_trace *tr, double link_GBps, uint64_t min_byt
     a.peak_after = peak_after; a.load_min = load_min;
     a.custom = nullptr; a.pick_wdoa = swdoa;
     // 1. the SWDOA walk, once: the value every candidate is picked at
-    static const uint32_t h_swdoa = LAP_PS_SWDOA;
-    LAP_HIP(hipMemcpyAsync(d_kinds, &h_swdoa, 4, hipMemcpyHostToDevice, st));
+    const uint32_t h_swdoa = LAP_PS_SWDOA;
+    LAP_HIP(lap::launch_put_words(d_kinds, &h_swdoa, 1, st));
     LAP_HIP(lap::launch_select_swaps(a, true, st));
     // 2. the aggregated score of every weight vector, 3. its walk down to the limit
-    LAP_HIP(hipMemcpyAsync(d_weights, hw.data(), (size_t)W * 32, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_put_words(d_weights, weights, (size_t)W * 8, st));
     LAP_HIP(lap::launch_weighted_scores(n, W, d_weights, aoa, doa, wdoa, swdoa, bo, st));
-    LAP_HIP(hipMemcpyAsync(d_kinds, hk.data(), (size_t)W * 4, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_put_words(d_kinds, hk.data(), W, st));
     a.K = W; a.L = 1; a.custom = bo; a.pick_wdoa = nullptr;
     {
         ProfScope p(LAP_K_SELECT, st);
         LAP_HIP(lap::launch_select_swaps(a, false, st));
     }
     // 4. every selection replayed under the limit, 5. the vector that loses the least time
-    static const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
-    LAP_HIP(hipMemcpyAsync(s_kind, &h_kind, 4, hipMemcpyHostToDevice, st));
+    const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
+    LAP_HIP(lap::launch_put_words(s_kind, &h_kind, 1, st));
     LAP_HIP(lap::launch_fill_u64(s_seed, 1, 0, st));
     const uint32_t *step_lo = tr->gap_lo ? tr->gap_lo : tr->alloc;
     const uint32_t *step_hi = tr->gap_hi ? tr->gap_hi : tr->free_;
@@ -639,8 +630,8 @@ int lap_schedule_swaps(const lap_trace *tr, double link_GBps, const uint64_t *lo
     LAP_HIP(lap::launch_swap_prefix(T, load, tr->step_ns, C, S, PM, SM, peak, t_peak, st));
     // all variables by (first access, index) and by (next access, index): the ascending-step sort of
     // the placement orders, fed with the access steps
-    static const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
-    LAP_HIP(hipMemcpyAsync(kinds, &h_kind, 4, hipMemcpyHostToDevice, st));
+    const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
+    LAP_HIP(lap::launch_put_words(kinds, &h_kind, 1, st));
     LAP_HIP(lap::launch_fill_u64(seeds, 1, 0, st));
     const uint32_t *step_lo = tr->gap_lo ? tr->gap_lo : tr->alloc;
     const uint32_t *step_hi = tr->gap_hi ? tr->gap_hi : tr->free_;
@@ -702,18 +693,14 @@ int lap_simulate_swaps(const lap_trace *tr, double link_GBps, const uint32_t *sw
     uint8_t *out_done = c.take<uint8_t>(0);
     c.used += (size_t)Q * up((size_t)n);
 
-    static thread_local std::vector<uint32_t> hp;
-    static thread_local std::vector<uint64_t> hl;
-    hp.assign(prefix_len, prefix_len + Q);
-    hl.assign(limits, limits + Q);
-    LAP_HIP(hipMemcpyAsync(d_prefix, hp.data(), (size_t)Q * 4, hipMemcpyHostToDevice, st));
-    LAP_HIP(hipMemcpyAsync(d_limits, hl.data(), (size_t)Q * 8, hipMemcpyHostToDevice, st));
+    LAP_HIP(lap::launch_put_words(d_prefix, prefix_len, Q, st));
+    LAP_HIP(lap::launch_put_words(d_limits, limits, (size_t)Q * 2, st));
     // the step start times come from the same prefix kernel as the scores (it needs a load curve)
     rc = load_profile_impl(tr, load_ws, peak, t_peak, delta, st);
     if (rc) return rc;
     LAP_HIP(lap::launch_swap_prefix(T, load_ws, tr->step_ns, C, S, PM, SM, peak, t_peak, st));
-    static const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
-    LAP_HIP(hipMemcpyAsync(kinds, &h_kind, 4, hipMemcpyHostToDevice, st));
+    const uint32_t h_kind = LAP_ORD_ALLOC_ASC;
+    LAP_HIP(lap::launch_put_words(kinds, &h_kind, 1, st));
     LAP_HIP(lap::launch_fill_u64(seeds, 1, 0, st));
     const uint32_t *step_lo = tr->gap_lo ? tr->gap_lo : tr->alloc;
     const uint32_t *step_hi = tr->gap_hi ? tr->gap_hi : tr->free_;

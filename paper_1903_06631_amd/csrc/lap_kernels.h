@@ -19,6 +19,9 @@ struct PlanHeader {
 constexpr uint32_t PLAN_CL = 6;
 
 hipError_t launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st);
+// copies n_words 32-bit words of HOST memory to the device through kernel arguments (the host
+// array is read before the call returns; nothing waits)
+hipError_t launch_put_words(void *dst, const void *host_src, size_t n_words, hipStream_t st);
 hipError_t launch_delta(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                         uint64_t *delta, hipStream_t st);
 hipError_t launch_scan_peak(uint32_t T, uint64_t *delta, uint64_t *load, uint64_t *peak, uint32_t *t_peak,

@@ -6,6 +6,8 @@
 // order of events inside one step does not affect the per-step load).  A
 // prefix sum over the T bins gives load[t]; the same pass takes the maximum
 // and the earliest step that reaches it.
+#include <string.h>
+
 #include "lap_dev.h"
 #include "lap_kernels.h"
 
@@ -16,6 +18,16 @@ __global__ void k_fill_u64(uint64_t *p, size_t n, uint64_t v)
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) p[i] = v;
+}
+
+// A few KB of host values travel to the device inside the kernel arguments: the runtime copies
+// the arguments when the launch is enqueued, so the host array may change or vanish as soon as
+// the launch call returns, nothing waits, and the launch can be captured in a graph.
+constexpr uint32_t PUT_WORDS = 448;             // 32-bit words per launch (1792 B of the 4 KB argument space)
+struct PutChunk { uint32_t w[PUT_WORDS]; };
+__global__ __launch_bounds__(256) void k_put_words(uint32_t *dst, uint32_t count, PutChunk c)
+{
+    for (uint32_t i = threadIdx.x; i < count; i += blockDim.x) dst[i] = c.w[i];
 }
 
 // Bins kept in LDS per workgroup, flushed once with global atomics.  Arithmetic
@@ -355,6 +367,19 @@ hipError_t launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st)
     const size_t want = (n + threads - 1) / threads;
     const int blocks = (int)(want < 2048 ? want : 2048);
     hipLaunchKernelGGL(k_fill_u64, dim3(blocks), dim3(threads), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_put_words(void *dst, const void *host_src, size_t n_words, hipStream_t st)
+{
+    const uint32_t *src = (const uint32_t *)host_src;
+    uint32_t *d = (uint32_t *)dst;
+    for (size_t done = 0; done < n_words; done += PUT_WORDS) {
+        PutChunk c;
+        const uint32_t cnt = (uint32_t)(n_words - done < PUT_WORDS ? n_words - done : PUT_WORDS);
+        memcpy(c.w, src + done, (size_t)cnt * 4);
+        hipLaunchKernelGGL(k_put_words, dim3(1), dim3(256), 0, st, d + done, cnt, c);
+    }
     return hipGetLastError();
 }
 
