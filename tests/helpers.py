@@ -123,3 +123,51 @@ def optimal_footprint(tr, granule):
 
 def all_perms(n):
     return itertools.permutations(range(n))
+
+
+def validate_cases():
+    """(name, trace, status) triples for trace validation.  The status of every case is written
+    out here from the documented rules (the error list of the library's header), not taken from
+    either implementation: -6 = invalid content (size 0, alloc >= free, free > n_steps, gap outside
+    [alloc, free-1], step_ns 0), -7 = out of range (a size >= 2^53, sum of sizes >= 2^63, sum of
+    step_ns >= 2^53, max size * n_steps >= 2^64), 0 = valid.  Invalid content is reported before
+    a range problem of the same trace."""
+    from traces import random_trace
+
+    def base(n=1000, T=40, step=True):
+        return random_trace(3, n, T, with_step_ns=step)
+
+    def edit(field, i, v, **kw):
+        t = base(**kw)
+        getattr(t, field)[i] = v
+        return t
+
+    cases = [("valid", base(), 0), ("valid without step times", base(step=False), 0)]
+    cases.append(("size 0", edit("size", 5, 0), -6))
+    t = base(); t.alloc[9] = t.free[9]; cases.append(("alloc == free", t, -6))
+    t = base(); t.alloc[9] = 39; t.free[9] = 12; cases.append(("alloc > free", t, -6))
+    cases.append(("free > n_steps", edit("free", 7, 41), -6))
+    t = base(); t.alloc[7] = 39; t.free[7] = 40; t.gap_lo[7] = t.gap_hi[7] = 39
+    cases.append(("free == n_steps is allowed", t, 0))
+    t = base(); i = int(np.argmax(t.alloc > 0)); t.gap_lo[i] = t.alloc[i] - 1
+    cases.append(("gap_lo below alloc", t, -6))
+    t = base(); t.gap_hi[4] = t.free[4]; cases.append(("gap_hi above free-1", t, -6))
+    t = base(); i = int(np.argmax(t.free - t.alloc > 2)); t.gap_lo[i] = t.alloc[i] + 1; t.gap_hi[i] = t.alloc[i]
+    cases.append(("gap_lo above gap_hi", t, -6))
+    cases.append(("step_ns 0", edit("step_ns", 3, 0), -6))
+    cases.append(("size 2^53", edit("size", 11, 1 << 53), -7))
+    cases.append(("size 2^53 - 1 is allowed", edit("size", 11, (1 << 53) - 1), 0))
+    cases.append(("one step_ns of 2^53", edit("step_ns", 2, 1 << 53), -7))
+    t = base(); t.step_ns[:] = 1; t.step_ns[0] = (1 << 53) - 39
+    cases.append(("sum of step_ns == 2^53", t, -7))
+    t = base(); t.step_ns[:] = 1; t.step_ns[0] = (1 << 53) - 40
+    cases.append(("sum of step_ns == 2^53 - 1 is allowed", t, 0))
+    for n, st in ((1024, 0), (1025, -7)):          # 1024 * (2^53 - 1) = 2^63 - 1024; one more reaches 2^63
+        t = base(n=n); t.size[:] = (1 << 53) - 1
+        cases.append((f"sum of {n} sizes of 2^53 - 1", t, st))
+    for T, st in ((4095, 0), (4096, -7)):          # 2^52 * 4096 = 2^64
+        t = base(T=T); t.size[17] = 1 << 52
+        cases.append((f"size 2^52 over {T} steps", t, st))
+    t = base(); t.size[5] = 0; t.size[6] = 1 << 53
+    cases.append(("invalid content comes before a range problem", t, -6))
+    return cases

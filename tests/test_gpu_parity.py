@@ -294,22 +294,9 @@ def test_score_swaps_configs(lap, oracle_mod, cfg):
 
 
 def test_validate_trace(lap, oracle_mod):
-    tr = random_trace(3, 1000, 40, with_step_ns=True)
-    assert lap.validate_trace(lap.DeviceTrace(tr)) == 0 == oracle_mod.validate_trace(tr)
-
-    def broken(**kw):
-        t = random_trace(3, 1000, 40, with_step_ns=True)
-        for k, (i, v) in kw.items():
-            getattr(t, k)[i] = v
-        return t
-    cases = [broken(size=(5, 0)), broken(free=(7, 41)), broken(alloc=(9, 40)), broken(step_ns=(3, 0)),
-             broken(size=(11, 1 << 53)), broken(step_ns=(2, 1 << 53))]
-    t = random_trace(3, 1000, 40); t.gap_lo[4] = t.gap_hi[4] + 1; cases.append(t)
-    t = random_trace(3, 1000, 40); t.gap_hi[4] = t.free[4]; cases.append(t)
-    t = random_trace(3, 1000, 40); t.size[:] = (1 << 53) - 1; t.size = np.tile(t.size, 2)[:1025]
-    t.alloc = np.tile(t.alloc, 2)[:1025]; t.free = np.tile(t.free, 2)[:1025]
-    t.gap_lo = t.alloc.copy(); t.gap_hi = (t.free - 1).astype(np.uint32); cases.append(t)   # sum >= 2^63
-    for t in cases:
-        want = oracle_mod.validate_trace(t)
-        assert want in (-6, -7)
-        assert lap.validate_trace(lap.DeviceTrace(t)) == want
+    """Every documented rule with its exact status (the table of helpers.validate_cases, which the
+    oracle is pinned to as well)."""
+    from helpers import validate_cases
+    for name, t, status in validate_cases():
+        assert oracle_mod.validate_trace(t) == status, name
+        assert lap.validate_trace(lap.DeviceTrace(t)) == status, name
