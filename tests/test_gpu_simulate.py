@@ -44,6 +44,16 @@ def test_simulate_golden(lap, oracle_mod):
     assert [r["total_ns"] for r in refs[:4]] == [1000, 1000, 1030, 1060]
 
 
+def test_simulate_golden_listed_variable_without_idle_gap(lap, oracle_mod):
+    g = read_golden("e6_simulate.txt")
+    ints = lambda key: [int(x) for x in g[key][0]]
+    tr = mk_trace(ints("nogap_size"), ints("nogap_alloc"), ints("nogap_free"), T=10, gap_lo=ints("nogap_gap_lo"),
+                  gap_hi=ints("nogap_gap_hi"), step_ns=[100] * 10)
+    refs = _check(lap, oracle_mod, tr, 1.0, ints("nogap_swap_list"), [(4, lim) for lim in ints("nogap_limits")])
+    assert [r["total_ns"] for r in refs] == ints("nogap_total_ns")
+    assert [r["peak_resident"] for r in refs] == ints("nogap_peak_resident")
+
+
 @pytest.mark.parametrize("seed,n,T", [(0, 1, 1), (1, 30, 9), (2, 400, 25), (3, 3000, 120), (4, 12000, 700)])
 def test_simulate_random(lap, oracle_mod, seed, n, T):
     tr = random_trace(1900 + seed, n, T, with_step_ns=(seed % 2 == 0))

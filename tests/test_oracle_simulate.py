@@ -26,6 +26,23 @@ def test_e6_golden(oracle_mod):
     assert oracle_mod.simulate_swaps(tr, 1.0, [], 830)["forced"] == 0
 
 
+def test_e6_listed_variable_without_idle_gap(oracle_mod):
+    """Section IV-E, reading: a listed variable whose two accesses coincide is never swapped and takes
+    no time on the streams of the plan, so its presence moves no other variable's swap-in."""
+    g = read_golden("e6_simulate.txt")
+    ints = lambda key: [int(x) for x in g[key][0]]
+    tr = mk_trace(ints("nogap_size"), ints("nogap_alloc"), ints("nogap_free"), T=10, gap_lo=ints("nogap_gap_lo"),
+                  gap_hi=ints("nogap_gap_hi"), step_ns=[100] * 10)
+    sl = ints("nogap_swap_list")
+    for q, lim in enumerate(ints("nogap_limits")):
+        r = oracle_mod.simulate_swaps(tr, 1.0, sl, lim)
+        assert r["total_ns"] == ints("nogap_total_ns")[q], lim
+        assert r["peak_resident"] == ints("nogap_peak_resident")[q] and r["forced"] == ints("nogap_forced")[q]
+        # and the variable's place in the list does not matter
+        for other in ([4, 2, 0, 1], [2, 0, 1, 4], [2, 0, 1]):
+            assert oracle_mod.simulate_swaps(tr, 1.0, other, lim) == r
+
+
 def tick_simulation(tr, link, sl, limit, plan):
     """The same machine advanced one nanosecond at a time, written around per-variable states
     instead of event times."""
