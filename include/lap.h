@@ -150,6 +150,22 @@ size_t lap_workspace_bytes(int which_call, uint32_t n_vars, uint32_t n_steps, ui
 int lap_load_profile(const lap_trace *trace, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
                      void *ws, size_t ws_bytes, void *hip_stream);
 
+/* lap_load_profile for callers that cannot allocate device memory and have no workspace to pass
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments without ws, same kernels, same results.  The scratch (the difference array, 8 bytes
+ * per step) is a fixed array inside the library's code object, (LAP_STATIC_MAX_STEPS + 1) * 8 bytes
+ * = 8 MiB per GPU, held until the process ends; the call allocates nothing and frees nothing.
+ *   - n_steps > LAP_STATIC_MAX_STEPS returns LAP_E_SIZE (and says so on stderr) before anything
+ *     is enqueued; n_vars is not limited.
+ *   - The first call on each device looks up the array's address on that device (no allocation, but
+ *     a runtime query: make that first call outside a graph capture); later calls only launch.
+ *   - All calls on one GPU share that GPU's array, whatever their stream: calls that overlap in
+ *     time on one GPU race.  Order them on one stream or with events.  The array keeps the last
+ *     call's contents; the kernels clear the part they use before they use it. */
+#define LAP_STATIC_MAX_STEPS (1u << 20)
+int lap_load_profile_static(const lap_trace *trace, uint64_t *load, uint64_t *peak, uint32_t *t_peak,
+                            void *hip_stream);
+
 /* Section III-C, for B orderings (each with its own fit policy) at once.
  *   ords           [B] host
  *   best_offsets   [N]   out: byte offset of every variable under the best ordering

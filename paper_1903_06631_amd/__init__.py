@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     load_profile,
+    load_profile_static,
     plan_pool,
     profile_enable,
     profile_last_ms,

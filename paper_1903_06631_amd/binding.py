@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "liblap.so")
 _lib = None
 
 EXPORTS = [
-    "lap_workspace_bytes", "lap_load_profile", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
+    "lap_workspace_bytes", "lap_load_profile", "lap_load_profile_static", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
     "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps", "lap_evaluate_weights",
     "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms",
 ]
@@ -57,6 +57,8 @@ def load_library():
     lib.lap_load_profile.restype = C.c_int
     lib.lap_load_profile.argtypes = [C.POINTER(_Trace), C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lap_load_profile_static.restype = C.c_int
+    lib.lap_load_profile_static.argtypes = [C.POINTER(_Trace), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.lap_plan_pool.restype = C.c_int
     lib.lap_plan_pool.argtypes = [C.POINTER(_Trace), C.POINTER(_Ordering), C.c_uint32,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -180,6 +182,26 @@ def load_profile(dt: DeviceTrace, sync: bool = True):
                               ws.data_ptr(), need, _stream_ptr(dt.device))
     if rc:
         raise LapError(rc, "lap_load_profile")
+    if sync:
+        torch.cuda.current_stream(dt.device).synchronize()
+    return dict(load=load, peak=peak, t_peak=t_peak)
+
+
+STATIC_MAX_STEPS = 1 << 20
+
+
+def load_profile_static(dt: DeviceTrace, sync: bool = True):
+    """lap_load_profile_static: as load_profile, with the library's own fixed scratch array (no workspace)."""
+    torch = _torch()
+    lib = load_library()
+    load = torch.empty(dt.n_steps, dtype=torch.int64, device=dt.device)
+    peak = torch.empty(1, dtype=torch.int64, device=dt.device)
+    t_peak = torch.empty(1, dtype=torch.int32, device=dt.device)
+    tr = dt.c_struct()
+    rc = lib.lap_load_profile_static(C.byref(tr), load.data_ptr(), peak.data_ptr(), t_peak.data_ptr(),
+                                     _stream_ptr(dt.device))
+    if rc:
+        raise LapError(rc, "lap_load_profile_static")
     if sync:
         torch.cuda.current_stream(dt.device).synchronize()
     return dict(load=load, peak=peak, t_peak=t_peak)

@@ -3,6 +3,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "../../include/lap.h"
@@ -183,6 +184,35 @@ int load_profile_impl(const lap_trace *tr, uint64_t *load, uint64_t *peak, uint3
     return LAP_OK;
 }
 
+// Scratch of lap_load_profile_static: the difference array of the largest supported time line.
+// One copy per GPU, held from module load to process end.  In host code the name only stands
+// for the symbol; its device address comes from hipGetSymbolAddress, once per device.
+constexpr uint32_t STATIC_MAX_STEPS = LAP_STATIC_MAX_STEPS;
+constexpr size_t STATIC_SCRATCH_BYTES = ((size_t)STATIC_MAX_STEPS + 1) * 8;
+static __device__ __align__(256) unsigned char scratch[(STATIC_SCRATCH_BYTES + 255) / 256 * 256];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[MAX_DEVICES];      // per device: address of its copy of `scratch`, null until asked for
+
+// address of the current device's copy of the scratch array (no allocation: the array is part of
+// the loaded code object)
+int static_scratch(void **out)
+{
+    int dev = -1;
+    LAP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return LAP_E_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        LAP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return LAP_E_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LAP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -245,6 +275,23 @@ int lap_load_profile(const lap_trace *tr, uint64_t *load, uint64_t *peak, uint32
     Carver c(ws);
     uint64_t *delta = c.take<uint64_t>((size_t)tr->n_steps + 1);
     return load_profile_impl(tr, load, peak, t_peak, delta, (hipStream_t)hip_stream);
+}
+
+int lap_load_profile_static(const lap_trace *tr, uint64_t *load, uint64_t *peak, uint32_t *t_peak, void *hip_stream)
+{
+    int rc = check_trace_args(tr);
+    if (rc) return rc;
+    if (!load || !peak || !t_peak) return LAP_E_NULL;
+    if (tr->n_steps > STATIC_MAX_STEPS) {
+        fprintf(stderr, "liblap: lap_load_profile_static: n_steps = %u exceeds LAP_STATIC_MAX_STEPS = %u; "
+                        "use lap_load_profile with a workspace\n", tr->n_steps, STATIC_MAX_STEPS);
+        return LAP_E_SIZE;
+    }
+    void *p = nullptr;
+    rc = static_scratch(&p);
+    if (rc) return rc;
+    // same kernels as lap_load_profile; they clear the part of the array they use first
+    return load_profile_impl(tr, load, peak, t_peak, (uint64_t *)p, (hipStream_t)hip_stream);
 }
 
 int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uint64_t *best_offsets,

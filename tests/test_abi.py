@@ -149,3 +149,19 @@ def test_product_never_imports_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 txt = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in txt.lower() or f == "__init__.py" and "oracle" not in txt, (dirpath, f)
+
+
+def test_static_entry_point_rejects_on_the_host(lap):
+    """lap_load_profile_static: NULL arguments and time lines beyond its fixed scratch are refused
+    before any HIP call."""
+    from paper_1903_06631_amd.binding import STATIC_MAX_STEPS, _Trace
+    lib = lap.load_library()
+    fake = 0x1000
+    hdr = open(os.path.join(ROOT, "include", "lap.h")).read()
+    assert int(re.search(r"#define LAP_STATIC_MAX_STEPS \(1u << (\d+)\)", hdr).group(1)) == STATIC_MAX_STEPS.bit_length() - 1
+    assert lib.lap_load_profile_static(None, fake, fake, fake, None) == -1
+    ok = _Trace(4, 3, fake, fake, fake, None, None, None)
+    assert lib.lap_load_profile_static(C.byref(ok), None, fake, fake, None) == -1
+    long_ = _Trace(4, STATIC_MAX_STEPS + 1, fake, fake, fake, None, None, None)
+    assert lib.lap_load_profile_static(C.byref(long_), fake, fake, fake, None) == -2
+    assert lib.lap_load_profile_static(C.byref(_Trace(0, 3, fake, fake, fake, None, None, None)), fake, fake, fake, None) == -2
