@@ -311,6 +311,17 @@ int lap_validate_trace(const lap_trace *trace, void *ws, size_t ws_bytes, void *
 
 const char *lap_status_string(int status);
 
+/* Tuning knobs, process-wide and not thread safe: set them before the calls they affect.
+ *   LAP_OPT_SEG_MIN_VARS  lap_plan_pool has three ways to keep track of free addresses and picks
+ *       one per trace on the device: per-step free lists when the lifetimes are short (their sum
+ *       is at most 6 N), else, for first-fit orderings, free lists per time segment when the
+ *       trace has at least this many variables (default 32768) and the workspace has room for
+ *       them, else a sweep over the sorted list of placed blocks.  All three give the same
+ *       offsets.  0 = segment lists whenever they apply.
+ * Returns LAP_E_ORDERING for an unknown option. */
+enum { LAP_OPT_SEG_MIN_VARS = 0 };
+int lap_set_option(int option, uint64_t value);
+
 /* Optional kernel timing for benchmarks.  When enabled, each call brackets
  * its dominant kernel with HIP events on the caller's stream; after the
  * stream is synchronised lap_profile_last_ms returns that kernel's duration

@@ -6,6 +6,8 @@ the library's kernels.  There is no CPU fallback: if liblap.so is missing or a
 call fails, an exception is raised.
 """
 from .binding import (  # noqa: F401
+    OPT_SEG_MIN_VARS,
+    SEG_MIN_VARS_DEFAULT,
     DeviceTrace,
     LapError,
     detect_iteration,
@@ -20,6 +22,7 @@ from .binding import (  # noqa: F401
     schedule_swaps,
     score_swaps,
     select_swaps,
+    set_option,
     simulate_swaps,
     status_string,
     validate_trace,

@@ -14,7 +14,7 @@ _lib = None
 EXPORTS = [
     "lap_workspace_bytes", "lap_load_profile", "lap_load_profile_static", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
     "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps", "lap_evaluate_weights",
-    "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms",
+    "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms", "lap_set_option",
 ]
 
 
@@ -88,6 +88,8 @@ def load_library():
                                          C.c_void_p]
     lib.lap_validate_trace.restype = C.c_int
     lib.lap_validate_trace.argtypes = [C.POINTER(_Trace), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lap_set_option.restype = C.c_int
+    lib.lap_set_option.argtypes = [C.c_int, C.c_uint64]
     lib.lap_profile_enable.restype = C.c_int
     lib.lap_profile_enable.argtypes = [C.c_int]
     lib.lap_profile_last_ms.restype = C.c_float
@@ -102,6 +104,16 @@ def status_string(status: int) -> str:
 
 def workspace_bytes(which: int, n_vars: int, n_steps: int, B: int = 0) -> int:
     return int(load_library().lap_workspace_bytes(which, n_vars, n_steps, B))
+
+
+OPT_SEG_MIN_VARS = 0
+SEG_MIN_VARS_DEFAULT = 32768
+
+
+def set_option(option: int, value: int) -> None:
+    rc = load_library().lap_set_option(int(option), int(value))
+    if rc:
+        raise LapError(rc, "lap_set_option")
 
 
 def profile_enable(on: bool) -> None:

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblap.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
-SOURCES = ["api.hip", "load_profile.hip", "orderings.hip", "place_fast.hip", "place_wide.hip",
+SOURCES = ["api.hip", "load_profile.hip", "orderings.hip", "place_fast.hip", "place_wide.hip", "place_seg.hip",
            "swap_scores.hip", "select_swaps.hip", "detect_iteration.hip",
            "schedule_swaps.hip", "simulate_swaps.hip"]
 

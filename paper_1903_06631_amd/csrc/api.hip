@@ -3,6 +3,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -40,13 +41,18 @@ inline uint64_t plan_list_cap(uint32_t n) { return ((uint64_t)n * lap::PLAN_CL +
 
 // block lists of the placement kernels: the 64-bit path needs off/end/life per ordering, the
 // packed 32-bit path a packed main list with lifetimes, the per-step lists and their counters
+// entries of the segment kernel's list pool (all orderings together), and of its list directory
+inline size_t seg_pool_entries(uint32_t n, uint32_t B) { return (size_t)B * n * lap::PLAN_SEG_BUDGET; }
+inline size_t seg_dir_cap(uint32_t T) { return (size_t)T + 2 * (((size_t)T >> lap::PLAN_SEG_SHIFT0) + 1) + 1; }
+
 size_t ws_plan_lists(uint32_t n, uint32_t T, uint32_t B)
 {
     const size_t bn = (size_t)B * n;
     const size_t wide = 3 * up(bn * 8);
     const size_t fast = 4 * up(bn * 8) + 4 * up((size_t)B * lap::PLAN_REC * 8) + up((size_t)B * plan_list_cap(n) * 8) +
                         2 * up((size_t)B * T * 4);
-    return wide > fast ? wide : fast;
+    const size_t seg = up(seg_pool_entries(n, B) * 8);
+    return std::max(wide, std::max(fast, seg));
 }
 
 size_t ws_plan(uint32_t n, uint32_t T, uint32_t B)
@@ -58,6 +64,8 @@ size_t ws_plan(uint32_t n, uint32_t T, uint32_t B)
            + up((size_t)B * 8)                                         // footprints
            + up((size_t)n * 16)                                        // packed variable records
            + up(bn * 8)                                                // offsets of every ordering
+           + 2 * up((seg_dir_cap(T) + 2) * 4)                          // segment lists: blocks per list, list starts
+           + up((size_t)B * seg_dir_cap(T) * 4)                        // and their lengths, per slot
            + ws_plan_lists(n, T, B);
 }
 
@@ -131,6 +139,9 @@ int check_ws(void *ws, size_t have, size_t need)
     if (!ws || ((uintptr_t)ws % ALIGN) != 0 || have < need) return LAP_E_WORKSPACE;
     return LAP_OK;
 }
+
+// lap_set_option(LAP_OPT_SEG_MIN_VARS): variables from which on the segment lists are used
+uint64_t g_seg_min_vars = 32768;
 
 bool g_prof = false;
 hipEvent_t g_ev[LAP_K_COUNT][2];
@@ -249,6 +260,13 @@ const char *lap_status_string(int s)
     }
 }
 
+int lap_set_option(int option, uint64_t value)
+{
+    if (option != LAP_OPT_SEG_MIN_VARS) return LAP_E_ORDERING;
+    g_seg_min_vars = value;
+    return LAP_OK;
+}
+
 int lap_profile_enable(int on)
 {
     g_prof = on != 0;
@@ -329,7 +347,12 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint64_t *fps_ws = c.take<uint64_t>(B);
     uint64_t *vrec = c.take<uint64_t>((size_t)n * 2);
     uint64_t *offs_ws = c.take<uint64_t>(bn);
-    // the two placement kernels never both run: their lists share one region
+    const size_t dir_cap = seg_dir_cap(T);
+    uint32_t *seg_cnt = c.take<uint32_t>(dir_cap + 2);
+    uint32_t *seg_lst = c.take<uint32_t>(dir_cap + 2);
+    uint32_t *seg_len = c.take<uint32_t>((size_t)B * dir_cap);
+    // the placement kernels run one after the other and none needs another's lists: they share one region
+    uint64_t *seg_pool = (uint64_t *)((char *)ws + c.used);
     Carver cw((char *)ws + c.used), cf((char *)ws + c.used);
     uint64_t *m_off = cw.take<uint64_t>(bn);
     uint64_t *m_end = cw.take<uint64_t>(bn);
@@ -367,7 +390,10 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     static_assert(sizeof(lap::PlanHeader) % 8 == 0, "header is cleared in 64-bit words");
     LAP_HIP(lap::launch_fill_u64((uint64_t *)hdr, sizeof(lap::PlanHeader) / 8, 0, st));
     LAP_HIP(lap::launch_fill_u64((uint64_t *)cntd, ((size_t)T + 2) / 2, 0, st));
-    LAP_HIP(lap::launch_plan_prep(n, T, tr->size, tr->alloc, tr->free_, cntd, lstart, hdr, vrec, st));
+    LAP_HIP(lap::launch_plan_prep(n, T, B, tr->size, tr->alloc, tr->free_, cntd, lstart, hdr, vrec,
+                                  seg_pool_entries(n, B), g_seg_min_vars, st));
+    LAP_HIP(lap::launch_seg_prep(n, T, B, tr->alloc, tr->free_, hdr, seg_cnt, seg_lst, (uint32_t)dir_cap,
+                                 seg_pool_entries(n, B), st));
     // per-step entry counts start at zero (cleared as 64-bit words, the regions are padded)
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_ns, ((size_t)B * T + 1) / 2, 0, st));
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_nu, ((size_t)B * T + 1) / 2, 0, st));
@@ -378,6 +404,8 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
                                        f_life2, f_roe, f_rlife, f_roe2, f_rlife2, f_L, capL, l_ns, l_nu, offs, fps, st));
         LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, fits, hdr, m_off, m_end, m_life, offs,
                                        fps, st));
+        LAP_HIP(lap::launch_place_seg(n, T, B, perm, fits, any_first, hdr, vrec, seg_lst, seg_pool, seg_len,
+                                      (uint32_t)dir_cap, offs, fps, st));
     }
     LAP_HIP(lap::launch_select(n, B, fps, offs, perm, best_footprint, best_ordering, best_offsets, all_offsets, st));
     return LAP_OK;

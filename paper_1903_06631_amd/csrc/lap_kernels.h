@@ -5,6 +5,12 @@
 
 namespace lap {
 
+// candidate segment widths of the segment kernel: 2^PLAN_SEG_SHIFT0 .. 2^(PLAN_SEG_SHIFT0 + PLAN_SEG_CAND - 1) steps
+constexpr uint32_t PLAN_SEG_SHIFT0 = 2, PLAN_SEG_CAND = 9;
+// list entries of the segment kernel's pool per ordering and variable (the pool is shared: an
+// ordering that needs more leaves fewer slots)
+constexpr uint32_t PLAN_SEG_BUDGET = 24;
+
 // Per-call facts about the trace, computed on the device before placement.
 struct PlanHeader {
     unsigned long long or_sizes;   // bitwise OR of all sizes
@@ -15,6 +21,13 @@ struct PlanHeader {
     uint32_t mode1;                // 1: per-step lists are in use (sum of lifetimes <= PLAN_CL * N)
     uint32_t part[2];              // placement workgroups that have started, per fit policy
     uint32_t progress[2];          // their progress, in units of 512 ranks, summed
+    // segment lists (place_seg.hip), used when per-step lists are not and the pool has room
+    uint32_t mode2;                // 1: the segment kernel places this trace
+    uint32_t seg_shift;            // log2 of the segment width in steps
+    uint32_t seg_K;                // number of segments
+    uint32_t seg_slots;            // orderings that have room in the list pool at once
+    unsigned long long seg_need;   // list entries one ordering needs
+    unsigned long long seg_tot[PLAN_SEG_CAND];   // per candidate width: blocks entered into lists, summed over the variables
 };
 constexpr uint32_t PLAN_CL = 6;
 
@@ -33,8 +46,15 @@ hipError_t launch_validate(uint32_t n, uint32_t T, const uint64_t *size, const u
 hipError_t launch_sort_perm(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                             const uint32_t *kinds, const uint64_t *seeds, uint32_t *perm, uint32_t *tmp,
                             bool any_explicit, hipStream_t st);
-hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+hipError_t launch_plan_prep(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                             const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, void *vrec,
+                            uint64_t seg_pool_entries, uint64_t seg_min_vars, hipStream_t st);
+hipError_t launch_seg_prep(uint32_t n, uint32_t T, uint32_t B, const uint32_t *alloc, const uint32_t *free_,
+                           PlanHeader *hdr, uint32_t *cnt, uint32_t *lst, uint32_t dir_cap, uint64_t pool_entries,
+                           hipStream_t st);
+hipError_t launch_place_seg(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
+                            bool any_first, const PlanHeader *hdr, const void *vrec, const uint32_t *lst,
+                            uint64_t *pool, uint32_t *lens, uint32_t dir_cap, uint64_t *offs, uint64_t *fps,
                             hipStream_t st);
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,

@@ -93,13 +93,16 @@ __device__ __forceinline__ uint32_t wave_reduce_max32(uint32_t v) { return read_
 // preparation: granule shift, lifetime statistics, per-step list layout
 // ---------------------------------------------------------------------------
 
-__global__ __launch_bounds__(256) void k_plan_prep1(uint32_t n, const uint64_t *__restrict__ size,
+__global__ __launch_bounds__(256) void k_plan_prep1(uint32_t n, uint32_t T, const uint64_t *__restrict__ size,
                                                     const uint32_t *__restrict__ alloc,
                                                     const uint32_t *__restrict__ free_, uint32_t *cntd,
                                                     PlanHeader *hdr)
 {
     const uint32_t stride = gridDim.x * blockDim.x;
     unsigned long long orv = 0, sum = 0;
+    unsigned long long seg[PLAN_SEG_CAND];
+#pragma unroll
+    for (uint32_t c = 0; c < PLAN_SEG_CAND; ++c) seg[c] = 0;
     uint32_t multi = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         const uint64_t s = size[i];
@@ -109,14 +112,33 @@ __global__ __launch_bounds__(256) void k_plan_prep1(uint32_t n, const uint64_t *
         multi += (f - a > 1) ? 1u : 0u;
         atomicAdd(&cntd[a], 1u);
         atomicAdd(&cntd[f], 0xFFFFFFFFu);          // -1 modulo 2^32
+        // lists the block would enter with segments of 2^sh steps: one per segment it touches,
+        // one more per segment it lives through, one per step in the others
+#pragma unroll
+        for (uint32_t c = 0; c < PLAN_SEG_CAND; ++c) {
+            const uint32_t sh = PLAN_SEG_SHIFT0 + c, w = 1u << sh, K = (uint32_t)(((uint64_t)T + w - 1) >> sh);
+            const uint32_t k0 = a >> sh, k1 = (f - 1) >> sh;
+            const uint32_t kf0 = (uint32_t)(((uint64_t)a + w - 1) >> sh), kf1 = f == T ? K : f >> sh;
+            const uint32_t nf = kf1 > kf0 ? kf1 - kf0 : 0;
+            uint32_t steps = f - a;
+            if (nf) {
+                const uint64_t hi = (uint64_t)kf1 << sh;
+                steps -= (uint32_t)((hi < T ? hi : (uint64_t)T) - ((uint64_t)kf0 << sh));
+            }
+            seg[c] += 1ull + (k1 - k0 + 1) + nf + steps;      // (the first: the list of everything)
+        }
     }
     for (int m = WAVE / 2; m > 0; m >>= 1) orv |= shfl_xor64(orv, m);
     sum = wave_reduce_add(sum);
     multi = wave_reduce_add32(multi);
+#pragma unroll
+    for (uint32_t c = 0; c < PLAN_SEG_CAND; ++c) seg[c] = wave_reduce_add(seg[c]);
     if ((threadIdx.x & (WAVE - 1)) == 0) {
         atomicOr((unsigned long long *)&hdr->or_sizes, orv);
         atomicAdd((unsigned long long *)&hdr->sum_sizes, sum);
         atomicAdd(&hdr->n_multi, multi);
+#pragma unroll
+        for (uint32_t c = 0; c < PLAN_SEG_CAND; ++c) atomicAdd(&hdr->seg_tot[c], seg[c]);
     }
 }
 
@@ -140,9 +162,10 @@ __device__ __forceinline__ uint64_t prep_block_scan(uint64_t v, uint64_t *wtmp, 
 }
 
 // live[t] = number of variables live at step t; lstart = exclusive prefix sum of live + 1
-__global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_t T,
+__global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_t T, uint32_t B,
                                                              const uint32_t *__restrict__ cntd,
-                                                             uint32_t *__restrict__ lstart, PlanHeader *hdr)
+                                                             uint32_t *__restrict__ lstart, PlanHeader *hdr,
+                                                             uint64_t seg_pool_entries, uint64_t seg_min_vars)
 {
     __shared__ uint64_t wtmp[PREP_THREADS / WAVE];
     const uint32_t tid = threadIdx.x;
@@ -168,6 +191,37 @@ __global__ __launch_bounds__(PREP_THREADS) void k_plan_prep2(uint32_t n, uint32_
         hdr->shift = shift;
         hdr->fast = fast ? 1u : 0u;
         hdr->mode1 = lists ? 1u : 0u;
+        // Segment lists: the width that enters the fewest blocks into lists; every list has one
+        // entry more than the blocks it sees.  Taken when per-step lists are not, the trace has
+        // enough variables for them to pay (below that, sweeping the sorted blocks is faster), the
+        // list directory and one ordering fit 32-bit indices, addresses stay below the end marker
+        // of the top range, and the pool has room for at least one ordering.
+        uint32_t best_c = 0;
+        uint64_t best_need = ~0ull;
+        for (uint32_t c = 0; c < PLAN_SEG_CAND; ++c) {
+            const uint32_t sh = PLAN_SEG_SHIFT0 + c;
+            const uint64_t K = ((uint64_t)T + (1ull << sh) - 1) >> sh;
+            const uint64_t need = hdr->seg_tot[c] + 2 * K + T + 1;
+            if (need < best_need) { best_need = need; best_c = c; }
+        }
+        // ... or rather the narrowest width within an eighth of that: narrower segments mean fewer
+        // lists per variable (a variable asks about lifetime / w + w of them)
+        for (uint32_t c = 0; c < best_c; ++c) {
+            const uint32_t sh = PLAN_SEG_SHIFT0 + c;
+            const uint64_t K = ((uint64_t)T + (1ull << sh) - 1) >> sh;
+            const uint64_t need = hdr->seg_tot[c] + 2 * K + T + 1;
+            if (need <= best_need + best_need / 8) { best_need = need; best_c = c; break; }
+        }
+        const uint32_t ssh = PLAN_SEG_SHIFT0 + best_c;
+        const uint64_t K = ((uint64_t)T + (1ull << ssh) - 1) >> ssh;
+        const uint64_t slots = best_need ? seg_pool_entries / best_need : 0;
+        const bool seg = fast && !lists && n >= seg_min_vars && (sum >> shift) < 0xFFFFFFFEull &&
+                         best_need < 0xFFFFFFFFull && T < 0x7FFF0000u && slots >= 1;
+        hdr->mode2 = seg ? 1u : 0u;
+        hdr->seg_shift = ssh;
+        hdr->seg_K = (uint32_t)K;
+        hdr->seg_slots = (uint32_t)(slots < B ? slots : B);
+        hdr->seg_need = best_need;
     }
 }
 
@@ -868,6 +922,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     __shared__ uint32_t s_prio;              // wave priority in force for this workgroup
 
     if (!A.hdr->fast) return;               // the 64-bit kernel handles this trace
+    if (A.hdr->mode2 && !BEST) return;      // the segment kernel places the first-fit orderings of this trace
     const uint32_t b = blockIdx.x;
     if ((A.fits[b] != 0) != BEST) return;   // the other instantiation handles this ordering
     const bool mode1 = A.hdr->mode1 != 0;
@@ -1290,14 +1345,15 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     }
 }
 
-hipError_t launch_plan_prep(uint32_t n, uint32_t T, const uint64_t *size, const uint32_t *alloc,
+hipError_t launch_plan_prep(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                             const uint32_t *free_, uint32_t *cntd, uint32_t *lstart, PlanHeader *hdr, void *vrec,
-                            hipStream_t st)
+                            uint64_t seg_pool_entries, uint64_t seg_min_vars, hipStream_t st)
 {
     uint32_t blocks = (n + 255) / 256;
     blocks = blocks > 1024 ? 1024 : blocks;
-    hipLaunchKernelGGL(k_plan_prep1, dim3(blocks), dim3(256), 0, st, n, size, alloc, free_, cntd, hdr);
-    hipLaunchKernelGGL(k_plan_prep2, dim3(1), dim3(PREP_THREADS), 0, st, n, T, cntd, lstart, hdr);
+    hipLaunchKernelGGL(k_plan_prep1, dim3(blocks), dim3(256), 0, st, n, T, size, alloc, free_, cntd, hdr);
+    hipLaunchKernelGGL(k_plan_prep2, dim3(1), dim3(PREP_THREADS), 0, st, n, T, B, cntd, lstart, hdr, seg_pool_entries,
+                       seg_min_vars);
     hipLaunchKernelGGL(k_plan_pack, dim3(blocks), dim3(256), 0, st, n, size, alloc, free_, hdr, (uint4 *)vrec);
     return hipGetLastError();
 }

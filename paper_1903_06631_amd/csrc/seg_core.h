@@ -1,0 +1,225 @@
+// Free-range ("hole") lists over time segments: the per-thread primitives and the geometry of
+// the segment placement kernel (place_seg.hip).  Plain functions on memory, written so that a
+// host compiler accepts them too (LAP_HD is empty there): the same code can be run under a
+// host-side bounds checker.
+//
+// A list holds the free address ranges with respect to some set of placed blocks, sorted by
+// address, one 64-bit word each: start << 32 | end, in granules.  The last entry always is the
+// range above the highest block, with end = SEG_INF.  Starts and ends ascend strictly
+// (start_i < end_i < start_{i+1}), so a list can be binary searched by end.
+#pragma once
+#include <stdint.h>
+
+#ifndef LAP_HD
+#define LAP_HD
+#endif
+#ifndef SEG_LD
+#define SEG_LD(list, i) (list)[i]       // a host harness may count the reads
+#endif
+
+namespace lap {
+
+constexpr uint32_t SEG_INF = 0xFFFFFFFFu;
+constexpr uint32_t SEG_NOHINT = 0xFFFFFFFFu;     // seg_lower_end / seg_fit / seg_carve: no idea where to look
+
+LAP_HD inline uint64_t seg_pack(uint32_t start, uint32_t end) { return ((uint64_t)start << 32) | end; }
+LAP_HD inline uint32_t seg_start(uint64_t x) { return (uint32_t)(x >> 32); }
+LAP_HD inline uint32_t seg_end(uint64_t x) { return (uint32_t)x; }
+
+// Index of the first of the `len` >= 1 entries whose end is >= key (key < SEG_INF or the answer is
+// the last entry: its end is SEG_INF).  The search runs outward from `hint` in doubling steps and
+// finishes with a binary search, so an answer near the hint costs two or three probes.  (Probing
+// eight ways at a time shortens the chain of dependent reads but reads more: measured slower,
+// the lists' scattered reads are bound by their number, not by their latency.)
+LAP_HD inline uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uint32_t hint)
+{
+    uint32_t lo, hi;                         // the answer lies in [lo, hi]
+    if (hint == SEG_NOHINT) {                // nothing known: plain binary search
+        lo = 0;
+        hi = len - 1;
+    } else if (hint >= len) {
+        hint = len - 1;
+    }
+    if (hint == SEG_NOHINT) {
+    } else if (seg_end(SEG_LD(L, hint)) >= key) {
+        lo = 0;
+        hi = hint;
+        uint32_t step = 1;
+        while (hi > 0) {
+            const uint32_t p = hi > step ? hi - step : 0;
+            if (seg_end(SEG_LD(L, p)) >= key) {
+                hi = p;
+                step <<= 1;
+            } else {
+                lo = p + 1;
+                break;
+            }
+        }
+    } else {
+        lo = hint + 1;                       // hint < len - 1 here: the last end is SEG_INF >= key
+        hi = len - 1;
+        uint32_t step = 1;
+        while (lo < hi) {
+            const uint32_t p = (hi - lo > step - 1) ? lo + step - 1 : hi;
+            if (seg_end(SEG_LD(L, p)) >= key) {
+                hi = p;
+                break;
+            }
+            lo = p + 1;
+            step <<= 1;
+        }
+    }
+    while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (seg_end(SEG_LD(L, mid)) >= key) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+// Lowest address >= o at which s granules are free (o + s < SEG_INF).  idx: in, where to start
+// looking; out, the entry that holds the answer.  hole_end receives that entry's end (where the
+// free range around the answer stops).
+LAP_HD inline uint32_t seg_fit(const uint64_t *L, uint32_t len, uint32_t o, uint32_t s, uint32_t &idx,
+                               uint32_t &hole_end)
+{
+    uint32_t i = seg_lower_end(L, len, o + s, idx);
+    for (;;) {
+        const uint64_t x = SEG_LD(L, i);
+        const uint32_t st = seg_start(x), en = seg_end(x);
+        const uint32_t from = st > o ? st : o;
+        if (en - from >= s) {                // en >= o + s and en > st, so en >= from
+            idx = i;
+            hole_end = en;
+            return from;
+        }
+        ++i;                                 // the last entry always fits: the loop ends inside the list
+    }
+}
+
+// Takes [o, e) out of the free ranges (the range may be free, partly free or not free at all).
+// A list grows by at most one entry per call; `cap` is the room it has.  Returns false, and
+// leaves the list alone, if it would outgrow cap.
+LAP_HD inline bool seg_carve(uint64_t *L, uint32_t &len, uint32_t cap, uint32_t o, uint32_t e, uint32_t hint)
+{
+    const uint32_t i = seg_lower_end(L, len, o + 1, hint);      // first range that ends above o
+    const uint64_t x = SEG_LD(L, i);
+    const uint32_t hs = seg_start(x);
+    if (hs >= e) return true;                                    // nothing free inside [o, e)
+    uint32_t last_end = seg_end(x), j = i + 1;                   // ranges i .. j-1 meet [o, e)
+    while (j < len) {
+        const uint64_t y = SEG_LD(L, j);
+        if (seg_start(y) >= e) break;
+        last_end = seg_end(y);
+        ++j;
+    }
+    const bool left = hs < o, right = last_end > e;
+    const uint32_t keep = (left ? 1u : 0u) + (right ? 1u : 0u), gone = j - i;
+    if (keep > gone) {                                           // one range becomes two
+        if (len + 1 > cap) return false;
+        for (uint32_t q = len; q > j; --q) L[q] = SEG_LD(L, q - 1);
+        len += 1;
+    } else if (keep < gone) {
+        const uint32_t d = gone - keep;
+        for (uint32_t q = j; q < len; ++q) L[q - d] = SEG_LD(L, q);
+        len -= d;
+    }
+    uint32_t w = i;
+    if (left) L[w++] = seg_pack(hs, o);
+    if (right) L[w++] = seg_pack(e, last_end);
+    return true;
+}
+
+// ---------------------------------------------------------------------------
+// geometry: the time line in segments of 2^shift steps
+// ---------------------------------------------------------------------------
+//
+// Three families of lists, numbered in one directory:
+//   all[k]    id k            free w.r.t. every block whose lifetime meets segment k
+//   cover[k]  id K + k        free w.r.t. the blocks that live through all of segment k
+//   step[t]   id 2K + t       free w.r.t. the blocks alive at step t that do not live through
+//                             all of t's segment
+//   every     id 2K + T       free w.r.t. every block: all a variable that lives through the whole
+//                             time line has to ask
+// A variable that lives through all of segment k meets, in time, exactly the blocks of all[k];
+// one that lives through a part of it meets, at each of its steps t there, the blocks of
+// cover[k] and of step[t].  Its lifetime [a, f) therefore decomposes into full segments
+// [kf0, kf0 + nf) and at most two partial ones (the first and the last it touches).
+struct SegGeom {
+    uint32_t shift, K, T;
+    LAP_HD uint32_t w() const { return 1u << shift; }
+    LAP_HD uint32_t n_lists() const { return 2 * K + T + 1; }
+};
+
+struct SegSpan {
+    uint32_t k0, nseg;       // segments the lifetime touches: [k0, k0 + nseg)
+    uint32_t kf0, nf;        // of which it lives through entirely: [kf0, kf0 + nf)
+    uint32_t p0, p0a, p0n;   // first partial segment, its first step there, number of steps (0: none)
+    uint32_t p1, p1a, p1n;   // second partial segment
+    bool whole;              // lives through every segment
+    LAP_HD uint32_t n_query() const { return whole ? 1 : nf + (p0n ? 1 + p0n : 0) + (p1n ? 1 + p1n : 0); }
+    LAP_HD uint32_t n_update() const { return 1 + nseg + nf + p0n + p1n; }
+};
+
+LAP_HD inline SegSpan seg_span(const SegGeom &g, uint32_t a, uint32_t f)
+{
+    SegSpan sp;
+    const uint32_t sh = g.shift, w = 1u << sh;
+    sp.k0 = a >> sh;
+    const uint32_t k1 = (f - 1) >> sh;
+    sp.nseg = k1 - sp.k0 + 1;
+    sp.kf0 = (a + w - 1) >> sh;                          // first segment that starts at or after a
+    const uint32_t kf1 = f == g.T ? g.K : f >> sh;       // first segment that does not end by f
+    sp.nf = kf1 > sp.kf0 ? kf1 - sp.kf0 : 0;
+    sp.p0 = sp.p1 = 0;
+    sp.p0a = sp.p1a = 0;
+    sp.p0n = sp.p1n = 0;
+    const bool first_partial = sp.nf == 0 || sp.k0 < sp.kf0;
+    const bool last_partial = sp.nf == 0 ? k1 != sp.k0 : k1 >= kf1;
+    if (first_partial) {
+        sp.p0 = sp.k0;
+        sp.p0a = a;
+        const uint32_t seg_end_step = (sp.k0 + 1) << sh;
+        sp.p0n = (f < seg_end_step ? f : seg_end_step) - a;
+    }
+    if (last_partial) {
+        sp.p1 = k1;
+        sp.p1a = k1 << sh;
+        sp.p1n = f - sp.p1a;
+    }
+    sp.whole = sp.nf == g.K;
+    return sp;
+}
+
+// i-th list a variable asks (i < n_query): the all-lists of its full segments (the one list of
+// everything if those are all segments), then for each partial segment the cover-list and the
+// step-lists of its steps there
+LAP_HD inline uint32_t seg_query_list(const SegGeom &g, const SegSpan &sp, uint32_t i)
+{
+    if (sp.whole) return 2 * g.K + g.T;
+    if (i < sp.nf) return sp.kf0 + i;
+    i -= sp.nf;
+    if (sp.p0n) {
+        if (i == 0) return g.K + sp.p0;
+        if (i <= sp.p0n) return 2 * g.K + sp.p0a + (i - 1);
+        i -= 1 + sp.p0n;
+    }
+    if (i == 0) return g.K + sp.p1;
+    return 2 * g.K + sp.p1a + (i - 1);
+}
+
+// i-th list a placed block is taken out of (i < n_update): the list of everything, all[k] of every segment it touches,
+// cover[k] of its full segments, step[t] of its steps in the partial segments
+LAP_HD inline uint32_t seg_update_list(const SegGeom &g, const SegSpan &sp, uint32_t i)
+{
+    if (i == 0) return 2 * g.K + g.T;
+    i -= 1;
+    if (i < sp.nseg) return sp.k0 + i;
+    i -= sp.nseg;
+    if (i < sp.nf) return g.K + sp.kf0 + i;
+    i -= sp.nf;
+    if (i < sp.p0n) return 2 * g.K + sp.p0a + i;
+    i -= sp.p0n;
+    return 2 * g.K + sp.p1a + i;
+}
+
+}  // namespace lap
