@@ -29,6 +29,37 @@ def count_edges(tr) -> int:
     return n * (n - 1) // 2 - disjoint
 
 
+def source_stamp(*names) -> str:
+    """16 hex digits of SHA-256 over the named kernel sources: a counter summary under profiles/ is
+    only used while the kernel it was measured on is the one in the tree."""
+    import hashlib
+    h = hashlib.sha256()
+    for nm in names:
+        with open(os.path.join(ROOT, "paper_1903_06631_amd", "csrc", nm), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def read_profile_values(path):
+    """'key: value' lines of a text summary under profiles/ (comments and tables are skipped)."""
+    import re
+    vals = {}
+    if os.path.exists(path):
+        for ln in open(path):
+            m = re.match(r"^([A-Za-z_0-9]+):\s*(\S+)\s*$", ln)
+            if m:
+                vals[m.group(1)] = m.group(2)
+    return vals
+
+
+# dominant placement kernel of every benchmark configuration: its name, the sources it is built
+# from, and the stem of its counter summaries under profiles/
+PLACE_KERNEL = {
+    5: ("k_place_fast<u32,false>", ("place_fast.hip", "lap_dev.h"), "k_place_fast_transformer_B1024"),
+    4: ("k_place_seg", ("place_seg.hip", "seg_core.h", "lap_dev.h"), "k_place_seg_deepchain_B4096"),
+}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,8 +71,6 @@ def main() -> int:
     ap.add_argument("--no-stress", action="store_true",
                     help="skip the load-profile run on the 2 GiB time-tiled trace")
     ap.add_argument("--no-extras", action="store_true", help="skip the best-fit and selection legs")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build plans on ONE GPU (the orderings are what would shard across GPUs); "
@@ -66,12 +95,22 @@ def main() -> int:
     upload_s = time.perf_counter() - t0
     assert lap.validate_trace(dt) == 0
 
-    if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)     # 1 GiB read + 1 GiB written
-        dst = torch.empty_like(src)
+    # a plain device-to-device copy of 1 GiB, timed in this run: what this GPU's memory system gives
+    # a kernel that does nothing but stream (and the kernel rocprofv3's FETCH_SIZE / WRITE_SIZE
+    # readings are scaled by)
+    src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    copy_ms = []
+    for _ in range(5):
+        ev0.record()
         dst.copy_(src)
+        ev1.record()
         torch.cuda.synchronize()
-        del src, dst
+        copy_ms.append(ev0.elapsed_time(ev1))
+    copy_GBps = 2 * src.numel() * 4 / (float(np.median(copy_ms)) * 1e-3) / 1e9      # bytes read + bytes written
+    del src, dst
 
     out = None
     lap.profile_enable(True)
@@ -104,40 +143,83 @@ def main() -> int:
     best_fp = int(u64(out["best_footprint"])[0])
     fps = u64(out["footprints"])
 
-    # dominant kernel: placement.  Algorithmic bytes per launch: every time-overlapping pair is
-    # examined once per ordering (16 B: the earlier block's offset and end) plus 24 B per variable.
-    alg_bytes = B * (16 * n_edges + 24 * n)
+    # Dominant kernel: placement.  Its duration is measured here (HIP events on the launch stream);
+    # the HBM bytes it moves per launch come from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this same
+    # command, kept under profiles/ with a stamp of the kernel source: if the source has changed
+    # since, the bytes are not used and achieved / frac are null.
     k_ms = float(np.mean(place_ms))
-    achieved = alg_bytes / (k_ms * 1e-3) / 1e9
-    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (separate runs of this
-    # command, calibrated against a plain copy); only valid for the workload it was measured on
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "k_place_fast_transformer_B1024_hbm_traffic.txt")
-    if args.config == 5 and B == 1024 and os.path.exists(tpath):
-        for ln in open(tpath):
-            if ln.startswith("traffic_bytes_per_launch:"):
-                traffic = int(ln.split(":")[1])
-    roofline = dict(bound="hbm", kernel="k_place_fast", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBPS, traffic=traffic, kernel_ms=k_ms, algorithmic_bytes=alg_bytes,
+    k_name, k_src, k_stem = PLACE_KERNEL.get(args.config, ("k_place_*", ("place_fast.hip", "lap_dev.h"), None))
+    traffic, counters = None, {}
+    if k_stem and B == tr.meta["B"]:
+        tv = read_profile_values(os.path.join(ROOT, "profiles", k_stem + "_hbm_traffic.txt"))
+        if tv.get("source_sha256_16") == source_stamp(*k_src) and "traffic_bytes_per_launch" in tv:
+            traffic = int(tv["traffic_bytes_per_launch"])
+            cv = read_profile_values(os.path.join(ROOT, "profiles", k_stem + "_sq_counters.txt"))
+            if cv.get("source_sha256_16") == source_stamp(*k_src):
+                counters = {k: float(v) for k, v in cv.items() if k not in ("source_sha256_16",)}
+    achieved = traffic / (k_ms * 1e-3) / 1e9 if traffic else None
+    # the pair-by-pair model: every time-overlapping pair examined once per ordering (16 B: the earlier
+    # block's offset and end) plus 24 B per variable.  Not a bound for this kernel: per-step hole lists
+    # summarise the one-step neighbours, so it moves fewer bytes than that.
+    pair_bytes = B * (16 * n_edges + 24 * n)
+    roofline = dict(bound="hbm", kernel=k_name, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBPS if achieved else None, traffic=traffic, kernel_ms=k_ms,
+                    limited_by="the dependent memory accesses of one placement (latency and number of scattered "
+                               "requests, see counters), not HBM bandwidth",
+                    counters=counters or None, copy_GBps=copy_GBps,
+                    frac_of_copy=achieved / copy_GBps if achieved else None,
                     sort_kernel_ms=float(np.mean(sort_ms)),
-                    note="achieved = algorithmic bytes (every overlapping pair read once) / kernel time; the kernel "
-                         "moves fewer bytes than that (see traffic): per-step hole lists summarise the one-step "
-                         "neighbours, so frac can exceed 1 and says how far the kernel is ahead of a pair-by-pair "
-                         "kernel running at the HBM peak")
+                    pairwise_model=dict(bytes=pair_bytes, GBps=pair_bytes / (k_ms * 1e-3) / 1e9,
+                                        over_hbm_peak=pair_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                        note="not a bound and not a roofline fraction: bytes a kernel that reads "
+                                             "every overlapping pair would move, over this kernel's time"),
+                    note="achieved = HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/, "
+                         "stamped with the kernel source) / kernel duration measured in this run")
 
+    # The oracle (plain single-threaded C, as it stands) on this machine's host cores, after the timed region.
+    # Leg 1, one thread: the ordering the timed run found best, all N variables -- the paper's planner is
+    # a single-threaded host program that runs one ordering (Section III-C, VI-A).  Leg 2, every hardware
+    # thread this process may use: one ordering per thread.  Both are compared with the TIMED outputs.
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
+        from concurrent.futures import ThreadPoolExecutor
         oracle.build()
-        perm = oracle.make_perm(tr, int(kinds[0]), int(seeds[0]))
+        best_b = int(out["best_ordering"].item())
+        perm = oracle.make_perm(tr, int(kinds[best_b]), int(seeds[best_b]))
         c0 = time.perf_counter()
         o_off, o_fp = oracle.place(tr, perm)
         c_s = time.perf_counter() - c0
-        one = lap.plan_pool(dt, kinds[:1], seeds[:1], want_all=True)
-        assert np.array_equal(u64(one["all_offsets"])[0], o_off), "GPU offsets differ from the oracle"
-        assert int(fps[0]) == o_fp
-        cpu = dict(value=n / c_s, unit="placements/s", cores=1, kind="oracle",
-                   sample=f"first-fit placement of ordering 0 (size-descending), all {n} variables, {c_s:.1f} s")
+        assert np.array_equal(u64(out["best_offsets"]), o_off), "timed GPU offsets differ from the oracle"
+        assert int(fps[best_b]) == o_fp == best_fp
+        cores = max(1, min(16, len(os.sched_getaffinity(0))))
+        nb = B if c_s * B / cores < 20.0 else cores          # all orderings when that takes seconds, else one per thread
+        which = list(range(B)) if nb == B else [4 + i for i in range(cores)] if B >= 4 + cores else list(range(nb))
+
+        def one(b):
+            pm = oracle.make_perm(tr, int(kinds[b]), int(seeds[b]))
+            return b, oracle.place(tr, pm)                   # ctypes releases the GIL during the call
+
+        c0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            res = list(ex.map(one, which))
+        m_s = time.perf_counter() - c0
+        chk = lap.plan_pool(dt, [kinds[b] for b in which], [seeds[b] for b in which], want_all=True)
+        chk_off = u64(chk["all_offsets"])
+        for i, (b, (off_b, fp_b)) in enumerate(res):
+            assert int(fps[b]) == fp_b, f"timed footprint of ordering {b} differs from the oracle"
+            assert np.array_equal(chk_off[i], off_b), f"GPU offsets of ordering {b} differ from the oracle"
+        cpu = dict(value=len(which) * n / m_s, unit="placements/s", cores=cores, kind="oracle",
+                   sample=f"first-fit placement of {len(which)} of the {B} orderings "
+                          f"({'all' if nb == B else 'the seeded orderings ' + str(which[0]) + '..' + str(which[-1])}), "
+                          f"all {n} variables each, one ordering per thread on {cores} threads, {m_s:.1f} s",
+                   full_batch_s_extrapolated=B * n / (len(which) * n / m_s),
+                   extrapolation="linear in the number of orderings (they are independent)",
+                   pair_tests_per_s=len(which) * n_edges / m_s,
+                   single_thread=dict(value=n / c_s, unit="placements/s", cores=1,
+                                      sample=f"first-fit placement of ordering {best_b} (the best of the timed run: "
+                                             f"kind {int(kinds[best_b])}), all {n} variables, {c_s:.1f} s",
+                                      pair_tests_per_s=n_edges / c_s))
 
     # The rows built beyond the timed path (never part of `value`): the same orderings planned
     # best-fit, and the selection walk for all five priority scores down to a sweep of limits.
@@ -232,6 +314,7 @@ def main() -> int:
         "config": {"workload": f"configs[{args.config - 1}] {CONFIG_NAMES[args.config]}-shaped trace",
                    "n_vars": n, "n_steps": T, "orderings": B, "edges": n_edges,
                    "link_GBps": tr.meta["link_GBps"], "trace_bytes": dt.nbytes(), "upload_ms": 1e3 * upload_s},
+        "pair_tests_per_s": B * n_edges * args.steps / total_s,
         "footprint_over_peak": best_fp / peak, "best_ordering": int(out["best_ordering"].item()),
         "footprint_over_peak_fixed_orders": [float(x) / peak for x in fps[:4]],
         "roofline": roofline, "cpu_baseline": cpu, "beyond_the_timed_path": extra,

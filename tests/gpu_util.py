@@ -4,6 +4,7 @@ from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
+# one oracle run per host thread; a GPU machine gives a job 16 CPUs whatever os.cpu_count() says
 WORKERS = max(1, min(16, (os.cpu_count() or 8)))
 
 

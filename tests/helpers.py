@@ -171,3 +171,45 @@ def validate_cases():
     t = base(); t.size[5] = 0; t.size[6] = 1 << 53
     cases.append(("invalid content comes before a range problem", t, -6))
     return cases
+
+
+# ---- the full-size ordering batches and their stored oracle results -------------------------
+# The two largest configurations are planned for every ordering on the GPU; the oracle needs a
+# minute or more per ordering there, so its results are computed ahead of time by
+# tests/golden/make_fullsize_hashes.py (which calls only the oracle) and stored as one line per
+# ordering: footprint and a SHA-256 prefix of the offsets.
+
+def fullsize_batch(cfg):
+    """(kinds, seeds) of the batch planned at full size: the benchmark's own batch (4 fixed orders,
+    then seeded shuffles with seeds 631 + b) with every 64th ordering (b % 64 == 63) turned into a
+    shuffle inside size classes (kind 6) of the same seed, so that every kind is covered."""
+    from traces import make_config, make_orderings
+    B = make_config(cfg).meta["B"]
+    kinds, seeds = make_orderings(B)
+    kinds = kinds.copy()
+    kinds[63::64] = 6
+    return kinds, seeds
+
+
+def offsets_digest(off):
+    """16 hex digits of SHA-256 over the little-endian u64 offsets of one ordering."""
+    import hashlib
+    return hashlib.sha256(np.ascontiguousarray(off, dtype="<u8").tobytes()).hexdigest()[:16]
+
+
+def fullsize_golden_path(cfg, best_fit):
+    return os.path.join(GOLDEN, f"fullsize_cfg{cfg}_{'best' if best_fit else 'first'}_fit.txt")
+
+
+def read_fullsize_golden(cfg, best_fit):
+    """ordering index -> (kind, seed, footprint, digest) for the orderings the oracle has done."""
+    out = {}
+    path = fullsize_golden_path(cfg, best_fit)
+    if not os.path.exists(path):
+        return out
+    with open(path) as fh:
+        for line in fh:
+            line = line.split("#")[0].split()
+            if len(line) == 5:
+                out[int(line[0])] = (int(line[1]), int(line[2]), int(line[3]), line[4])
+    return out

@@ -17,68 +17,114 @@ def lap():
     return lap
 
 
-def _neighbours_disjoint(tr, off, steps):
-    """No two variables alive at the same step share addresses (checked at the given steps)."""
+def _all_neighbours_disjoint(tr, all_off, size_dev, steps, rows=None, chunk_elems=1 << 28):
+    """Section III-B on the device, for many orderings at once: at every given step, the blocks of the
+    variables alive at that step, sorted by offset, do not touch each other's addresses.  Two variables
+    whose lifetimes overlap are both alive at the later of their two first steps, so checking every
+    step at which something is allocated covers every pair.  Returns the number of violations."""
+    import torch
     a, f = tr.alloc.astype(np.int64), tr.free.astype(np.int64)
-    e = off + tr.size
+    order = np.argsort(a, kind="stable")
+    bad = 0
+    off_all = all_off if rows is None else all_off[rows]
     for t in steps:
         live = np.nonzero((a <= t) & (t < f))[0]
-        s = live[np.argsort(off[live], kind="stable")]
-        if np.any(e[s][:-1] > off[s][1:]):
-            return False
-    return True
+        if len(live) < 2:
+            continue
+        idx = torch.from_numpy(live).to(all_off.device)
+        per = max(1, chunk_elems // len(live))
+        for r0 in range(0, off_all.shape[0], per):
+            o = off_all[r0:r0 + per].index_select(1, idx)
+            so, si = torch.sort(o, dim=1)
+            e = so + size_dev[idx][si]
+            bad += int((e[:, :-1] > so[:, 1:]).sum().item())
+    return bad
 
 
-@pytest.mark.parametrize("cfg,sample,step_stride", [(5, [0, 1, 3, 4, 517, 1023], 1), (4, [0, 2, 3, 4, 2048, 4095], 97)])
-def test_full_size_plan(lap, oracle_mod, cfg, sample, step_stride):
+def _digests(all_off, rows, chunk=64):
+    """SHA-256 prefixes of the given orderings' offsets (rows move to the host in chunks)."""
+    from helpers import offsets_digest
+    out = {}
+    for k in range(0, len(rows), chunk):
+        part = rows[k:k + chunk]
+        host = u64(all_off[part])
+        for i, b in enumerate(part):
+            out[b] = offsets_digest(host[i])
+    return out
+
+
+def _full_size(lap, oracle_mod, cfg, best_fit, live_sample, all_steps_rows, step_stride):
+    import torch
+    from helpers import fullsize_batch, read_fullsize_golden
     tr = make_config(cfg)
-    B = tr.meta["B"]
-    kinds, seeds = make_orderings(B)
+    kinds, seeds = fullsize_batch(cfg)
+    B = len(kinds)
+    assert B == tr.meta["B"]
+    fits = [1] * B if best_fit else None
     dt = lap.DeviceTrace(tr)
-    got = lap.plan_pool(dt, kinds, seeds)
+    got = lap.plan_pool(dt, kinds, seeds, fits=fits)
     fps = u64(got["footprints"])
     best = int(got["best_ordering"].item())
     all_off = got["all_offsets"]
-    # sampled orderings, element by element
-    ref = oracle_all_orderings(oracle_mod, tr, kinds, seeds, which=sample)
+
+    # 1. every ordering the oracle has been run on ahead of time (stored footprint and digest of the
+    #    offsets, written by tests/golden/make_fullsize_hashes.py from the oracle alone)
+    gold = read_fullsize_golden(cfg, best_fit)
+    assert len(gold) >= 64, f"stored oracle results for cfg {cfg}: {len(gold)}"
+    assert {0, 1, 2, 3, 4, 6} <= {g[0] for g in gold.values()}, "every ordering kind is among them"
+    rows = sorted(gold)
+    for b in rows:
+        assert (int(kinds[b]), int(seeds[b])) == gold[b][:2], f"ordering {b} is not the one the oracle ran"
+    dig = _digests(all_off, rows)
+    wrong = [b for b in rows if dig[b] != gold[b][3] or int(fps[b]) != gold[b][2]]
+    assert not wrong, f"cfg {cfg}: {len(wrong)} of {len(rows)} orderings differ from the oracle, first {wrong[:8]}"
+
+    # 2. a live sample recomputed by the oracle now (one ordering per host thread), element by element
+    ref = oracle_all_orderings(oracle_mod, tr, kinds, seeds, which=live_sample, fits=fits)
     for b, (_, off, fp) in ref.items():
         assert np.array_equal(u64(all_off[b]), off), f"cfg {cfg} ordering {b}"
         assert fps[b] == fp
-    # every ordering: footprint = highest block end, never below the peak load (Eq. 2)
+        if b in gold:
+            from helpers import offsets_digest
+            assert offsets_digest(off) == gold[b][3] and fp == gold[b][2]     # the stored line is this oracle's
+
+    # 3. every ordering: footprint = highest block end, never below the peak load (Eq. 2); the best one
     _, peak, _ = oracle_mod.load_profile(tr)
-    size_dev = dt.size
-    top = (all_off + size_dev[None, :]).max(dim=1).values        # sums stay far below 2^63
+    top = (all_off + dt.size[None, :]).max(dim=1).values        # sums stay far below 2^63
     assert np.array_equal(u64(top), fps)
     assert (fps >= peak).all()
     assert best == int(np.argmin(fps)) and int(u64(got["best_footprint"])[0]) == int(fps.min())
     assert np.array_equal(u64(got["best_offsets"]), u64(all_off[best]))
-    # validity of orderings the oracle did not recompute
-    steps = range(0, tr.n_steps, step_stride)
-    for b in (best, 7, B // 2 + 1):
-        assert _neighbours_disjoint(tr, u64(all_off[b]), steps), f"cfg {cfg} ordering {b}"
+
+    # 4. every ordering: no two variables alive together share addresses
+    alloc_steps = np.unique(tr.alloc)
+    if step_stride == 1:
+        assert _all_neighbours_disjoint(tr, all_off, dt.size, alloc_steps) == 0
+    else:
+        assert _all_neighbours_disjoint(tr, all_off, dt.size, alloc_steps[::step_stride]) == 0
+        rws = torch.tensor(sorted(set(all_steps_rows) | {best}), device=all_off.device)
+        assert _all_neighbours_disjoint(tr, all_off, dt.size, alloc_steps, rows=rws) == 0
+    return len(rows)
 
 
-def test_full_size_best_fit(lap, oracle_mod):
-    """Config 5 with every ordering planned best-fit: sampled orderings against the oracle, the
-    invariants on all of them."""
-    tr = make_config(5)
-    B = tr.meta["B"]
-    kinds, seeds = make_orderings(B)
-    dt = lap.DeviceTrace(tr)
-    got = lap.plan_pool(dt, kinds, seeds, fits=[1] * B)
-    fps = u64(got["footprints"])
-    all_off = got["all_offsets"]
-    sample = [0, 3, 4, 700]
-    ref = oracle_all_orderings(oracle_mod, tr, kinds, seeds, which=sample, fits=[1] * B)
-    for b, (_, off, fp) in ref.items():
-        assert np.array_equal(u64(all_off[b]), off), f"ordering {b}"
-        assert fps[b] == fp
-    _, peak, _ = oracle_mod.load_profile(tr)
-    top = (all_off + dt.size[None, :]).max(dim=1).values
-    assert np.array_equal(u64(top), fps) and (fps >= peak).all()
-    best = int(got["best_ordering"].item())
-    for b in (best, 9, B - 1):
-        assert _neighbours_disjoint(tr, u64(all_off[b]), range(tr.n_steps)), f"ordering {b}"
+def test_full_size_plan_transformer(lap, oracle_mod):
+    """Config 5, the benchmark's launch: 1024 orderings of 200 000 variables."""
+    _full_size(lap, oracle_mod, 5, False, live_sample=[0, 1, 2, 3, 63, 127, 4, 5, 100, 333, 517, 640, 777, 901, 1000, 1023],
+               all_steps_rows=[], step_stride=1)
+
+
+def test_full_size_plan_deep_chain(lap, oracle_mod):
+    """Config 4: 4096 orderings of 50 000 variables on 14 000 steps (dense interval graph; the segment-list
+    kernel).  The pairwise check runs on every 61st allocation step for all orderings and on every step
+    for 16 of them.  (Best-fit is not run at this size: on a dense trace it looks at thousands of holes per
+    variable and takes minutes per ordering.)"""
+    _full_size(lap, oracle_mod, 4, False, live_sample=[0, 1, 2, 3, 63, 127, 4, 9, 800, 1500, 2048, 2600, 3100, 3600, 4000, 4095],
+               all_steps_rows=list(range(5, 4096, 273)), step_stride=61)
+
+
+def test_full_size_best_fit_transformer(lap, oracle_mod):
+    """Config 5 with every ordering planned best-fit."""
+    _full_size(lap, oracle_mod, 5, True, live_sample=[0, 1, 2, 3, 63, 4, 6, 200, 700, 1023], all_steps_rows=[], step_stride=1)
 
 
 def test_full_size_plan_and_replay_of_swaps(lap, oracle_mod):
