@@ -135,6 +135,7 @@ def main() -> int:
         sort_ms.append(lap.profile_last_ms(lap.K_SORT))
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
+    ord_ms = lap.profile_ordering_ms(dt, B)          # how long the last launch worked on each ordering
     ms_per_step = 1e3 * total_s / args.steps
     value = B * n * args.steps / total_s
 
@@ -167,6 +168,10 @@ def main() -> int:
                     limited_by="the dependent memory accesses of one placement (latency and number of scattered "
                                "requests, see counters), not HBM bandwidth",
                     counters=counters or None, copy_GBps=copy_GBps,
+                    # the launch ends with its slowest ordering
+                    ordering_ms=dict(min=float(ord_ms.min()), median=float(np.median(ord_ms)), mean=float(ord_ms.mean()),
+                                     p90=float(np.percentile(ord_ms, 90)), max=float(ord_ms.max()),
+                                     slowest=int(ord_ms.argmax()), fixed_orders=[float(x) for x in ord_ms[:4]]),
                     frac_of_copy=achieved / copy_GBps if achieved else None,
                     sort_kernel_ms=float(np.mean(sort_ms)),
                     pairwise_model=dict(bytes=pair_bytes, GBps=pair_bytes / (k_ms * 1e-3) / 1e9,

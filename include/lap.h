@@ -329,6 +329,12 @@ int lap_set_option(int option, uint64_t value);
 enum { LAP_K_LOAD_SCATTER = 0, LAP_K_PLACE = 1, LAP_K_SCORE = 2, LAP_K_SORT = 3, LAP_K_SELECT = 4, LAP_K_COUNT = 5 };
 int lap_profile_enable(int on);
 float lap_profile_last_ms(int kernel_id);
+/* How long the placement kernel worked on every ordering of the last lap_plan_pool call that used
+ * this workspace with these n_vars, n_steps and B (always recorded, by the device's constant-rate
+ * timer): the launch ends with its slowest ordering.  Waits for the stream.
+ *   ms_host [B] HOST out */
+int lap_profile_ordering_ms(uint32_t n_vars, uint32_t n_steps, uint32_t B, const void *ws, size_t ws_bytes,
+                            void *hip_stream, float *ms_host);
 
 #ifdef __cplusplus
 }

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     plan_pool,
     profile_enable,
     profile_last_ms,
+    profile_ordering_ms,
     schedule_swaps,
     score_swaps,
     select_swaps,

@@ -14,7 +14,7 @@ _lib = None
 EXPORTS = [
     "lap_workspace_bytes", "lap_load_profile", "lap_load_profile_static", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
     "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps", "lap_evaluate_weights",
-    "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms", "lap_set_option",
+    "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms", "lap_profile_ordering_ms", "lap_set_option",
 ]
 
 
@@ -92,6 +92,9 @@ def load_library():
     lib.lap_set_option.argtypes = [C.c_int, C.c_uint64]
     lib.lap_profile_enable.restype = C.c_int
     lib.lap_profile_enable.argtypes = [C.c_int]
+    lib.lap_profile_ordering_ms.restype = C.c_int
+    lib.lap_profile_ordering_ms.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                            C.c_void_p]
     lib.lap_profile_last_ms.restype = C.c_float
     lib.lap_profile_last_ms.argtypes = [C.c_int]
     _lib = lib
@@ -122,6 +125,17 @@ def profile_enable(on: bool) -> None:
 
 def profile_last_ms(kernel_id: int) -> float:
     return float(load_library().lap_profile_last_ms(kernel_id))
+
+
+def profile_ordering_ms(dt, B: int) -> np.ndarray:
+    """lap_profile_ordering_ms: per-ordering duration (ms) of the last plan_pool call on this trace with B orderings."""
+    ws, need = dt.workspace(1, B)
+    out = np.zeros(B, np.float32)
+    rc = load_library().lap_profile_ordering_ms(dt.n_vars, dt.n_steps, B, ws.data_ptr(), need, _stream_ptr(dt.device),
+                                                out.ctypes.data_as(C.c_void_p))
+    if rc:
+        raise LapError(rc, "lap_profile_ordering_ms")
+    return out
 
 
 def _torch():

@@ -59,7 +59,7 @@ size_t ws_plan(uint32_t n, uint32_t T, uint32_t B)
 {
     const size_t bn = (size_t)B * n;
     return up(sizeof(lap::PlanHeader)) + 2 * up(((size_t)T + 2) * 4)   // header, step counts, list starts
-           + 2 * up((size_t)B * 4) + up((size_t)B * 8)                // kinds, fit policies, seeds
+           + 2 * up((size_t)B * 4) + 2 * up((size_t)B * 8)            // kinds, fit policies, seeds, durations
            + 2 * up(bn * 4)                                            // perm, sort scratch
            + up((size_t)B * 8)                                         // footprints
            + up((size_t)n * 16)                                        // packed variable records
@@ -274,6 +274,34 @@ int lap_profile_enable(int on)
     return LAP_OK;
 }
 
+int lap_profile_ordering_ms(uint32_t n_vars, uint32_t n_steps, uint32_t B, const void *ws, size_t ws_bytes,
+                            void *hip_stream, float *ms_host)
+{
+    if (!ms_host) return LAP_E_NULL;
+    if (n_vars == 0 || n_steps == 0 || B == 0) return LAP_E_SIZE;
+    const int rc = check_ws(const_cast<void *>(ws), ws_bytes, ws_plan(n_vars, n_steps, B));
+    if (rc) return rc;
+    // same steps as lap_plan_pool takes to its `ticks` region
+    Carver c(const_cast<void *>(ws));
+    c.take<lap::PlanHeader>(1);
+    c.take<uint32_t>((size_t)n_steps + 2);
+    c.take<uint32_t>((size_t)n_steps + 2);
+    c.take<uint32_t>(B);
+    c.take<uint32_t>(B);
+    c.take<uint64_t>(B);
+    const uint64_t *ticks = c.take<uint64_t>(B);
+    std::vector<uint64_t> h(B);
+    hipStream_t st = (hipStream_t)hip_stream;
+    LAP_HIP(hipMemcpyAsync(h.data(), ticks, (size_t)B * 8, hipMemcpyDeviceToHost, st));
+    LAP_HIP(hipStreamSynchronize(st));
+    int dev = 0, khz = 0;
+    LAP_HIP(hipGetDevice(&dev));
+    LAP_HIP(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) return LAP_E_HIP;
+    for (uint32_t b = 0; b < B; ++b) ms_host[b] = (float)((double)h[b] / (double)khz);
+    return LAP_OK;
+}
+
 float lap_profile_last_ms(int id)
 {
     if (id < 0 || id >= LAP_K_COUNT || !g_ev_used[id]) return -1.0f;
@@ -342,6 +370,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint32_t *kinds = c.take<uint32_t>(B);
     uint32_t *fits = c.take<uint32_t>(B);
     uint64_t *seeds = c.take<uint64_t>(B);
+    uint64_t *ticks = c.take<uint64_t>(B);          // (lap_profile_ordering_ms finds them by the same steps)
     uint32_t *perm = c.take<uint32_t>(bn);
     uint32_t *tmp = c.take<uint32_t>(bn);
     uint64_t *fps_ws = c.take<uint64_t>(B);
@@ -401,11 +430,11 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
         ProfScope p(LAP_K_PLACE, st);
         LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, fits, any_first, any_best, hdr, vrec,
                                        lstart, f_oe, f_life, f_oe2,
-                                       f_life2, f_roe, f_rlife, f_roe2, f_rlife2, f_L, capL, l_ns, l_nu, offs, fps, st));
+                                       f_life2, f_roe, f_rlife, f_roe2, f_rlife2, f_L, capL, l_ns, l_nu, offs, fps, ticks, st));
         LAP_HIP(lap::launch_place_wide(n, B, tr->size, tr->alloc, tr->free_, perm, fits, hdr, m_off, m_end, m_life, offs,
-                                       fps, st));
+                                       fps, ticks, st));
         LAP_HIP(lap::launch_place_seg(n, T, B, perm, fits, any_first, hdr, vrec, seg_lst, seg_pool, seg_len,
-                                      (uint32_t)dir_cap, offs, fps, st));
+                                      (uint32_t)dir_cap, offs, fps, ticks, st));
     }
     LAP_HIP(lap::launch_select(n, B, fps, offs, perm, best_footprint, best_ordering, best_offsets, all_offsets, st));
     return LAP_OK;

@@ -55,19 +55,21 @@ hipError_t launch_seg_prep(uint32_t n, uint32_t T, uint32_t B, const uint32_t *a
 hipError_t launch_place_seg(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
                             bool any_first, const PlanHeader *hdr, const void *vrec, const uint32_t *lst,
                             uint64_t *pool, uint32_t *lens, uint32_t dir_cap, uint64_t *offs, uint64_t *fps,
-                            hipStream_t st);
+                            uint64_t *ticks, hipStream_t st);
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits, bool any_first,
                              bool any_best, PlanHeader *hdr, const void *vrec,
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,
-                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st);
+                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, uint64_t *ticks,
+                             hipStream_t st);
 constexpr uint32_t PLAN_REC = 4096;   // entries of the sorted "recent" list per ordering
 hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc,
                              const uint32_t *free_, const uint32_t *perm, const uint32_t *fits,
                              const PlanHeader *hdr, uint64_t *m_off,
-                             uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st);
+                             uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, uint64_t *ticks,
+                             hipStream_t st);
 hipError_t launch_select(uint32_t n, uint32_t B, const uint64_t *fps, const uint64_t *offs_rank, const uint32_t *perm,
                          uint64_t *best_fp, uint32_t *best_idx, uint64_t *best_offsets, uint64_t *all_offsets,
                          hipStream_t st);

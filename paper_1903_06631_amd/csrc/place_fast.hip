@@ -495,6 +495,7 @@ struct FastArgs {
     uint64_t capL;
     uint64_t *offs;              // [B][n] in rank order
     uint64_t *fps;               // [B]
+    uint64_t *ticks;             // [B] duration of every ordering in timer ticks
 };
 
 constexpr int COOP_U = 4;                    // chunks per wave in one cooperative round
@@ -925,6 +926,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     if (A.hdr->mode2 && !BEST) return;      // the segment kernel places the first-fit orderings of this trace
     const uint32_t b = blockIdx.x;
     if ((A.fits[b] != 0) != BEST) return;   // the other instantiation handles this ordering
+    const long long t_begin = wall_clock64();
     const bool mode1 = A.hdr->mode1 != 0;
     const uint32_t sh = A.hdr->shift;
     const int l = lane_id();
@@ -1342,6 +1344,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         uint32_t m = s_fp[0];
         for (int w = 1; w < PW; ++w) m = max(m, s_fp[w]);
         A.fps[b] = (uint64_t)m << sh;
+        A.ticks[b] = (uint64_t)(wall_clock64() - t_begin);
     }
 }
 
@@ -1364,12 +1367,13 @@ hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t 
                              const uint32_t *lstart, uint64_t *m_oe, uint64_t *m_life, uint64_t *m_oe2,
                              uint64_t *m_life2, uint64_t *r_oe, uint64_t *r_life, uint64_t *r_oe2,
                              uint64_t *r_life2, uint64_t *L, uint64_t capL,
-                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, hipStream_t st)
+                             uint32_t *l_ns, uint32_t *l_nu, uint64_t *offs, uint64_t *fps, uint64_t *ticks,
+                             hipStream_t st)
 {
     FastArgs A{n, T, size, alloc, free_, (const uint4 *)vrec, perm, fits, hdr, lstart, {m_oe, m_oe2}, {m_life, m_life2}, {r_oe, r_oe2}, {r_life, r_life2},
                L, l_ns,
                l_nu, capL,
-               offs, fps};
+               offs, fps, ticks};
     // each instantiation leaves the orderings of the other policy alone
     if (T <= 0xFFFFu) {
         if (any_first) hipLaunchKernelGGL((k_place_fast<uint32_t, false>), dim3(B), dim3(PW * WAVE), 0, st, A);

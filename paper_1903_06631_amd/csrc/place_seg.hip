@@ -118,6 +118,7 @@ struct SegArgs {
     uint32_t dir_cap;
     uint64_t *offs;              // [B][n] in rank order
     uint64_t *fps;               // [B]
+    uint64_t *ticks;             // [B] duration of every ordering in timer ticks
 };
 
 __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
@@ -139,6 +140,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
 
     for (uint32_t b = blockIdx.x; b < A.B; b += slots) {
         if (A.fits[b] != 0) continue;                // best-fit orderings: the sweep kernel places them
+        const long long t_begin = wall_clock64();
         const uint32_t *perm = A.perm + (size_t)b * n;
         uint64_t *offs = A.offs + (size_t)b * n;
         // every list starts as one range: the whole address space
@@ -200,7 +202,10 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 __syncthreads();
             }
         }
-        if (tid == 0) A.fps[b] = (uint64_t)fp << sh;
+        if (tid == 0) {
+            A.fps[b] = (uint64_t)fp << sh;
+            A.ticks[b] = (uint64_t)(wall_clock64() - t_begin);
+        }
         __syncthreads();
     }
 }
@@ -221,9 +226,9 @@ hipError_t launch_seg_prep(uint32_t n, uint32_t T, uint32_t B, const uint32_t *a
 hipError_t launch_place_seg(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
                             bool any_first, const PlanHeader *hdr, const void *vrec, const uint32_t *lst,
                             uint64_t *pool, uint32_t *lens, uint32_t dir_cap, uint64_t *offs, uint64_t *fps,
-                            hipStream_t st)
+                            uint64_t *ticks, hipStream_t st)
 {
-    SegArgs A{n, T, B, (const uint4 *)vrec, perm, fits, hdr, lst, pool, lens, dir_cap, offs, fps};
+    SegArgs A{n, T, B, (const uint4 *)vrec, perm, fits, hdr, lst, pool, lens, dir_cap, offs, fps, ticks};
     if (any_first) hipLaunchKernelGGL(k_place_seg, dim3(B), dim3(SEG_THREADS), 0, st, A);
     return hipGetLastError();
 }

@@ -178,10 +178,12 @@ __global__ __launch_bounds__(64) void k_place_wide(uint32_t n, const uint64_t *_
                                               const uint32_t *__restrict__ fits,
                                               const PlanHeader *__restrict__ hdr,
                                               uint64_t *m_off_all, uint64_t *m_end_all, uint64_t *m_life_all,
-                                              uint64_t *__restrict__ offs_all, uint64_t *__restrict__ fps)
+                                              uint64_t *__restrict__ offs_all, uint64_t *__restrict__ fps,
+                                              uint64_t *__restrict__ ticks)
 {
     __shared__ uint64_t r_off[RECENT], r_end[RECENT], r_life[RECENT];
     if (hdr->fast) return;                 // the 32-bit granule kernel handles this trace
+    const long long t_begin = wall_clock64();
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
     const bool best_fit = fits[b] != 0;
@@ -234,7 +236,10 @@ __global__ __launch_bounds__(64) void k_place_wide(uint32_t n, const uint64_t *_
             nr = 0;
         }
     }
-    if (l == 0) fps[b] = fp;
+    if (l == 0) {
+        fps[b] = fp;
+        ticks[b] = (uint64_t)(wall_clock64() - t_begin);      // how long this ordering took, in timer ticks
+    }
 }
 
 // best = lowest index among the smallest footprints
@@ -292,10 +297,11 @@ __global__ __launch_bounds__(256) void k_unpermute(uint32_t n, const uint64_t *_
 
 hipError_t launch_place_wide(uint32_t n, uint32_t B, const uint64_t *size, const uint32_t *alloc, const uint32_t *free_,
                         const uint32_t *perm, const uint32_t *fits, const PlanHeader *hdr, uint64_t *m_off,
-                        uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, hipStream_t st)
+                        uint64_t *m_end, uint64_t *m_life, uint64_t *offs, uint64_t *fps, uint64_t *ticks,
+                        hipStream_t st)
 {
     hipLaunchKernelGGL(k_place_wide, dim3(B), dim3(WAVE), 0, st, n, size, alloc, free_, perm, fits, hdr, m_off,
-                       m_end, m_life, offs, fps);
+                       m_end, m_life, offs, fps, ticks);
     return hipGetLastError();
 }
 

@@ -300,3 +300,16 @@ def test_validate_trace(lap, oracle_mod):
     for name, t, status in validate_cases():
         assert oracle_mod.validate_trace(t) == status, name
         assert lap.validate_trace(lap.DeviceTrace(t)) == status, name
+
+
+def test_profile_ordering_ms(lap, oracle_mod):
+    """The per-ordering durations of the last launch: one positive value per ordering, none longer than the launch."""
+    tr = make_config(2)
+    kinds, seeds = make_orderings(tr.meta["B"])
+    dt = lap.DeviceTrace(tr)
+    lap.profile_enable(True)
+    lap.plan_pool(dt, kinds, seeds, fits=[b % 2 for b in range(len(kinds))])
+    ms = lap.profile_ordering_ms(dt, len(kinds))
+    launch = lap.profile_last_ms(lap.K_PLACE)
+    lap.profile_enable(False)
+    assert ms.shape == (len(kinds),) and (ms > 0).all() and ms.max() <= launch * 1.05 + 0.05
