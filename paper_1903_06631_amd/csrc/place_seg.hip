@@ -159,7 +159,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 const uint32_t a = read_lane(rec.x, (int)p), f = read_lane(rec.y, (int)p), s = read_lane(rec.z, (int)p);
                 const SegSpan sp = seg_span(g, a, f);
                 const uint32_t nq = sp.n_query(), nu = sp.n_update();
-                const bool longv = f - a > 1;         // long-lived blocks sit high, one-step ones low
+                const bool longv = f - a > 1;         // long-lived blocks end up high, one-step ones low
                 // lowest address that is free in every list of the variable: every thread asks its
                 // lists for their lowest fit at or above the candidate, the maximum is the next
                 // candidate, until no list moves it
@@ -171,11 +171,25 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                     for (uint32_t i = tid; i < nq; i += SEG_THREADS, ++j) {
                         const uint32_t id = seg_query_list(g, sp, i);
                         const uint32_t len = lens[id];
-                        // where to look first: where this list answered in the round before; else
-                        // at the top for a long-lived variable, at the bottom for a one-step one
-                        uint32_t idx = longv ? len - 1 : 0u, he;
-                        if (have && j < SEG_MEMO) idx = memo[j];
-                        const uint32_t x = seg_fit(pool + lst[id], len, o, s, idx, he);
+                        // Where to look first.  The first round asks from address 0 and is answered
+                        // low in the list.  Later rounds: where this list answered before, or, for a
+                        // long-lived variable whose candidate has jumped up, further up at the
+                        // place the candidate would have if the holes were spread evenly below the
+                        // list's top (one read for the top; it saves most of the climb: a third
+                        // fewer list reads in all).
+                        const uint64_t *L = pool + lst[id];
+                        uint32_t idx = 0, he;
+                        if (have) {
+                            if (j < SEG_MEMO) idx = memo[j];
+                            if (longv && len > 8) {
+                                const uint32_t top = seg_start(L[len - 1]);
+                                if (top) {
+                                    const uint64_t at = (uint64_t)len * ((uint64_t)o + s) / top;
+                                    idx = max(idx, (uint32_t)(at < len - 1 ? at : len - 1));
+                                }
+                            }
+                        }
+                        const uint32_t x = seg_fit(L, len, o, s, idx, he);
                         if (j < SEG_MEMO) memo[j] = idx;
                         best = max(best, x);
                     }
