@@ -318,8 +318,14 @@ const char *lap_status_string(int status);
  *       trace has at least this many variables (default 32768) and the workspace has room for
  *       them, else a sweep over the sorted list of placed blocks.  All three give the same
  *       offsets.  0 = segment lists whenever they apply.
- * Returns LAP_E_ORDERING for an unknown option. */
-enum { LAP_OPT_SEG_MIN_VARS = 0 };
+ *   LAP_OPT_SEG_TRIAL_PERCENT  whether the segment lists pay also depends on how their searches
+ *       converge (two to three rounds on traces with nested lifetimes, as a training iteration
+ *       has; six to eight with lifetimes at random, where the sweep is faster).  Before they are
+ *       used, one workgroup places the first 2048 variables of the first first-fit ordering with
+ *       them and counts the rounds of the multi-step variables; above this many rounds per
+ *       variable, times 100 (default 250), the sweep places the trace.  0 = no trial.
+ * Returns LAP_E_ORDERING for an unknown option or value. */
+enum { LAP_OPT_SEG_MIN_VARS = 0, LAP_OPT_SEG_TRIAL_PERCENT = 1 };
 int lap_set_option(int option, uint64_t value);
 
 /* Optional kernel timing for benchmarks.  When enabled, each call brackets

@@ -7,7 +7,9 @@ call fails, an exception is raised.
 """
 from .binding import (  # noqa: F401
     OPT_SEG_MIN_VARS,
+    OPT_SEG_TRIAL_PERCENT,
     SEG_MIN_VARS_DEFAULT,
+    SEG_TRIAL_PERCENT_DEFAULT,
     DeviceTrace,
     LapError,
     detect_iteration,

@@ -110,7 +110,9 @@ def workspace_bytes(which: int, n_vars: int, n_steps: int, B: int = 0) -> int:
 
 
 OPT_SEG_MIN_VARS = 0
+OPT_SEG_TRIAL_PERCENT = 1
 SEG_MIN_VARS_DEFAULT = 32768
+SEG_TRIAL_PERCENT_DEFAULT = 250
 
 
 def set_option(option: int, value: int) -> None:

@@ -142,6 +142,9 @@ int check_ws(void *ws, size_t have, size_t need)
 
 // lap_set_option(LAP_OPT_SEG_MIN_VARS): variables from which on the segment lists are used
 uint64_t g_seg_min_vars = 32768;
+// lap_set_option(LAP_OPT_SEG_TRIAL_PERCENT): search rounds per multi-step variable (times 100) in the
+// trial run above which the segment lists are not used; 0 = no trial
+uint64_t g_seg_trial_percent = 250;
 
 bool g_prof = false;
 hipEvent_t g_ev[LAP_K_COUNT][2];
@@ -262,8 +265,9 @@ const char *lap_status_string(int s)
 
 int lap_set_option(int option, uint64_t value)
 {
-    if (option != LAP_OPT_SEG_MIN_VARS) return LAP_E_ORDERING;
-    g_seg_min_vars = value;
+    if (option == LAP_OPT_SEG_MIN_VARS) g_seg_min_vars = value;
+    else if (option == LAP_OPT_SEG_TRIAL_PERCENT && value <= 0xFFFFFFFFull) g_seg_trial_percent = value;
+    else return LAP_E_ORDERING;
     return LAP_OK;
 }
 
@@ -427,7 +431,12 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_ns, ((size_t)B * T + 1) / 2, 0, st));
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_nu, ((size_t)B * T + 1) / 2, 0, st));
     {
+        int trial_b = -1;                   // the first first-fit ordering shows how the segment lists' searches go
+        for (uint32_t b = 0; b < B && trial_b < 0; ++b)
+            if (ords[b].fit == LAP_FIT_FIRST) trial_b = (int)b;
         ProfScope p(LAP_K_PLACE, st);
+        LAP_HIP(lap::launch_seg_trial(n, T, B, perm, fits, trial_b, (uint32_t)g_seg_trial_percent, hdr, vrec, seg_lst,
+                                      seg_pool, seg_len, (uint32_t)dir_cap, offs, fps, ticks, st));
         LAP_HIP(lap::launch_place_fast(n, T, B, tr->size, tr->alloc, tr->free_, perm, fits, any_first, any_best, hdr, vrec,
                                        lstart, f_oe, f_life, f_oe2,
                                        f_life2, f_roe, f_rlife, f_roe2, f_rlife2, f_L, capL, l_ns, l_nu, offs, fps, ticks, st));

@@ -28,6 +28,8 @@ struct PlanHeader {
     uint32_t seg_slots;            // orderings that have room in the list pool at once
     unsigned long long seg_need;   // list entries one ordering needs
     unsigned long long seg_tot[PLAN_SEG_CAND];   // per candidate width: blocks entered into lists, summed over the variables
+    uint32_t seg_trial_rounds;     // trial run: search rounds of its multi-step variables, summed
+    uint32_t seg_trial_vars;       // ... and how many those were
 };
 constexpr uint32_t PLAN_CL = 6;
 
@@ -52,8 +54,14 @@ hipError_t launch_plan_prep(uint32_t n, uint32_t T, uint32_t B, const uint64_t *
 hipError_t launch_seg_prep(uint32_t n, uint32_t T, uint32_t B, const uint32_t *alloc, const uint32_t *free_,
                            PlanHeader *hdr, uint32_t *cnt, uint32_t *lst, uint32_t dir_cap, uint64_t pool_entries,
                            hipStream_t st);
+// trial_b: ordering whose first ranks are placed ahead of time to see how the searches go (negative:
+// no trial); trial_percent: rounds per multi-step variable, times 100, above which the sweep is kept
+hipError_t launch_seg_trial(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
+                            int trial_b, uint32_t trial_percent, PlanHeader *hdr, const void *vrec, const uint32_t *lst,
+                            uint64_t *pool, uint32_t *lens, uint32_t dir_cap, uint64_t *offs, uint64_t *fps,
+                            uint64_t *ticks, hipStream_t st);
 hipError_t launch_place_seg(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
-                            bool any_first, const PlanHeader *hdr, const void *vrec, const uint32_t *lst,
+                            bool any_first, PlanHeader *hdr, const void *vrec, const uint32_t *lst,
                             uint64_t *pool, uint32_t *lens, uint32_t dir_cap, uint64_t *offs, uint64_t *fps,
                             uint64_t *ticks, hipStream_t st);
 hipError_t launch_place_fast(uint32_t n, uint32_t T, uint32_t B, const uint64_t *size, const uint32_t *alloc,

@@ -111,7 +111,7 @@ struct SegArgs {
     const uint4 *vrec;           // [n] (first step, end of life, size in granules, -)
     const uint32_t *perm;        // [B][n]
     const uint32_t *fits;        // [B]
-    const PlanHeader *hdr;
+    PlanHeader *hdr;
     const uint32_t *lst;         // [n_lists + 1] start of every list inside a slot
     uint64_t *pool;              // [slots][seg_need]
     uint32_t *lens;              // [slots][dir_cap]
@@ -119,30 +119,42 @@ struct SegArgs {
     uint64_t *offs;              // [B][n] in rank order
     uint64_t *fps;               // [B]
     uint64_t *ticks;             // [B] duration of every ordering in timer ticks
+    int trial_b;                 // >= 0: trial run on the first ranks of this ordering, one workgroup
+    uint32_t trial_percent;
 };
 
+// Whether these lists pay depends on how the searches converge, which depends on the trace: with
+// nested lifetimes and a tight packing (a training iteration) two to three rounds, with lifetimes
+// at random six to eight, and then the sweep over the sorted blocks is the faster way.  So the
+// first ranks of one ordering are placed ahead of time by one workgroup (TRIAL = true), counting
+// the rounds of the multi-step variables; above `trial_percent` / 100 rounds per variable the
+// trace is handed back to the sweep (mode2 = 0), before any placement kernel looks at that flag.
+constexpr uint32_t SEG_TRIAL_RANKS = 2048;
+
+template <bool TRIAL>
 __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
 {
     __shared__ uint32_t s_max[2][SEG_WAVES];
 
-    const PlanHeader *hdr = A.hdr;
+    PlanHeader *hdr = A.hdr;
     if (!hdr->mode2) return;
-    const uint32_t slots = hdr->seg_slots;
+    const uint32_t slots = TRIAL ? 1u : hdr->seg_slots;
     if (blockIdx.x >= slots) return;
     const SegGeom g{hdr->seg_shift, hdr->seg_K, A.T};
     const uint32_t nl = g.n_lists();
     const uint32_t sh = hdr->shift;
-    const uint32_t n = A.n;
+    const uint32_t n = TRIAL ? min(A.n, SEG_TRIAL_RANKS) : A.n;
     const uint32_t tid = threadIdx.x, l = tid & (WAVE - 1), wave = tid / WAVE;
+    uint32_t trial_rounds = 0, trial_vars = 0;
     uint64_t *pool = A.pool + (size_t)blockIdx.x * hdr->seg_need;
     uint32_t *lens = A.lens + (size_t)blockIdx.x * A.dir_cap;
     const uint32_t *__restrict__ lst = A.lst;
 
-    for (uint32_t b = blockIdx.x; b < A.B; b += slots) {
+    for (uint32_t b = TRIAL ? (uint32_t)A.trial_b : blockIdx.x; b < A.B; b += TRIAL ? A.B : slots) {
         if (A.fits[b] != 0) continue;                // best-fit orderings: the sweep kernel places them
         const long long t_begin = wall_clock64();
-        const uint32_t *perm = A.perm + (size_t)b * n;
-        uint64_t *offs = A.offs + (size_t)b * n;
+        const uint32_t *perm = A.perm + (size_t)b * A.n;
+        uint64_t *offs = A.offs + (size_t)b * A.n;
         // every list starts as one range: the whole address space
         for (uint32_t j = tid; j < nl; j += SEG_THREADS) {
             pool[lst[j]] = seg_pack(0u, SEG_INF);
@@ -199,9 +211,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                     __syncthreads();
                     best = max(max(s_max[flip][0], s_max[flip][1]), max(s_max[flip][2], s_max[flip][3]));
                     flip ^= 1;
+                    if (TRIAL && longv) ++trial_rounds;
                     if (best == o) break;             // every list accepts o
                     o = best;
                 }
+                if (TRIAL && longv) ++trial_vars;
                 const uint32_t en = o + s;
                 fp = max(fp, en);
                 if (tid == 0) offs[r0 + p] = (uint64_t)o << sh;      // rank order; un-permuted at the end
@@ -216,11 +230,17 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 __syncthreads();
             }
         }
-        if (tid == 0) {
+        if (tid == 0 && !TRIAL) {
             A.fps[b] = (uint64_t)fp << sh;
             A.ticks[b] = (uint64_t)(wall_clock64() - t_begin);
         }
         __syncthreads();
+    }
+    if (TRIAL && tid == 0) {
+        hdr->seg_trial_rounds = trial_rounds;
+        hdr->seg_trial_vars = trial_vars;
+        // (a handful of variables says nothing: then the lists stay)
+        if (trial_vars >= 32 && (uint64_t)trial_rounds * 100 > (uint64_t)trial_vars * A.trial_percent) hdr->mode2 = 0;
     }
 }
 
@@ -237,13 +257,25 @@ hipError_t launch_seg_prep(uint32_t n, uint32_t T, uint32_t B, const uint32_t *a
     return hipGetLastError();
 }
 
-hipError_t launch_place_seg(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
-                            bool any_first, const PlanHeader *hdr, const void *vrec, const uint32_t *lst,
+hipError_t launch_seg_trial(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
+                            int trial_b, uint32_t trial_percent, PlanHeader *hdr, const void *vrec, const uint32_t *lst,
                             uint64_t *pool, uint32_t *lens, uint32_t dir_cap, uint64_t *offs, uint64_t *fps,
                             uint64_t *ticks, hipStream_t st)
 {
-    SegArgs A{n, T, B, (const uint4 *)vrec, perm, fits, hdr, lst, pool, lens, dir_cap, offs, fps, ticks};
-    if (any_first) hipLaunchKernelGGL(k_place_seg, dim3(B), dim3(SEG_THREADS), 0, st, A);
+    if (trial_b < 0 || trial_percent == 0) return hipSuccess;
+    SegArgs A{n, T, B, (const uint4 *)vrec, perm, fits, hdr, lst, pool, lens, dir_cap, offs, fps, ticks, trial_b,
+              trial_percent};
+    hipLaunchKernelGGL(k_place_seg<true>, dim3(1), dim3(SEG_THREADS), 0, st, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_place_seg(uint32_t n, uint32_t T, uint32_t B, const uint32_t *perm, const uint32_t *fits,
+                            bool any_first, PlanHeader *hdr, const void *vrec, const uint32_t *lst,
+                            uint64_t *pool, uint32_t *lens, uint32_t dir_cap, uint64_t *offs, uint64_t *fps,
+                            uint64_t *ticks, hipStream_t st)
+{
+    SegArgs A{n, T, B, (const uint4 *)vrec, perm, fits, hdr, lst, pool, lens, dir_cap, offs, fps, ticks, -1, 0};
+    if (any_first) hipLaunchKernelGGL(k_place_seg<false>, dim3(B), dim3(SEG_THREADS), 0, st, A);
     return hipGetLastError();
 }
 

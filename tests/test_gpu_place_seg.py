@@ -16,8 +16,10 @@ def lap():
     import paper_1903_06631_amd as lap
     lap.load_library()
     lap.set_option(lap.OPT_SEG_MIN_VARS, 0)
+    lap.set_option(lap.OPT_SEG_TRIAL_PERCENT, 0)             # no trial run: the lists place whatever applies
     yield lap
     lap.set_option(lap.OPT_SEG_MIN_VARS, lap.SEG_MIN_VARS_DEFAULT)
+    lap.set_option(lap.OPT_SEG_TRIAL_PERCENT, lap.SEG_TRIAL_PERCENT_DEFAULT)
 
 
 def _check(lap, oracle, tr, kinds, seeds, fits=None, explicit_np=None):
@@ -111,3 +113,16 @@ def test_default_threshold_keeps_small_traces_on_the_sweep(lap, oracle_mod):
     finally:
         lap.set_option(lap.OPT_SEG_MIN_VARS, 0)
     assert np.array_equal(forced, swept)
+
+
+def test_trial_run_hands_random_lifetimes_back_to_the_sweep(lap, oracle_mod):
+    """With the trial on, a trace with lifetimes at random (searches of many rounds) is placed by the sweep
+    and a nested one by the lists; the offsets are the oracle's either way."""
+    lap.set_option(lap.OPT_SEG_TRIAL_PERCENT, lap.SEG_TRIAL_PERCENT_DEFAULT)
+    try:
+        tr = _long_lived(40, 3000, 900)
+        kinds, seeds = make_orderings(8)
+        _check(lap, oracle_mod, tr, kinds, seeds)
+        _check(lap, oracle_mod, make_config(3), kinds, seeds)
+    finally:
+        lap.set_option(lap.OPT_SEG_TRIAL_PERCENT, 0)
