@@ -226,6 +226,32 @@ def main() -> int:
                                              f"kind {int(kinds[best_b])}), all {n} variables, {c_s:.1f} s",
                                       pair_tests_per_s=n_edges / c_s))
 
+    # The same step captured in a HIP graph and replayed (no per-kernel events inside a graph, so this leg
+    # has no kernel times): what the launch overhead of the ~25 small kernels of a step costs.  Not `value`.
+    graph_ms = None
+    if not args.no_extras:
+        lap.profile_enable(False)
+        lap.load_profile(dt); lap.plan_pool(dt, kinds, seeds, want_all=False); torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                glp = lap.load_profile(dt, sync=False)
+                gpp = lap.plan_pool(dt, kinds, seeds, want_all=False, sync=False)
+                lap.score_swaps(dt, tr.meta["link_GBps"], tr.meta["min_bytes"], load=glp["load"], sync=False)
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay(); torch.cuda.synchronize()
+        reps = max(2, min(args.steps, 5))
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = 1e3 * (time.perf_counter() - c0) / reps
+        assert torch.equal(gpp["best_offsets"], out["best_offsets"]) and torch.equal(gpp["footprints"], out["footprints"])
+        del g, glp, gpp
+        lap.profile_enable(True)
+
     # The rows built beyond the timed path (never part of `value`): the same orderings planned
     # best-fit, and the selection walk for all five priority scores down to a sweep of limits.
     extra = None
@@ -322,7 +348,8 @@ def main() -> int:
         "pair_tests_per_s": B * n_edges * args.steps / total_s,
         "footprint_over_peak": best_fp / peak, "best_ordering": int(out["best_ordering"].item()),
         "footprint_over_peak_fixed_orders": [float(x) / peak for x in fps[:4]],
-        "roofline": roofline, "cpu_baseline": cpu, "beyond_the_timed_path": extra,
+        "roofline": roofline, "cpu_baseline": cpu, "graph_replay_ms_per_step": graph_ms,
+        "beyond_the_timed_path": extra,
         "load_profile": {"kernel_ms_on_workload": lp_small_ms, "stress": stress},
     }
     print(json.dumps(line))
