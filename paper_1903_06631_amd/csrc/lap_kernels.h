@@ -30,6 +30,8 @@ struct PlanHeader {
     unsigned long long seg_tot[PLAN_SEG_CAND];   // per candidate width: blocks entered into lists, summed over the variables
     uint32_t seg_trial_rounds;     // trial run: search rounds of its multi-step variables, summed
     uint32_t seg_trial_vars;       // ... and how many those were
+    uint32_t seg_next;             // next ordering to hand to a workgroup of the segment kernel
+    uint32_t seg_pad;
 };
 constexpr uint32_t PLAN_CL = 6;
 

@@ -135,6 +135,7 @@ template <bool TRIAL>
 __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
 {
     __shared__ uint32_t s_max[2][SEG_WAVES];
+    __shared__ uint32_t s_next;
 
     PlanHeader *hdr = A.hdr;
     if (!hdr->mode2) return;
@@ -150,8 +151,21 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
     uint32_t *lens = A.lens + (size_t)blockIdx.x * A.dir_cap;
     const uint32_t *__restrict__ lst = A.lst;
 
-    for (uint32_t b = TRIAL ? (uint32_t)A.trial_b : blockIdx.x; b < A.B; b += TRIAL ? A.B : slots) {
-        if (A.fits[b] != 0) continue;                // best-fit orderings: the sweep kernel places them
+    // The workgroups take orderings from a common counter, so that one that drew quick orderings goes
+    // on to the next instead of idling (orderings differ by a factor of two in their time).
+    for (;;) {
+        uint32_t b = (uint32_t)A.trial_b;
+        if (!TRIAL) {
+            if (tid == 0) s_next = atomicAdd(&hdr->seg_next, 1u);
+            __syncthreads();
+            b = s_next;
+            __syncthreads();
+        }
+        if (b >= A.B) break;
+        if (A.fits[b] != 0) {                        // best-fit orderings: the sweep kernel places them
+            if (TRIAL) break;
+            continue;
+        }
         const long long t_begin = wall_clock64();
         const uint32_t *perm = A.perm + (size_t)b * A.n;
         uint64_t *offs = A.offs + (size_t)b * A.n;
@@ -235,6 +249,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
             A.ticks[b] = (uint64_t)(wall_clock64() - t_begin);
         }
         __syncthreads();
+        if (TRIAL) break;
     }
     if (TRIAL && tid == 0) {
         hdr->seg_trial_rounds = trial_rounds;
