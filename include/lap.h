@@ -117,7 +117,11 @@ enum {
  *   FIT_FIRST  the lowest hole that is large enough (lowest feasible offset)
  *   FIT_BEST   the smallest hole that is large enough, the lowest of equally small ones (the
  *              paper's default).  A hole is a free range below the neighbours' highest end.
- * With both, a variable that fits no hole goes above the neighbours' highest end. */
+ * With both, a variable that fits no hole goes above the neighbours' highest end.
+ * Cost: first-fit stops at the first hole that fits, best-fit looks at every one.  On traces whose
+ * lifetimes are short (a transformer-shaped trace of 200 000 variables) best-fit takes 1.5 times as
+ * long as first-fit; on dense interval graphs (tens of thousands of variables that mostly live
+ * together) a variable can have thousands of fitting holes and best-fit takes minutes per ordering. */
 enum { LAP_FIT_FIRST = 0, LAP_FIT_BEST = 1 };
 
 typedef struct {

@@ -31,6 +31,10 @@
 //          instead (steps_fit_pass), in turn with the ALL sweeps, until neither
 //          moves the candidate offset.
 //
+// Without the L[t] lists every variable queries ALL (the sweep).  First-fit orderings of large
+// traces whose variables live long may instead be placed by free lists per time segment
+// (place_seg.hip); k_plan_prep2 and a trial run decide, and this kernel then leaves them alone.
+//
 // One-step variables of different steps never interact, so between two
 // multi-step variables of the rank order the waves work in parallel: wave w
 // owns the steps t with t % PW == w.  Multi-step variables are handled by all
