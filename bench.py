@@ -30,13 +30,19 @@ def count_edges(tr) -> int:
 
 
 def source_stamp(*names) -> str:
-    """16 hex digits of SHA-256 over the named kernel sources: a counter summary under profiles/ is
-    only used while the kernel it was measured on is the one in the tree."""
+    """16 hex digits of SHA-256 over the code of the named kernel sources (comments and blank space
+    left out): a counter summary under profiles/ is only used while the kernel it was measured on is
+    the one in the tree."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for nm in names:
-        with open(os.path.join(ROOT, "paper_1903_06631_amd", "csrc", nm), "rb") as fh:
-            h.update(fh.read())
+        with open(os.path.join(ROOT, "paper_1903_06631_amd", "csrc", nm)) as fh:
+            text = re.sub(r"/\*.*?\*/", "", fh.read(), flags=re.S)
+        for ln in text.split("\n"):
+            ln = " ".join(ln.split("//")[0].split())
+            if ln:
+                h.update(ln.encode() + b"\n")
     return h.hexdigest()[:16]
 
 

@@ -22,7 +22,7 @@
 // the total smallest.
 //
 // One workgroup of 256 threads works on one ordering at a time in its own slot of the list
-// pool and goes on to the ordering `slots` further on; the number of slots is what the
+// pool and then takes the next ordering from a common counter; the number of slots is what the
 // workspace has room for.  Results are identical to placing the variables one by one in rank
 // order (same fixed point: the lowest address free of every time-overlapping block).
 // Best-fit orderings of such a trace stay with the sweep over the sorted blocks (place_fast.hip):
