@@ -332,10 +332,12 @@ const char *lap_status_string(int status);
 enum { LAP_OPT_SEG_MIN_VARS = 0, LAP_OPT_SEG_TRIAL_PERCENT = 1 };
 int lap_set_option(int option, uint64_t value);
 
-/* Optional kernel timing for benchmarks.  When enabled, each call brackets
- * its dominant kernel with HIP events on the caller's stream; after the
- * stream is synchronised lap_profile_last_ms returns that kernel's duration
- * in ms (negative if none was recorded).  Not thread safe. */
+/* Optional kernel timing for benchmarks, per calling thread.  When a thread has enabled it, each of
+ * its calls brackets its dominant kernel with HIP events on the caller's stream; after the stream is
+ * synchronised lap_profile_last_ms, called by the same thread, returns that kernel's duration in ms
+ * (negative if none was recorded).  LAP_K_PLACE covers every placement kernel a lap_plan_pool call
+ * launches (those that do not apply to the trace or to an ordering's policy return at once).  The
+ * event records do not belong inside a graph capture: leave the timing off there. */
 enum { LAP_K_LOAD_SCATTER = 0, LAP_K_PLACE = 1, LAP_K_SCORE = 2, LAP_K_SORT = 3, LAP_K_SELECT = 4, LAP_K_COUNT = 5 };
 int lap_profile_enable(int on);
 float lap_profile_last_ms(int kernel_id);

@@ -146,10 +146,11 @@ uint64_t g_seg_min_vars = 32768;
 // trial run above which the segment lists are not used; 0 = no trial
 uint64_t g_seg_trial_percent = 250;
 
-bool g_prof = false;
-hipEvent_t g_ev[LAP_K_COUNT][2];
-bool g_ev_made[LAP_K_COUNT];
-bool g_ev_used[LAP_K_COUNT];
+// kernel timing is per calling thread: each thread that enables it gets events of its own
+thread_local bool g_prof = false;
+thread_local hipEvent_t g_ev[LAP_K_COUNT][2];
+thread_local bool g_ev_made[LAP_K_COUNT];
+thread_local bool g_ev_used[LAP_K_COUNT];
 
 struct ProfScope {
     int id;
