@@ -77,6 +77,7 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     __shared__ uint32_t stage[TS];
     __shared__ uint32_t wtot[SW];
     __shared__ uint32_t s_skip;
+    __shared__ uint32_t hist_all[4][256];    // seeded kinds: the digit counts of all their passes, counted in one sweep
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
     const uint32_t tid = threadIdx.x, w = tid / WAVE;
@@ -114,31 +115,48 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     uint32_t *dst = perm;
     const uint64_t lt_mask = (1ull << l) - 1ull;
     const int first_pass = (kind == 4) ? (n <= (1u << 22) ? 5 : 4) : (kind == 6) ? 4 : 0;
-    for (int pass = first_pass; pass < 8; ++pass) {
-        const int shift = pass * 8;
-        // ---- histogram of this pass's digit over all ranks (thread-strided, independent loads)
-        hist[w][l] = 0; hist[w][l + 64] = 0; hist[w][l + 128] = 0; hist[w][l + 192] = 0;
+    if (first_pass) {
+        // How often a digit occurs does not depend on the order of the ranks, so the counts of all
+        // the passes of a seeded kind come from one sweep over the variables in index order (no
+        // read of the ranks at all) instead of one sweep per pass.
+        for (int q = 0; q < 8 - first_pass; ++q) hist_all[q][tid] = 0;
         __syncthreads();
-        for (uint32_t base = 0; base < n; base += 4 * SW * WAVE) {
-            uint32_t iv[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t r = base + u * SW * WAVE + tid;
-                iv[u] = r < n ? (cur ? cur[r] : r) : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t r = base + u * SW * WAVE + tid;
-                if (r < n) {
-                    const uint32_t d = (uint32_t)(order_key(kind, seed, iv[u], size, alloc, free_) >> shift) & 255u;
-                    atomicAdd(&hist[w][d], 1u);
-                }
-            }
+        for (uint32_t i = tid; i < n; i += SW * WAVE) {
+            const uint64_t key = order_key(kind, seed, i, size, alloc, free_);
+            for (int q = 0; q < 8 - first_pass; ++q)
+                atomicAdd(&hist_all[q][(uint32_t)(key >> ((first_pass + q) * 8)) & 255u], 1u);
         }
         __syncthreads();
+    }
+    for (int pass = first_pass; pass < 8; ++pass) {
+        const int shift = pass * 8;
         uint32_t tot = 0;
+        if (first_pass) {
+            tot = hist_all[pass - first_pass][tid];
+        } else {
+            // ---- histogram of this pass's digit over all ranks (thread-strided, independent loads)
+            hist[w][l] = 0; hist[w][l + 64] = 0; hist[w][l + 128] = 0; hist[w][l + 192] = 0;
+            __syncthreads();
+            for (uint32_t base = 0; base < n; base += 4 * SW * WAVE) {
+                uint32_t iv[4];
 #pragma unroll
-        for (int k = 0; k < SW; ++k) tot += hist[k][tid];
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t r = base + u * SW * WAVE + tid;
+                    iv[u] = r < n ? (cur ? cur[r] : r) : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t r = base + u * SW * WAVE + tid;
+                    if (r < n) {
+                        const uint32_t d = (uint32_t)(order_key(kind, seed, iv[u], size, alloc, free_) >> shift) & 255u;
+                        atomicAdd(&hist[w][d], 1u);
+                    }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < SW; ++k) tot += hist[k][tid];
+        }
         if (tid == 0) s_skip = 0;
         __syncthreads();
         if (tot == n) s_skip = 1;                     // every key has this digit: nothing moves
