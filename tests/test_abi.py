@@ -165,3 +165,21 @@ def test_static_entry_point_rejects_on_the_host(lap):
     long_ = _Trace(4, STATIC_MAX_STEPS + 1, fake, fake, fake, None, None, None)
     assert lib.lap_load_profile_static(C.byref(long_), fake, fake, fake, None) == -2
     assert lib.lap_load_profile_static(C.byref(_Trace(0, 3, fake, fake, fake, None, None, None)), fake, fake, fake, None) == -2
+
+
+def test_options_and_ordering_durations_reject_on_the_host(lap):
+    """lap_set_option refuses unknown options and values; lap_profile_ordering_ms checks its arguments before
+    it touches the device."""
+    import numpy as np
+    lib = lap.load_library()
+    assert lib.lap_set_option(99, 1) == -4
+    assert lib.lap_set_option(1, 1 << 40) == -4                       # rounds, times 100: 32 bits
+    assert lib.lap_set_option(0, lap.SEG_MIN_VARS_DEFAULT) == 0 and lib.lap_set_option(1, lap.SEG_TRIAL_PERCENT_DEFAULT) == 0
+    out = np.zeros(4, np.float32)
+    p = out.ctypes.data_as(C.c_void_p)
+    fake = 0x1000
+    assert lib.lap_profile_ordering_ms(10, 5, 4, fake, 1 << 30, None, None) == -1
+    assert lib.lap_profile_ordering_ms(0, 5, 4, fake, 1 << 30, None, p) == -2
+    assert lib.lap_profile_ordering_ms(10, 5, 4, None, 1 << 30, None, p) == -3
+    assert lib.lap_profile_ordering_ms(10, 5, 4, fake, 16, None, p) == -3             # workspace too small
+    assert lib.lap_profile_ordering_ms(10, 5, 4, fake + 8, 1 << 30, None, p) == -3    # misaligned
