@@ -39,7 +39,6 @@ constexpr int SEG_THREADS = 256;
 constexpr int SEG_WAVES = SEG_THREADS / WAVE;
 constexpr int SEG_MEMO = 2;        // lists per thread whose last answer is kept between rounds
 
-__device__ __forceinline__ uint32_t seg_uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ __forceinline__ uint32_t seg_wave_max(uint32_t v) { return read_lane(wave_scan_max_u32(v), WAVE - 1); }
 
 // ---------------------------------------------------------------------------
