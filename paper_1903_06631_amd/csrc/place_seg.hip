@@ -30,7 +30,7 @@
 // hole does not.
 #include "lap_dev.h"
 #include "lap_kernels.h"
-#define LAP_HD __device__
+#define LAP_HD __device__ __forceinline__
 #include "seg_core.h"
 
 namespace lap {
@@ -102,6 +102,332 @@ __global__ __launch_bounds__(SEG_SCAN_THREADS) void k_seg_scan(uint32_t T, uint3
 }
 
 // ---------------------------------------------------------------------------
+// one wave on one list: its 64 lanes read 64 neighbouring entries at once
+// ---------------------------------------------------------------------------
+//
+// A variable that lives one or two steps asks two to four lists and is taken out of three to
+// five: with one list per thread nearly all of the workgroup idles while one thread follows a
+// chain of dependent 8-byte reads (a search, a walk over ranges too small, a shift of the list's
+// tail entry by entry).  Such a variable is handled by one wave instead, all lanes on the same
+// list: a read fetches 64 neighbouring entries, a ballot finds the first that qualifies, the tail
+// is shifted 256 entries per step, and the wave needs no workgroup barrier between one such
+// variable and the next.  All arguments of these functions are the same in every lane.
+constexpr uint32_t SEG_SHORT_Q = 4;      // most lists such a variable may ask ...
+constexpr uint32_t SEG_SHORT_U = 5;      // ... and be taken out of
+constexpr uint32_t SEG_GROUP = 3;        // such variables placed side by side, one wave each
+constexpr uint32_t SEG_TAIL_SELF = 16;   // a thread moves a list's tail itself up to this many entries
+
+// (a variable that lives through the whole time line asks the list of everything, which the
+// waves do not keep up to date among themselves: it is placed by all threads)
+__device__ __forceinline__ bool seg_is_short(const SegSpan &sp)
+{
+    return !sp.whole && sp.n_query() <= SEG_SHORT_Q && sp.n_update() <= SEG_SHORT_U;
+}
+
+// entries at .. at + 63 (at < len), one per lane; lanes past the end repeat the last entry
+__device__ __forceinline__ uint64_t wv_chunk(const uint64_t *L, uint32_t len, uint32_t at, uint32_t l)
+{
+    const uint32_t i = at + l;
+    return L[i < len ? i : len - 1];
+}
+
+// Index of the first entry whose end is >= key.  In: x = wv_chunk(at); floor_known says that no
+// entry before `at` qualifies.  Out: (at, x) is a chunk that holds the answer.
+__device__ __forceinline__ uint32_t wv_lower_end(const uint64_t *L, uint32_t len, uint32_t key, bool floor_known,
+                                                 uint32_t l, uint32_t &at, uint64_t &x)
+{
+    uint32_t lo = 0, hi = len - 1;           // the answer lies in [lo, hi]; entry hi qualifies (end = SEG_INF at the top)
+    {
+        const uint64_t m = ballot(seg_end(x) >= key);
+        if (m != 0) {
+            const uint32_t f = (uint32_t)__ffsll((unsigned long long)m) - 1;
+            if (f > 0 || at == 0 || floor_known) return at + f;
+            hi = at;                          // the chunk starts at or above the answer
+        } else {
+            lo = at + WAVE;                   // (then at + 63 < len - 1: the last entry always qualifies)
+        }
+    }
+    for (int level = 0; level < 8; ++level) { // 64-way: a range of 2^32 is down to four chunks after four levels
+        const uint32_t m = hi - lo + 1;
+        if (m <= 4u * WAVE) break;
+        const uint32_t pos = lo + (uint32_t)(((uint64_t)(l + 1) * m) >> 6) - 1;    // ascending; lane 63 reads entry hi
+        const uint64_t y = L[pos];
+        const uint64_t q = ballot(seg_end(y) >= key) | (1ull << 63);
+        const uint32_t f = (uint32_t)__ffsll((unsigned long long)q) - 1;
+        hi = read_lane(pos, (int)f);
+        if (f > 0) lo = read_lane(pos, (int)f - 1) + 1;
+    }
+    // what is left, up to four chunks, in one go
+    const uint32_t m = hi - lo + 1;
+    uint64_t c[4];
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k)
+        if (m > WAVE * k) c[k] = wv_chunk(L, len, lo + WAVE * k, l);     // lo + 64 k <= hi < len
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k)
+        if (m > WAVE * k) {
+            const uint64_t q = ballot(seg_end(c[k]) >= key);
+            if (q != 0) {
+                at = lo + WAVE * k;
+                x = c[k];
+                return at + (uint32_t)__ffsll((unsigned long long)q) - 1;
+            }
+        }
+    at = lo;                                  // not reached: entry hi qualifies
+    x = c[0];
+    return lo;
+}
+
+// Lowest address >= o at which s granules are free (as seg_fit).  In: x = wv_chunk(at), no entry
+// before `at` ends at or above o + s.  Out: idx = the entry that holds the answer, (at, x) a chunk
+// that holds that entry.
+__device__ __forceinline__ uint32_t wv_fit(const uint64_t *L, uint32_t len, uint32_t o, uint32_t s, uint32_t l,
+                                           uint32_t &at, uint64_t &x, uint32_t &idx)
+{
+    const uint32_t i = wv_lower_end(L, len, o + s, true, l, at, x);
+    for (;;) {
+        const uint32_t st = seg_start(x), en = seg_end(x), e = at + l;
+        const uint32_t from = st > o ? st : o;
+        // entries from i on end at or above o + s, so en >= from there
+        const uint64_t q = ballot(e >= i && e < len && en - from >= s);
+        if (q != 0) {
+            const uint32_t f = (uint32_t)__ffsll((unsigned long long)q) - 1;
+            idx = at + f;
+            return read_lane(from, (int)f);
+        }
+        if (at + WAVE >= len) break;          // not reached: the last entry always fits
+        at += WAVE;
+        x = wv_chunk(L, len, at, l);
+    }
+    idx = len - 1;
+    const uint64_t top = L[len - 1];
+    at = len - 1;
+    x = wv_chunk(L, len, at, l);
+    return seg_start(top) > o ? seg_start(top) : o;
+}
+
+// entries j .. len-1 move by delta (as seg_carve_shift), 256 per step: all reads of a step come
+// before its writes, and no later step reads what an earlier one wrote
+__device__ __forceinline__ void wv_shift(uint64_t *L, uint32_t len, uint32_t j, int32_t delta, uint32_t l)
+{
+    if (delta > 0) {
+        for (uint32_t top = len; top > j;) {
+            const uint32_t span = top - j;
+            uint64_t v[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (l + WAVE * k < span) v[k] = L[top - 1 - l - WAVE * k];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (l + WAVE * k < span) L[top - l - WAVE * k] = v[k];
+            top = span > 4 * WAVE ? top - 4 * WAVE : j;
+        }
+    } else if (delta < 0) {
+        const uint32_t dn = (uint32_t)-delta;
+        for (uint32_t base = j; base < len; base += 4 * WAVE) {
+            uint64_t v[4];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (base + l + WAVE * k < len) v[k] = L[base + l + WAVE * k];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (base + l + WAVE * k < len) L[base + l + WAVE * k - dn] = v[k];
+        }
+    }
+}
+
+// The same for lists of several lanes at once: lane i's list starts at pool + base, `rem` of its
+// entries (0: none) move by delta, the next of them at `cur` (delta > 0: the entries below cur, from
+// the top down; delta < 0: the entries from cur on, upwards).  The wave moves four chunks of 64
+// entries per step, of one list or of several, so that tails of a few dozen entries in many lists
+// cost no more steps than one long tail.
+__device__ __forceinline__ void wv_shift_lanes(uint64_t *pool, uint32_t base, uint32_t rem, uint32_t cur, int32_t delta,
+                                               uint32_t l)
+{
+    for (;;) {
+        uint64_t need = ballot(rem > 0);
+        if (need == 0) break;
+        uint64_t v[4];
+        uint32_t s_base[4], s_cur[4], s_n[4];
+        int32_t s_delta[4];
+        int s_src[4];
+        int src = 0;
+        uint32_t srem = 0, scur = 0, sbase = 0;
+        int32_t sdelta = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            s_n[k] = 0;
+            if (srem == 0) {
+                if (need == 0) continue;
+                src = __ffsll((unsigned long long)need) - 1;
+                need &= need - 1;
+                srem = read_lane(rem, src);
+                scur = read_lane(cur, src);
+                sbase = read_lane(base, src);
+                sdelta = (int32_t)read_lane((uint32_t)delta, src);
+            }
+            const uint32_t nk = srem < (uint32_t)WAVE ? srem : (uint32_t)WAVE;
+            s_n[k] = nk;
+            s_base[k] = sbase;
+            s_cur[k] = scur;
+            s_delta[k] = sdelta;
+            s_src[k] = src;
+            srem -= nk;
+            scur = sdelta > 0 ? scur - nk : scur + nk;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (l < s_n[k]) v[k] = pool[s_base[k] + (s_delta[k] > 0 ? s_cur[k] - 1 - l : s_cur[k] + l)];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (l < s_n[k]) pool[s_base[k] + (uint32_t)((int32_t)(s_delta[k] > 0 ? s_cur[k] - 1 - l : s_cur[k] + l) + s_delta[k])] = v[k];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (s_n[k] != 0 && (int)l == s_src[k]) {
+                rem -= s_n[k];
+                cur = s_delta[k] > 0 ? cur - s_n[k] : cur + s_n[k];
+            }
+    }
+}
+
+// Takes [o, e) out of the free ranges (as seg_carve).  In: x = wv_chunk(at); either pos_known and
+// `pos` is the first entry that ends above o, inside the chunk, or the chunk is where to start
+// looking (floor_known as in wv_lower_end).  Returns the new length (the old one if the list has
+// no room: not reached, see k_seg_count).
+__device__ __forceinline__ uint32_t wv_carve(uint64_t *L, uint32_t len, uint32_t cap, uint32_t o, uint32_t e,
+                                             bool pos_known, uint32_t pos, bool floor_known, uint32_t l,
+                                             uint32_t at, uint64_t x)
+{
+    const uint32_t i = pos_known ? pos : wv_lower_end(L, len, o + 1, floor_known, l, at, x);
+    const uint32_t d = i - at;                                   // < 64
+    const uint64_t y = shfl64(x, (int)((l + d) & (WAVE - 1)));   // lane 0 holds entry i
+    const uint32_t avail = min((uint32_t)WAVE - d, len - i);     // entries i .. i + avail - 1 are in lanes 0 .. avail - 1
+    const uint64_t q = ballot(l < avail && seg_start(y) < e);    // a prefix: starts ascend
+    const uint32_t gone = (uint32_t)__popcll((unsigned long long)q);
+    if (gone == 0) return len;                                   // nothing free inside [o, e)
+    if (gone == avail && i + avail < len) {                      // more ranges than the chunk shows: one lane, entry by entry
+        uint32_t nlen = len;
+        if (l == 0) seg_carve(L, nlen, cap, o, e, i);
+        return read_lane(nlen, 0);
+    }
+    const uint32_t hs = read_lane(seg_start(y), 0), last_end = read_lane(seg_end(y), (int)gone - 1);
+    const bool left = hs < o, right = last_end > e;
+    const uint32_t keep = (left ? 1u : 0u) + (right ? 1u : 0u), j = i + gone;
+    const int32_t delta = (int32_t)keep - (int32_t)gone;
+    if (delta > 0 && len + 1 > cap) return len;
+    wv_shift(L, len, j, delta, l);
+    const uint32_t nlen = (uint32_t)((int32_t)len + delta);
+    if (l == 0) {
+        uint32_t w = i;
+        if (left) L[w++] = seg_pack(hs, o);
+        if (right) L[w++] = seg_pack(e, last_end);
+    }
+    return nlen;
+}
+
+// One variable with few lists, placed by one wave: the fixed point of k_place_seg with every list
+// read 64 entries at a time.  Lane i holds what concerns the i-th list the variable asks and
+// the i-th list it is taken out of.  The chunks of the lists it will be taken out of but does
+// not ask (whose place to look first does not depend on the answer) are fetched together with
+// the first round's, the others are those the last round left.  The list of everything (the first
+// of the lists it is taken out of) is left to the caller.  Returns the offset in granules.
+__device__ __forceinline__ uint32_t place_short(const SegGeom &g, const SegSpan &sp, uint32_t nq, uint32_t nu,
+                                                uint32_t s, bool longv, uint32_t l,
+                                                const uint32_t *__restrict__ lst, uint64_t *pool, uint32_t *lens,
+                                                uint32_t &trial_rounds)
+{
+    const uint32_t qid = l < nq ? seg_query_list(g, sp, l) : 0u;
+    const uint32_t uid = l < nu ? seg_update_list(g, sp, l) : 0u;
+    const uint32_t qbase = lst[qid], ubase = lst[uid], ucap = lst[uid + 1] - ubase;
+    const uint32_t qlen = lens[qid];
+    const uint32_t ulen0 = lens[uid];
+    uint32_t ulen = ulen0;
+    // which asked list an update list is, if any
+    uint32_t uq = SEG_SHORT_Q;
+    for (uint32_t i = 0; i < nq; ++i)
+        if (read_lane(qid, (int)i) == uid) uq = i;
+
+    uint64_t xq[SEG_SHORT_Q], xu[SEG_SHORT_U];
+    uint32_t qat = 0, qidx = 0;                   // lane i: where list i's chunk starts, the entry that answered
+    // where to look first in an update list that is not asked: long-lived blocks end up high
+    uint32_t uat = (longv && ulen > (uint32_t)WAVE) ? ulen - WAVE : 0u;
+#pragma unroll
+    for (uint32_t i = 0; i < SEG_SHORT_Q; ++i)
+        if (i < nq) xq[i] = wv_chunk(pool + read_lane(qbase, (int)i), read_lane(qlen, (int)i), 0u, l);
+#pragma unroll
+    for (uint32_t u = 1; u < SEG_SHORT_U; ++u)
+        if (u < nu && read_lane(uq, (int)u) == SEG_SHORT_Q)
+            xu[u] = wv_chunk(pool + read_lane(ubase, (int)u), read_lane(ulen, (int)u), read_lane(uat, (int)u), l);
+
+    uint32_t o = 0;
+    for (;;) {
+        // a list's next answer is at or after its last one, often in the chunk the last round left
+        uint32_t best = o;
+        for (uint32_t i = 0; i < nq; ++i) {
+            uint64_t x = xq[0];
+#pragma unroll
+            for (uint32_t k = 1; k < SEG_SHORT_Q; ++k)
+                if (i == k) x = xq[k];
+            uint32_t at = read_lane(qat, (int)i), idx;
+            const uint32_t a = wv_fit(pool + read_lane(qbase, (int)i), read_lane(qlen, (int)i), o, s, l, at, x, idx);
+#pragma unroll
+            for (uint32_t k = 0; k < SEG_SHORT_Q; ++k)
+                if (i == k) xq[k] = x;
+            if (l == i) {
+                qat = at;
+                qidx = idx;
+            }
+            best = max(best, a);
+        }
+        if (longv) ++trial_rounds;
+        if (best == o) break;                     // every list accepts o
+        o = best;
+    }
+    const uint32_t en = o + s;
+    for (uint32_t u = 1; u < nu; ++u) {
+        // an asked list: the range that holds [o, en) is the one that answered, and the first that ends above o
+        const uint32_t qi = read_lane(uq, (int)u);
+        const bool asked = qi < SEG_SHORT_Q;
+        uint64_t x = asked ? xq[0] : xu[1];
+#pragma unroll
+        for (uint32_t k = 1; k < SEG_SHORT_Q; ++k)
+            if (asked && qi == k) x = xq[k];
+#pragma unroll
+        for (uint32_t k = 2; k < SEG_SHORT_U; ++k)
+            if (!asked && u == k) x = xu[k];
+        const uint32_t at = asked ? read_lane(qat, (int)(qi & (SEG_SHORT_Q - 1))) : read_lane(uat, (int)u);
+        const uint32_t pos = read_lane(qidx, (int)(qi & (SEG_SHORT_Q - 1)));
+        const uint32_t nlen = wv_carve(pool + read_lane(ubase, (int)u), read_lane(ulen, (int)u), read_lane(ucap, (int)u),
+                                       o, en, asked, pos, asked || at == 0, l, at, x);
+        if (l == u) ulen = nlen;
+    }
+    if (l >= 1 && l < nu && ulen != ulen0) lens[uid] = ulen;
+    // the wave's later reads of these lists come after these writes (same wave: in order)
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    return o;
+}
+
+// The blocks of the last group of few-list variables, taken out of the list of everything by one
+// wave while the others place the next group (nothing but a variable that lives through the
+// whole time line asks that list, and such a variable waits for this).
+__device__ __forceinline__ void every_apply(const SegGeom &g, const uint32_t *__restrict__ lst, uint64_t *pool,
+                                            uint32_t *lens, const uint4 *pend, uint32_t n_pend, uint32_t l)
+{
+    const uint32_t id = 2 * g.K + g.T;
+    const uint32_t base = read_lane(lst[id], 0), cap = read_lane(lst[id + 1], 0) - base;
+    const uint32_t len0 = read_lane(lens[id], 0);
+    uint32_t len = len0;
+    uint64_t *L = pool + base;
+    for (uint32_t m = 0; m < n_pend; ++m) {
+        const uint4 pe = pend[m];
+        const uint32_t o = read_lane(pe.x, 0), en = read_lane(pe.y, 0), at = (read_lane(pe.z, 0) && len > (uint32_t)WAVE) ? len - WAVE : 0u;
+        const uint64_t x = wv_chunk(L, len, at, l);
+        len = wv_carve(L, len, cap, o, en, false, 0u, at == 0, l, at, x);
+    }
+    if (l == 0 && len != len0) lens[id] = len;
+}
+
+// ---------------------------------------------------------------------------
 // the placement kernel
 // ---------------------------------------------------------------------------
 
@@ -135,6 +461,9 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
 {
     __shared__ uint32_t s_max[2][SEG_WAVES];
     __shared__ uint32_t s_next;
+    __shared__ uint32_t s_pos[SEG_THREADS];          // where the list a thread asked answered last
+    __shared__ uint4 s_pend[2][SEG_GROUP];           // (offset, end, long-lived?, -) of the blocks of the last two groups
+    __shared__ uint32_t s_fp[SEG_WAVES], s_rounds[SEG_WAVES], s_vars[SEG_WAVES];
 
     PlanHeader *hdr = A.hdr;
     if (!hdr->mode2) return;
@@ -145,7 +474,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
     const uint32_t sh = hdr->shift;
     const uint32_t n = TRIAL ? min(A.n, SEG_TRIAL_RANKS) : A.n;
     const uint32_t tid = threadIdx.x, l = tid & (WAVE - 1), wave = tid / WAVE;
-    uint32_t trial_rounds = 0, trial_vars = 0;
+    uint32_t trial_rounds = 0, trial_vars = 0;         // of the variables all threads place together ...
+    uint32_t short_rounds = 0, short_vars = 0;         // ... and of those this wave places alone
     uint64_t *pool = A.pool + (size_t)blockIdx.x * hdr->seg_need;
     uint32_t *lens = A.lens + (size_t)blockIdx.x * A.dir_cap;
     const uint32_t *__restrict__ lst = A.lst;
@@ -175,39 +505,125 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
         }
         __syncthreads();
         uint32_t fp = 0, flip = 0;
+        uint32_t pend = 0, ppar = 0;       // blocks the list of everything has not seen yet: s_pend[ppar][0 .. pend)
         for (uint32_t r0 = 0; r0 < n; r0 += WAVE) {
             // every wave holds the records of ranks r0 .. r0 + 63, lane i that of rank r0 + i
             uint4 rec = make_uint4(0u, 1u, 1u, 0u);
             if (r0 + l < n) rec = A.vrec[perm[r0 + l]];
             const uint32_t wn = min((uint32_t)WAVE, n - r0);
-            for (uint32_t p = 0; p < wn; ++p) {
+            for (uint32_t p = 0; p < wn;) {
                 const uint32_t a = read_lane(rec.x, (int)p), f = read_lane(rec.y, (int)p), s = read_lane(rec.z, (int)p);
                 const SegSpan sp = seg_span(g, a, f);
                 const uint32_t nq = sp.n_query(), nu = sp.n_update();
                 const bool longv = f - a > 1;         // long-lived blocks end up high, one-step ones low
+                if (seg_is_short(sp)) {
+                    // Few lists: one wave, all lanes on one list at a time.  Up to three such
+                    // variables in a row whose segments differ share no list but that of
+                    // everything and do not meet in time: three waves place them side by side,
+                    // the fourth takes the last group's blocks out of the list of everything.
+                    uint32_t gsz = 1, lo1 = 0, hi1 = 0;
+                    const uint32_t lo0 = sp.k0, hi0 = sp.k0 + sp.nseg;
+                    for (uint32_t m = 1; m < SEG_GROUP && p + m < wn; ++m) {
+                        const SegSpan sm = seg_span(g, read_lane(rec.x, (int)(p + m)), read_lane(rec.y, (int)(p + m)));
+                        if (!seg_is_short(sm)) break;
+                        const uint32_t lo = sm.k0, hi = sm.k0 + sm.nseg;
+                        if (lo < hi0 && lo0 < hi) break;
+                        if (m == 2 && lo < hi1 && lo1 < hi) break;
+                        lo1 = lo;
+                        hi1 = hi;
+                        ++gsz;
+                    }
+                    if (wave < gsz) {
+                        const uint32_t q = p + wave;
+                        const uint32_t aq = read_lane(rec.x, (int)q), fq = read_lane(rec.y, (int)q), sq = read_lane(rec.z, (int)q);
+                        const SegSpan sq_ = seg_span(g, aq, fq);
+                        const bool lq = fq - aq > 1;
+                        const uint32_t o = place_short(g, sq_, sq_.n_query(), sq_.n_update(), sq, lq, l, lst, pool, lens, short_rounds);
+                        if (lq) ++short_vars;
+                        fp = max(fp, o + sq);
+                        if (l == 0) {
+                            offs[r0 + q] = (uint64_t)o << sh;
+                            s_pend[ppar ^ 1][wave] = make_uint4(o, o + sq, lq ? 1u : 0u, 0u);
+                        }
+                    } else if (wave == SEG_WAVES - 1 && pend) {
+                        every_apply(g, lst, pool, lens, s_pend[ppar], pend, l);
+                    }
+                    __syncthreads();
+                    ppar ^= 1;
+                    pend = gsz;
+                    p += gsz;
+                    continue;
+                }
+                if (pend) {                           // the list of everything is asked, or written, below
+                    if (wave == SEG_WAVES - 1) every_apply(g, lst, pool, lens, s_pend[ppar], pend, l);
+                    __syncthreads();
+                    pend = 0;
+                }
                 // lowest address that is free in every list of the variable: every thread asks its
                 // lists for their lowest fit at or above the candidate, the maximum is the next
                 // candidate, until no list moves it
-                uint32_t memo[SEG_MEMO];
+                uint32_t memo[SEG_MEMO] = {0u, 0u};
                 bool have = false;
                 uint32_t o = 0;
+                // what a thread needs of its first list in every round, and of the first list it will
+                // take the block out of, is read once, ahead of the searches
+                uint32_t q_len = 0, q_base = 0, q_top = 0, u_len = 0, u_base = 0, u_cap = 0;
+                if (tid < nq) {
+                    const uint32_t id = seg_query_list(g, sp, tid);
+                    q_len = lens[id];
+                    q_base = lst[id];
+                }
+                if (tid < nu) {
+                    const uint32_t id = seg_update_list(g, sp, tid);
+                    u_len = lens[id];
+                    u_base = lst[id];
+                    u_cap = lst[id + 1] - u_base;
+                }
+                if (tid < nq && longv && q_len > 8) q_top = seg_start(pool[q_base + q_len - 1]);
+                // A first candidate from one list, the one with most in it (the segment in the
+                // middle of the lifetime), read by one wave 64 entries at a time: asked from there,
+                // the others are spared the climb from address 0 over everything that does not
+                // concern them (a walk over thousands of ranges too small, when large variables
+                // come late).
+                uint32_t x_last = 0xFFFFFFFFu, he_last = 0;     // this thread's first list: its last answer and where that range ends
+                if (nq >= 8) {
+                    uint32_t first = 0;
+                    if (wave == 0) {
+                        const uint32_t id = seg_query_list(g, sp, sp.nf / 2);
+                        const uint32_t len = read_lane(lens[id], 0);
+                        const uint64_t *L = pool + read_lane(lst[id], 0);
+                        uint32_t at = 0, idx;
+                        uint64_t x = wv_chunk(L, len, 0u, l);
+                        first = wv_fit(L, len, 0u, s, l, at, x, idx);
+                    }
+                    if (l == 0) s_max[flip][wave] = first;
+                    __syncthreads();
+                    o = max(max(s_max[flip][0], s_max[flip][1]), max(s_max[flip][2], s_max[flip][3]));
+                    flip ^= 1;
+                    have = o > 0;                     // (then start where the candidate would be, as in later rounds)
+                }
                 for (;;) {
                     uint32_t best = o, j = 0;
                     for (uint32_t i = tid; i < nq; i += SEG_THREADS, ++j) {
-                        const uint32_t id = seg_query_list(g, sp, i);
-                        const uint32_t len = lens[id];
+                        // the range that answered last holds the new candidate as well: nothing to read
+                        if (j == 0 && have && x_last <= o && he_last - o >= s && he_last >= o) continue;
+                        uint32_t len = q_len, base = q_base;
+                        if (j > 0) {
+                            const uint32_t id = seg_query_list(g, sp, i);
+                            len = lens[id];
+                            base = lst[id];
+                        }
                         // Where to look first.  The first round asks from address 0 and is answered
                         // low in the list.  Later rounds: where this list answered before, or, for a
                         // long-lived variable whose candidate has jumped up, further up at the
                         // place the candidate would have if the holes were spread evenly below the
-                        // list's top (one read for the top; it saves most of the climb: a third
-                        // fewer list reads in all).
-                        const uint64_t *L = pool + lst[id];
+                        // list's top (it saves most of the climb: a third fewer list reads in all).
+                        const uint64_t *L = pool + base;
                         uint32_t idx = 0, he;
                         if (have) {
                             if (j < SEG_MEMO) idx = memo[j];
                             if (longv && len > 8) {
-                                const uint32_t top = seg_start(L[len - 1]);
+                                const uint32_t top = j > 0 ? seg_start(L[len - 1]) : q_top;
                                 if (top) {
                                     const uint64_t at = (uint64_t)len * ((uint64_t)o + s) / top;
                                     idx = max(idx, (uint32_t)(at < len - 1 ? at : len - 1));
@@ -216,14 +632,19 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                         }
                         const uint32_t x = seg_fit(L, len, o, s, idx, he);
                         if (j < SEG_MEMO) memo[j] = idx;
+                        if (j == 0) {
+                            x_last = x;
+                            he_last = he;
+                        }
                         best = max(best, x);
                     }
-                    have = true;
                     best = seg_wave_max(best);
                     if (l == 0) s_max[flip][wave] = best;
+                    s_pos[tid] = memo[0];             // after the last round: the range that holds the block
                     __syncthreads();
                     best = max(max(s_max[flip][0], s_max[flip][1]), max(s_max[flip][2], s_max[flip][3]));
                     flip ^= 1;
+                    have = true;
                     if (TRIAL && longv) ++trial_rounds;
                     if (best == o) break;             // every list accepts o
                     o = best;
@@ -232,20 +653,66 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 const uint32_t en = o + s;
                 fp = max(fp, en);
                 if (tid == 0) offs[r0 + p] = (uint64_t)o << sh;      // rank order; un-permuted at the end
-                for (uint32_t i = tid; i < nu; i += SEG_THREADS) {
-                    const uint32_t id = seg_update_list(g, sp, i);
-                    const uint32_t base = lst[id], cap = lst[id + 1] - base;
-                    uint32_t len = lens[id];
-                    // a list never outgrows its room (it sees at most cap - 1 blocks); the check
-                    // keeps the stores inside the list whatever happens
-                    if (seg_carve(pool + base, len, cap, o, en, longv ? len - 1 : 0u)) lens[id] = len;
+                // One list per thread: where the block goes and what changes (seg_carve_plan); a
+                // list's tail moves by its thread if it is short and by the whole wave, 256
+                // entries per step, if it is long (large blocks that come late split ranges low
+                // in lists of thousands: entry by entry that was most of a slow ordering's time).
+                for (uint32_t i0 = 0; i0 < nu; i0 += SEG_THREADS) {
+                    const uint32_t i = i0 + tid;
+                    const bool mine = i < nu;
+                    uint32_t base = u_base, cap = u_cap, len = u_len, id = 0;
+                    SegCarve c;
+                    c.i = c.j = 0;
+                    c.delta = 0;
+                    if (mine) {
+                        id = seg_update_list(g, sp, i);
+                        if (i0 > 0) {
+                            base = lst[id];
+                            cap = lst[id + 1] - base;
+                            len = lens[id];
+                        }
+                        // Where to look first.  A list that was asked: the range that answered holds
+                        // the block.  Otherwise long-lived blocks end up high, one-step ones low (the
+                        // place the address would have if the ranges were spread evenly below the
+                        // top: measured worse).
+                        uint32_t hint = longv ? len - 1 : 0u;
+                        const uint32_t q = seg_update_query(sp, i);
+                        if (q < SEG_THREADS) hint = s_pos[q];
+                        c = seg_carve_plan(pool + base, len, o, en, hint);
+                        // a list never outgrows its room (it sees at most cap - 1 blocks); the check
+                        // keeps the stores inside the list whatever happens
+                        if (c.delta > 0 && len + 1 > cap) c.j = c.i;
+                    }
+                    const bool act = c.j != c.i;
+                    const uint32_t tail = act && c.delta != 0 ? len - c.j : 0u;
+                    if (tail > 0 && tail <= SEG_TAIL_SELF) seg_carve_shift(pool + base, len, c.j, c.delta);
+                    wv_shift_lanes(pool, base, tail > SEG_TAIL_SELF ? tail : 0u, c.delta > 0 ? len : c.j, c.delta, l);
+                    if (act) {
+                        seg_carve_finish(pool + base, c, o, en);
+                        if (c.delta != 0) lens[id] = (uint32_t)((int32_t)len + c.delta);
+                    }
                 }
                 __syncthreads();
+                ++p;
             }
         }
-        if (tid == 0 && !TRIAL) {
-            A.fps[b] = (uint64_t)fp << sh;
-            A.ticks[b] = (uint64_t)(wall_clock64() - t_begin);
+        // what the waves placed on their own: highest end, rounds
+        if (l == 0) {
+            s_fp[wave] = fp;
+            s_rounds[wave] = short_rounds;
+            s_vars[wave] = short_vars;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 0; w < SEG_WAVES; ++w) {
+                fp = max(fp, s_fp[w]);
+                trial_rounds += s_rounds[w];
+                trial_vars += s_vars[w];
+            }
+            if (!TRIAL) {
+                A.fps[b] = (uint64_t)fp << sh;
+                A.ticks[b] = (uint64_t)(wall_clock64() - t_begin);
+            }
         }
         __syncthreads();
         if (TRIAL) break;

@@ -1,6 +1,6 @@
 // Free-range ("hole") lists over time segments: the per-thread primitives and the geometry of
 // the segment placement kernel (place_seg.hip).  Plain functions on memory, written so that a
-// host compiler accepts them too (LAP_HD is empty there): the same code can be run under a
+// host compiler accepts them too (LAP_HD is plain `inline` there): the same code can be run under a
 // host-side bounds checker.
 //
 // A list holds the free address ranges with respect to some set of placed blocks, sorted by
@@ -11,7 +11,7 @@
 #include <stdint.h>
 
 #ifndef LAP_HD
-#define LAP_HD
+#define LAP_HD inline
 #endif
 #ifndef SEG_LD
 #define SEG_LD(list, i) (list)[i]       // a host harness may count the reads
@@ -22,16 +22,16 @@ namespace lap {
 constexpr uint32_t SEG_INF = 0xFFFFFFFFu;
 constexpr uint32_t SEG_NOHINT = 0xFFFFFFFFu;     // seg_lower_end / seg_fit / seg_carve: no idea where to look
 
-LAP_HD inline uint64_t seg_pack(uint32_t start, uint32_t end) { return ((uint64_t)start << 32) | end; }
-LAP_HD inline uint32_t seg_start(uint64_t x) { return (uint32_t)(x >> 32); }
-LAP_HD inline uint32_t seg_end(uint64_t x) { return (uint32_t)x; }
+LAP_HD uint64_t seg_pack(uint32_t start, uint32_t end) { return ((uint64_t)start << 32) | end; }
+LAP_HD uint32_t seg_start(uint64_t x) { return (uint32_t)(x >> 32); }
+LAP_HD uint32_t seg_end(uint64_t x) { return (uint32_t)x; }
 
 // Index of the first of the `len` >= 1 entries whose end is >= key (key < SEG_INF or the answer is
 // the last entry: its end is SEG_INF).  The search runs outward from `hint` in doubling steps and
 // finishes with a binary search, so an answer near the hint costs two or three probes.  (Probing
 // eight ways at a time shortens the chain of dependent reads but reads more: measured slower,
 // the lists' scattered reads are bound by their number, not by their latency.)
-LAP_HD inline uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uint32_t hint)
+LAP_HD uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uint32_t hint)
 {
     uint32_t lo, hi;                         // the answer lies in [lo, hi]
     if (hint == SEG_NOHINT) {                // nothing known: plain binary search
@@ -79,53 +79,112 @@ LAP_HD inline uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t k
 // Lowest address >= o at which s granules are free (o + s < SEG_INF).  idx: in, where to start
 // looking; out, the entry that holds the answer.  hole_end receives that entry's end (where the
 // free range around the answer stops).
-LAP_HD inline uint32_t seg_fit(const uint64_t *L, uint32_t len, uint32_t o, uint32_t s, uint32_t &idx,
+LAP_HD uint32_t seg_fit(const uint64_t *L, uint32_t len, uint32_t o, uint32_t s, uint32_t &idx,
                                uint32_t &hole_end)
 {
     uint32_t i = seg_lower_end(L, len, o + s, idx);
     for (;;) {
-        const uint64_t x = SEG_LD(L, i);
-        const uint32_t st = seg_start(x), en = seg_end(x);
-        const uint32_t from = st > o ? st : o;
-        if (en - from >= s) {                // en >= o + s and en > st, so en >= from
-            idx = i;
-            hole_end = en;
-            return from;
+        // four entries per step: their reads do not wait for one another (past the end, the last
+        // entry again, which always fits: the loop ends inside the list)
+        uint64_t x[4];
+        for (uint32_t k = 0; k < 4; ++k) x[k] = SEG_LD(L, i + k < len ? i + k : len - 1);
+        for (uint32_t k = 0; k < 4; ++k) {
+            const uint32_t st = seg_start(x[k]), en = seg_end(x[k]);
+            const uint32_t from = st > o ? st : o;
+            if (en - from >= s) {            // en >= o + s and en > st, so en >= from
+                idx = i + k < len ? i + k : len - 1;
+                hole_end = en;
+                return from;
+            }
         }
-        ++i;                                 // the last entry always fits: the loop ends inside the list
+        i += 4;
     }
 }
 
-// Takes [o, e) out of the free ranges (the range may be free, partly free or not free at all).
-// A list grows by at most one entry per call; `cap` is the room it has.  Returns false, and
-// leaves the list alone, if it would outgrow cap.
-LAP_HD inline bool seg_carve(uint64_t *L, uint32_t &len, uint32_t cap, uint32_t o, uint32_t e, uint32_t hint)
+// Taking [o, e) out of the free ranges (the range may be free, partly free or not free at all), in
+// three steps so that a caller can do the middle one its own way: what changes (seg_carve_plan),
+// the move of the list's tail (seg_carve_shift), the one or two ranges written (seg_carve_finish).
+struct SegCarve {
+    uint32_t i, j;           // ranges i .. j-1 meet [o, e); j == i: nothing free inside, nothing to do
+    uint32_t hs, last_end;   // start of range i, end of range j-1
+    int32_t delta;           // what the length changes by: +1 (one range becomes two), 0, or -(ranges that go)
+};
+
+LAP_HD SegCarve seg_carve_plan(const uint64_t *L, uint32_t len, uint32_t o, uint32_t e, uint32_t hint)
 {
-    const uint32_t i = seg_lower_end(L, len, o + 1, hint);      // first range that ends above o
-    const uint64_t x = SEG_LD(L, i);
-    const uint32_t hs = seg_start(x);
-    if (hs >= e) return true;                                    // nothing free inside [o, e)
-    uint32_t last_end = seg_end(x), j = i + 1;                   // ranges i .. j-1 meet [o, e)
-    while (j < len) {
-        const uint64_t y = SEG_LD(L, j);
-        if (seg_start(y) >= e) break;
-        last_end = seg_end(y);
-        ++j;
+    SegCarve c;
+    c.i = seg_lower_end(L, len, o + 1, hint);                    // first range that ends above o
+    const uint64_t x = SEG_LD(L, c.i);
+    c.hs = seg_start(x);
+    c.last_end = seg_end(x);
+    c.j = c.i;
+    c.delta = 0;
+    if (c.hs >= e) return c;                                     // nothing free inside [o, e)
+    uint32_t j = c.i + 1;
+    for (bool more = j < len; more;) {                           // four entries per step, as in seg_fit
+        uint64_t y[4];
+        for (uint32_t k = 0; k < 4; ++k) y[k] = SEG_LD(L, j + k < len ? j + k : len - 1);
+        for (uint32_t k = 0; k < 4 && more; ++k) {
+            if (seg_start(y[k]) >= e) {
+                more = false;
+            } else {
+                c.last_end = seg_end(y[k]);
+                ++j;
+                more = j < len;
+            }
+        }
     }
-    const bool left = hs < o, right = last_end > e;
-    const uint32_t keep = (left ? 1u : 0u) + (right ? 1u : 0u), gone = j - i;
-    if (keep > gone) {                                           // one range becomes two
-        if (len + 1 > cap) return false;
-        for (uint32_t q = len; q > j; --q) L[q] = SEG_LD(L, q - 1);
-        len += 1;
-    } else if (keep < gone) {
-        const uint32_t d = gone - keep;
-        for (uint32_t q = j; q < len; ++q) L[q - d] = SEG_LD(L, q);
-        len -= d;
+    c.j = j;
+    const uint32_t keep = (c.hs < o ? 1u : 0u) + (c.last_end > e ? 1u : 0u);
+    c.delta = (int32_t)keep - (int32_t)(j - c.i);
+    return c;
+}
+
+// entries j .. len-1 move by delta (+1, or down by -delta <= j), eight per step: all reads of a
+// step come before its writes, and no later step reads what an earlier one wrote
+LAP_HD void seg_carve_shift(uint64_t *L, uint32_t len, uint32_t j, int32_t delta)
+{
+    if (delta > 0) {
+        for (uint32_t q = len; q > j;) {
+            const uint32_t m = q - j < 8 ? q - j : 8;
+            uint64_t v[8];
+            for (uint32_t k = 0; k < 8; ++k)
+                if (k < m) v[k] = SEG_LD(L, q - 1 - k);
+            for (uint32_t k = 0; k < 8; ++k)
+                if (k < m) L[q - k] = v[k];
+            q -= m;
+        }
+    } else if (delta < 0) {
+        const uint32_t d = (uint32_t)-delta;
+        for (uint32_t q = j; q < len;) {
+            const uint32_t m = len - q < 8 ? len - q : 8;
+            uint64_t v[8];
+            for (uint32_t k = 0; k < 8; ++k)
+                if (k < m) v[k] = SEG_LD(L, q + k);
+            for (uint32_t k = 0; k < 8; ++k)
+                if (k < m) L[q + k - d] = v[k];
+            q += m;
+        }
     }
-    uint32_t w = i;
-    if (left) L[w++] = seg_pack(hs, o);
-    if (right) L[w++] = seg_pack(e, last_end);
+}
+
+LAP_HD void seg_carve_finish(uint64_t *L, const SegCarve &c, uint32_t o, uint32_t e)
+{
+    uint32_t w = c.i;
+    if (c.hs < o) L[w++] = seg_pack(c.hs, o);
+    if (c.last_end > e) L[w++] = seg_pack(e, c.last_end);
+}
+
+// All three.  A list grows by at most one entry per call; `cap` is the room it has.  Returns false,
+// and leaves the list alone, if it would outgrow cap.
+LAP_HD bool seg_carve(uint64_t *L, uint32_t &len, uint32_t cap, uint32_t o, uint32_t e, uint32_t hint)
+{
+    const SegCarve c = seg_carve_plan(L, len, o, e, hint);
+    if (c.j == c.i) return true;
+    if (c.delta > 0 && len + 1 > cap) return false;
+    seg_carve_shift(L, len, c.j, c.delta);
+    seg_carve_finish(L, c, o, e);
+    len = (uint32_t)((int32_t)len + c.delta);
     return true;
 }
 
@@ -160,7 +219,7 @@ struct SegSpan {
     LAP_HD uint32_t n_update() const { return 1 + nseg + nf + p0n + p1n; }
 };
 
-LAP_HD inline SegSpan seg_span(const SegGeom &g, uint32_t a, uint32_t f)
+LAP_HD SegSpan seg_span(const SegGeom &g, uint32_t a, uint32_t f)
 {
     SegSpan sp;
     const uint32_t sh = g.shift, w = 1u << sh;
@@ -193,7 +252,7 @@ LAP_HD inline SegSpan seg_span(const SegGeom &g, uint32_t a, uint32_t f)
 // i-th list a variable asks (i < n_query): the all-lists of its full segments (the one list of
 // everything if those are all segments), then for each partial segment the cover-list and the
 // step-lists of its steps there
-LAP_HD inline uint32_t seg_query_list(const SegGeom &g, const SegSpan &sp, uint32_t i)
+LAP_HD uint32_t seg_query_list(const SegGeom &g, const SegSpan &sp, uint32_t i)
 {
     if (sp.whole) return 2 * g.K + g.T;
     if (i < sp.nf) return sp.kf0 + i;
@@ -209,7 +268,7 @@ LAP_HD inline uint32_t seg_query_list(const SegGeom &g, const SegSpan &sp, uint3
 
 // i-th list a placed block is taken out of (i < n_update): the list of everything, all[k] of every segment it touches,
 // cover[k] of its full segments, step[t] of its steps in the partial segments
-LAP_HD inline uint32_t seg_update_list(const SegGeom &g, const SegSpan &sp, uint32_t i)
+LAP_HD uint32_t seg_update_list(const SegGeom &g, const SegSpan &sp, uint32_t i)
 {
     if (i == 0) return 2 * g.K + g.T;
     i -= 1;
@@ -220,6 +279,25 @@ LAP_HD inline uint32_t seg_update_list(const SegGeom &g, const SegSpan &sp, uint
     if (i < sp.p0n) return 2 * g.K + sp.p0a + i;
     i -= sp.p0n;
     return 2 * g.K + sp.p1a + i;
+}
+
+// which of the lists a variable asks (index as in seg_query_list) the i-th list it is taken out
+// of is; SEG_NOHINT if it does not ask that list
+LAP_HD uint32_t seg_update_query(const SegSpan &sp, uint32_t i)
+{
+    if (sp.whole) return i == 0 ? 0u : SEG_NOHINT;       // asks the list of everything alone
+    if (i == 0) return SEG_NOHINT;
+    i -= 1;
+    if (i < sp.nseg) {                                    // all[k0 + i]: asked if the segment is lived through entirely
+        const uint32_t k = sp.k0 + i;
+        return k >= sp.kf0 && k - sp.kf0 < sp.nf ? k - sp.kf0 : SEG_NOHINT;
+    }
+    i -= sp.nseg;
+    if (i < sp.nf) return SEG_NOHINT;                     // cover[k] of a full segment
+    i -= sp.nf;
+    if (i < sp.p0n) return sp.nf + 1 + i;                 // step lists of the first partial segment ...
+    i -= sp.p0n;
+    return sp.nf + (sp.p0n ? 1 + sp.p0n : 0) + 1 + i;     // ... and of the second
 }
 
 }  // namespace lap

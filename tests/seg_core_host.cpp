@@ -80,6 +80,12 @@ int seg_host_place(uint32_t n, uint32_t T, const uint32_t *size_granules, const 
         std::vector<uint32_t> q, u;
         for (uint32_t i = 0; i < sp.n_query(); ++i) q.push_back(seg_query_list(g, sp, i));
         for (uint32_t i = 0; i < sp.n_update(); ++i) u.push_back(seg_update_list(g, sp, i));
+        // seg_update_query: an update list maps to the asked list that it is, and to none otherwise
+        for (uint32_t i = 0; i < u.size(); ++i) {
+            const uint32_t qi = seg_update_query(sp, i);
+            const bool asked = std::find(q.begin(), q.end(), u[i]) != q.end();
+            if (qi == SEG_NOHINT ? asked : (qi >= q.size() || q[qi] != u[i])) return 6;
+        }
         for (uint32_t id : q) if (id >= nl) return 1;
         for (uint32_t id : u) { if (id >= nl) return 1; ++cnt[id]; }
         std::sort(q.begin(), q.end());
