@@ -9,7 +9,7 @@ namespace lap {
 constexpr uint32_t PLAN_SEG_SHIFT0 = 2, PLAN_SEG_CAND = 9;
 // list entries of the segment kernel's pool per ordering and variable (the pool is shared: an
 // ordering that needs more leaves fewer slots)
-constexpr uint32_t PLAN_SEG_BUDGET = 24;
+constexpr uint32_t PLAN_SEG_BUDGET = 27;
 
 // Per-call facts about the trace, computed on the device before placement.
 struct PlanHeader {

@@ -93,11 +93,19 @@ __global__ __launch_bounds__(SEG_SCAN_THREADS) void k_seg_scan(uint32_t T, uint3
     if (tid == 0) {
         // the slots are laid out with what the lists really take (the estimate that chose the
         // segment width counts the same blocks another way)
-        const uint64_t slots = pool_entries / carry;
+        uint64_t slots = pool_entries / carry;
         lst[nl] = (uint32_t)carry;
         hdr->seg_need = carry;
-        hdr->seg_slots = (uint32_t)(slots < B ? slots : B);
-        if (slots == 0 || carry >= 0xFFFFFFFFull) hdr->mode2 = 0;
+        if (slots == 0 || carry >= 0xFFFFFFFFull) {
+            hdr->mode2 = 0;
+            slots = 1;
+        }
+        if (slots > B) slots = B;
+        // No more slots than make every slot's share of the orderings the same number: the
+        // launch ends when the slots with the largest share do, and fewer slots slow one
+        // another down less.
+        const uint64_t share = (B + slots - 1) / slots;
+        hdr->seg_slots = (uint32_t)((B + share - 1) / share);
     }
 }
 
@@ -554,10 +562,15 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                     p += gsz;
                     continue;
                 }
-                if (pend) {                           // the list of everything is asked, or written, below
+                // The list of everything has to see the last group's blocks before it is asked (by a
+                // variable that lives through the whole time line) or written (by thread 0, below).
+                // If the last wave has no list to ask, it does that during the first candidate's
+                // search, whose barrier then covers it.
+                const bool first_cand = nq >= 8;
+                const bool drain_late = pend != 0 && first_cand && nq <= SEG_THREADS - WAVE;
+                if (pend && !drain_late) {
                     if (wave == SEG_WAVES - 1) every_apply(g, lst, pool, lens, s_pend[ppar], pend, l);
                     __syncthreads();
-                    pend = 0;
                 }
                 // lowest address that is free in every list of the variable: every thread asks its
                 // lists for their lowest fit at or above the candidate, the maximum is the next
@@ -568,6 +581,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 // what a thread needs of its first list in every round, and of the first list it will
                 // take the block out of, is read once, ahead of the searches
                 uint32_t q_len = 0, q_base = 0, q_top = 0, u_len = 0, u_base = 0, u_cap = 0;
+                uint64_t u_tope = 0;                  // the topmost range of that list
                 if (tid < nq) {
                     const uint32_t id = seg_query_list(g, sp, tid);
                     q_len = lens[id];
@@ -580,14 +594,16 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                     u_cap = lst[id + 1] - u_base;
                 }
                 if (tid < nq && longv && q_len > 8) q_top = seg_start(pool[q_base + q_len - 1]);
+                if (tid < nu && longv) u_tope = pool[u_base + u_len - 1];
                 // A first candidate from one list, the one with most in it (the segment in the
                 // middle of the lifetime), read by one wave 64 entries at a time: asked from there,
                 // the others are spared the climb from address 0 over everything that does not
                 // concern them (a walk over thousands of ranges too small, when large variables
                 // come late).
                 uint32_t x_last = 0xFFFFFFFFu, he_last = 0;     // this thread's first list: its last answer and where that range ends
-                if (nq >= 8) {
+                if (first_cand) {
                     uint32_t first = 0;
+                    if (drain_late && wave == SEG_WAVES - 1) every_apply(g, lst, pool, lens, s_pend[ppar], pend, l);
                     if (wave == 0) {
                         const uint32_t id = seg_query_list(g, sp, sp.nf / 2);
                         const uint32_t len = read_lane(lens[id], 0);
@@ -601,12 +617,19 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                     o = max(max(s_max[flip][0], s_max[flip][1]), max(s_max[flip][2], s_max[flip][3]));
                     flip ^= 1;
                     have = o > 0;                     // (then start where the candidate would be, as in later rounds)
+                    if (drain_late && tid == 0) {     // thread 0's list to write is the list of everything
+                        u_len = lens[2 * g.K + g.T];
+                        if (longv) u_tope = pool[u_base + u_len - 1];
+                    }
                 }
+                pend = 0;
                 for (;;) {
                     uint32_t best = o, j = 0;
                     for (uint32_t i = tid; i < nq; i += SEG_THREADS, ++j) {
                         // the range that answered last holds the new candidate as well: nothing to read
                         if (j == 0 && have && x_last <= o && he_last - o >= s && he_last >= o) continue;
+                        // so does the topmost range (long-lived blocks end up high)
+                        if (j == 0 && have && q_top != 0 && o >= q_top) continue;
                         uint32_t len = q_len, base = q_base;
                         if (j > 0) {
                             const uint32_t id = seg_query_list(g, sp, i);
@@ -644,10 +667,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                     __syncthreads();
                     best = max(max(s_max[flip][0], s_max[flip][1]), max(s_max[flip][2], s_max[flip][3]));
                     flip ^= 1;
-                    have = true;
                     if (TRIAL && longv) ++trial_rounds;
                     if (best == o) break;             // every list accepts o
                     o = best;
+                    if (nq == 1) break;               // one list: its answer is the answer
+                    have = true;
                 }
                 if (TRIAL && longv) ++trial_vars;
                 const uint32_t en = o + s;
@@ -678,7 +702,16 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                         uint32_t hint = longv ? len - 1 : 0u;
                         const uint32_t q = seg_update_query(sp, i);
                         if (q < SEG_THREADS) hint = s_pos[q];
-                        c = seg_carve_plan(pool + base, len, o, en, hint);
+                        if (i0 == 0 && longv && seg_start(u_tope) <= o) {
+                            // inside the topmost range, as most long-lived blocks are: nothing to read
+                            c.i = len - 1;
+                            c.j = len;
+                            c.hs = seg_start(u_tope);
+                            c.last_end = SEG_INF;
+                            c.delta = c.hs < o ? 1 : 0;
+                        } else {
+                            c = seg_carve_plan(pool + base, len, o, en, hint);
+                        }
                         // a list never outgrows its room (it sees at most cap - 1 blocks); the check
                         // keeps the stores inside the list whatever happens
                         if (c.delta > 0 && len + 1 > cap) c.j = c.i;

@@ -140,28 +140,28 @@ LAP_HD SegCarve seg_carve_plan(const uint64_t *L, uint32_t len, uint32_t o, uint
     return c;
 }
 
-// entries j .. len-1 move by delta (+1, or down by -delta <= j), eight per step: all reads of a
+// entries j .. len-1 move by delta (+1, or down by -delta <= j), four per step: all reads of a
 // step come before its writes, and no later step reads what an earlier one wrote
 LAP_HD void seg_carve_shift(uint64_t *L, uint32_t len, uint32_t j, int32_t delta)
 {
     if (delta > 0) {
         for (uint32_t q = len; q > j;) {
-            const uint32_t m = q - j < 8 ? q - j : 8;
-            uint64_t v[8];
-            for (uint32_t k = 0; k < 8; ++k)
+            const uint32_t m = q - j < 4 ? q - j : 4;
+            uint64_t v[4];
+            for (uint32_t k = 0; k < 4; ++k)
                 if (k < m) v[k] = SEG_LD(L, q - 1 - k);
-            for (uint32_t k = 0; k < 8; ++k)
+            for (uint32_t k = 0; k < 4; ++k)
                 if (k < m) L[q - k] = v[k];
             q -= m;
         }
     } else if (delta < 0) {
         const uint32_t d = (uint32_t)-delta;
         for (uint32_t q = j; q < len;) {
-            const uint32_t m = len - q < 8 ? len - q : 8;
-            uint64_t v[8];
-            for (uint32_t k = 0; k < 8; ++k)
+            const uint32_t m = len - q < 4 ? len - q : 4;
+            uint64_t v[4];
+            for (uint32_t k = 0; k < 4; ++k)
                 if (k < m) v[k] = SEG_LD(L, q + k);
-            for (uint32_t k = 0; k < 8; ++k)
+            for (uint32_t k = 0; k < 4; ++k)
                 if (k < m) L[q + k - d] = v[k];
             q += m;
         }
