@@ -65,7 +65,7 @@ size_t ws_plan(uint32_t n, uint32_t T, uint32_t B)
            + up((size_t)n * 16)                                        // packed variable records
            + up(bn * 8)                                                // offsets of every ordering
            + 2 * up((seg_dir_cap(T) + 2) * 4)                          // segment lists: blocks per list, list starts
-           + up((size_t)B * seg_dir_cap(T) * 4)                        // and their lengths, per slot
+           + up((size_t)B * seg_dir_cap(T) * 8)                        // and their lengths and topmost ranges, per slot
            + ws_plan_lists(n, T, B);
 }
 
@@ -384,7 +384,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     const size_t dir_cap = seg_dir_cap(T);
     uint32_t *seg_cnt = c.take<uint32_t>(dir_cap + 2);
     uint32_t *seg_lst = c.take<uint32_t>(dir_cap + 2);
-    uint32_t *seg_len = c.take<uint32_t>((size_t)B * dir_cap);
+    uint32_t *seg_len = c.take<uint32_t>((size_t)B * dir_cap * 2);   // per slot: dir_cap lengths, then dir_cap topmost ranges
     // the placement kernels run one after the other and none needs another's lists: they share one region
     uint64_t *seg_pool = (uint64_t *)((char *)ws + c.used);
     Carver cw((char *)ws + c.used), cf((char *)ws + c.used);

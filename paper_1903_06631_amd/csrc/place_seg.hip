@@ -132,17 +132,18 @@ __device__ __forceinline__ bool seg_is_short(const SegSpan &sp)
     return !sp.whole && sp.n_query() <= SEG_SHORT_Q && sp.n_update() <= SEG_SHORT_U;
 }
 
-// entries at .. at + 63 (at < len), one per lane; lanes past the end repeat the last entry
-__device__ __forceinline__ uint64_t wv_chunk(const uint64_t *L, uint32_t len, uint32_t at, uint32_t l)
+// entries at .. at + 63 (at < len), one per lane; lanes past the end repeat the last entry (which
+// is not in memory: seg_core.h)
+__device__ __forceinline__ uint64_t wv_chunk(const uint64_t *L, uint32_t len, uint32_t top, uint32_t at, uint32_t l)
 {
     const uint32_t i = at + l;
-    return L[i < len ? i : len - 1];
+    return i + 1 < len ? L[i] : seg_pack(top, SEG_INF);
 }
 
 // Index of the first entry whose end is >= key.  In: x = wv_chunk(at); floor_known says that no
 // entry before `at` qualifies.  Out: (at, x) is a chunk that holds the answer.
-__device__ __forceinline__ uint32_t wv_lower_end(const uint64_t *L, uint32_t len, uint32_t key, bool floor_known,
-                                                 uint32_t l, uint32_t &at, uint64_t &x)
+__device__ __forceinline__ uint32_t wv_lower_end(const uint64_t *L, uint32_t len, uint32_t top, uint32_t key,
+                                                 bool floor_known, uint32_t l, uint32_t &at, uint64_t &x)
 {
     uint32_t lo = 0, hi = len - 1;           // the answer lies in [lo, hi]; entry hi qualifies (end = SEG_INF at the top)
     {
@@ -159,7 +160,7 @@ __device__ __forceinline__ uint32_t wv_lower_end(const uint64_t *L, uint32_t len
         const uint32_t m = hi - lo + 1;
         if (m <= 4u * WAVE) break;
         const uint32_t pos = lo + (uint32_t)(((uint64_t)(l + 1) * m) >> 6) - 1;    // ascending; lane 63 reads entry hi
-        const uint64_t y = L[pos];
+        const uint64_t y = pos + 1 < len ? L[pos] : seg_pack(top, SEG_INF);
         const uint64_t q = ballot(seg_end(y) >= key) | (1ull << 63);
         const uint32_t f = (uint32_t)__ffsll((unsigned long long)q) - 1;
         hi = read_lane(pos, (int)f);
@@ -170,7 +171,7 @@ __device__ __forceinline__ uint32_t wv_lower_end(const uint64_t *L, uint32_t len
     uint64_t c[4];
 #pragma unroll
     for (uint32_t k = 0; k < 4; ++k)
-        if (m > WAVE * k) c[k] = wv_chunk(L, len, lo + WAVE * k, l);     // lo + 64 k <= hi < len
+        if (m > WAVE * k) c[k] = wv_chunk(L, len, top, lo + WAVE * k, l);     // lo + 64 k <= hi < len
 #pragma unroll
     for (uint32_t k = 0; k < 4; ++k)
         if (m > WAVE * k) {
@@ -189,10 +190,15 @@ __device__ __forceinline__ uint32_t wv_lower_end(const uint64_t *L, uint32_t len
 // Lowest address >= o at which s granules are free (as seg_fit).  In: x = wv_chunk(at), no entry
 // before `at` ends at or above o + s.  Out: idx = the entry that holds the answer, (at, x) a chunk
 // that holds that entry.
-__device__ __forceinline__ uint32_t wv_fit(const uint64_t *L, uint32_t len, uint32_t o, uint32_t s, uint32_t l,
-                                           uint32_t &at, uint64_t &x, uint32_t &idx)
+__device__ __forceinline__ uint32_t wv_fit(const uint64_t *L, uint32_t len, uint32_t top, uint32_t o, uint32_t s,
+                                           uint32_t l, uint32_t &at, uint64_t &x, uint32_t &idx)
 {
-    const uint32_t i = wv_lower_end(L, len, o + s, true, l, at, x);
+    if (o >= top) {                           // inside the topmost range: nothing to read
+        idx = at = len - 1;
+        x = seg_pack(top, SEG_INF);
+        return o;
+    }
+    const uint32_t i = wv_lower_end(L, len, top, o + s, true, l, at, x);
     for (;;) {
         const uint32_t st = seg_start(x), en = seg_end(x), e = at + l;
         const uint32_t from = st > o ? st : o;
@@ -205,17 +211,15 @@ __device__ __forceinline__ uint32_t wv_fit(const uint64_t *L, uint32_t len, uint
         }
         if (at + WAVE >= len) break;          // not reached: the last entry always fits
         at += WAVE;
-        x = wv_chunk(L, len, at, l);
+        x = wv_chunk(L, len, top, at, l);
     }
-    idx = len - 1;
-    const uint64_t top = L[len - 1];
-    at = len - 1;
-    x = wv_chunk(L, len, at, l);
-    return seg_start(top) > o ? seg_start(top) : o;
+    idx = at = len - 1;
+    x = seg_pack(top, SEG_INF);
+    return top > o ? top : o;
 }
 
-// entries j .. len-1 move by delta (as seg_carve_shift), 256 per step: all reads of a step come
-// before its writes, and no later step reads what an earlier one wrote
+// entries j .. len-1 of those in memory move by delta (as seg_carve_shift), 256 per step: all reads
+// of a step come before its writes, and no later step reads what an earlier one wrote
 __device__ __forceinline__ void wv_shift(uint64_t *L, uint32_t len, uint32_t j, int32_t delta, uint32_t l)
 {
     if (delta > 0) {
@@ -300,37 +304,49 @@ __device__ __forceinline__ void wv_shift_lanes(uint64_t *pool, uint32_t base, ui
 
 // Takes [o, e) out of the free ranges (as seg_carve).  In: x = wv_chunk(at); either pos_known and
 // `pos` is the first entry that ends above o, inside the chunk, or the chunk is where to start
-// looking (floor_known as in wv_lower_end).  Returns the new length (the old one if the list has
-// no room: not reached, see k_seg_count).
-__device__ __forceinline__ uint32_t wv_carve(uint64_t *L, uint32_t len, uint32_t cap, uint32_t o, uint32_t e,
-                                             bool pos_known, uint32_t pos, bool floor_known, uint32_t l,
-                                             uint32_t at, uint64_t x)
+// looking (floor_known as in wv_lower_end).  len and top receive the new length and topmost range
+// (unchanged if the list has no room: not reached, see k_seg_count).
+__device__ __forceinline__ void wv_carve(uint64_t *L, uint32_t &len, uint32_t &top, uint32_t cap, uint32_t o, uint32_t e,
+                                         bool pos_known, uint32_t pos, bool floor_known, uint32_t l, uint32_t at,
+                                         uint64_t x)
 {
-    const uint32_t i = pos_known ? pos : wv_lower_end(L, len, o + 1, floor_known, l, at, x);
+    if (o >= top) {                                              // inside the topmost range: nothing to read
+        if (top < o) {
+            if (len + 1 > cap) return;
+            if (l == 0) L[len - 1] = seg_pack(top, o);
+            len += 1;
+        }
+        top = e;
+        return;
+    }
+    const uint32_t i = pos_known ? pos : wv_lower_end(L, len, top, o + 1, floor_known, l, at, x);
     const uint32_t d = i - at;                                   // < 64
     const uint64_t y = shfl64(x, (int)((l + d) & (WAVE - 1)));   // lane 0 holds entry i
     const uint32_t avail = min((uint32_t)WAVE - d, len - i);     // entries i .. i + avail - 1 are in lanes 0 .. avail - 1
     const uint64_t q = ballot(l < avail && seg_start(y) < e);    // a prefix: starts ascend
     const uint32_t gone = (uint32_t)__popcll((unsigned long long)q);
-    if (gone == 0) return len;                                   // nothing free inside [o, e)
+    if (gone == 0) return;                                       // nothing free inside [o, e)
     if (gone == avail && i + avail < len) {                      // more ranges than the chunk shows: one lane, entry by entry
-        uint32_t nlen = len;
-        if (l == 0) seg_carve(L, nlen, cap, o, e, i);
-        return read_lane(nlen, 0);
+        uint32_t nlen = len, ntop = top;
+        if (l == 0) seg_carve(L, nlen, ntop, cap, o, e, i);
+        len = read_lane(nlen, 0);
+        top = read_lane(ntop, 0);
+        return;
     }
     const uint32_t hs = read_lane(seg_start(y), 0), last_end = read_lane(seg_end(y), (int)gone - 1);
     const bool left = hs < o, right = last_end > e;
     const uint32_t keep = (left ? 1u : 0u) + (right ? 1u : 0u), j = i + gone;
     const int32_t delta = (int32_t)keep - (int32_t)gone;
-    if (delta > 0 && len + 1 > cap) return len;
-    wv_shift(L, len, j, delta, l);
+    if (delta > 0 && len + 1 > cap) return;
+    wv_shift(L, len - 1, j, delta, l);                           // the entries in memory: all but the last
     const uint32_t nlen = (uint32_t)((int32_t)len + delta);
+    const uint32_t w = i + (left ? 1u : 0u);                     // where the rest above e goes, if any
     if (l == 0) {
-        uint32_t w = i;
-        if (left) L[w++] = seg_pack(hs, o);
-        if (right) L[w++] = seg_pack(e, last_end);
+        if (left) L[i] = seg_pack(hs, o);                        // (never the last entry: one that ends above e follows)
+        if (right && w + 1 < nlen) L[w] = seg_pack(e, last_end);
     }
-    return nlen;
+    if (right && w + 1 >= nlen) top = e;                         // the last entry: not in memory
+    len = nlen;
 }
 
 // One variable with few lists, placed by one wave: the fixed point of k_place_seg with every list
@@ -342,14 +358,14 @@ __device__ __forceinline__ uint32_t wv_carve(uint64_t *L, uint32_t len, uint32_t
 __device__ __forceinline__ uint32_t place_short(const SegGeom &g, const SegSpan &sp, uint32_t nq, uint32_t nu,
                                                 uint32_t s, bool longv, uint32_t l,
                                                 const uint32_t *__restrict__ lst, uint64_t *pool, uint32_t *lens,
-                                                uint32_t &trial_rounds)
+                                                uint32_t *tops, uint32_t &trial_rounds)
 {
     const uint32_t qid = l < nq ? seg_query_list(g, sp, l) : 0u;
     const uint32_t uid = l < nu ? seg_update_list(g, sp, l) : 0u;
     const uint32_t qbase = lst[qid], ubase = lst[uid], ucap = lst[uid + 1] - ubase;
-    const uint32_t qlen = lens[qid];
-    const uint32_t ulen0 = lens[uid];
-    uint32_t ulen = ulen0;
+    const uint32_t qlen = lens[qid], qtop = tops[qid];
+    const uint32_t ulen0 = lens[uid], utop0 = tops[uid];
+    uint32_t ulen = ulen0, utop = utop0;
     // which asked list an update list is, if any
     uint32_t uq = SEG_SHORT_Q;
     for (uint32_t i = 0; i < nq; ++i)
@@ -361,11 +377,12 @@ __device__ __forceinline__ uint32_t place_short(const SegGeom &g, const SegSpan 
     uint32_t uat = (longv && ulen > (uint32_t)WAVE) ? ulen - WAVE : 0u;
 #pragma unroll
     for (uint32_t i = 0; i < SEG_SHORT_Q; ++i)
-        if (i < nq) xq[i] = wv_chunk(pool + read_lane(qbase, (int)i), read_lane(qlen, (int)i), 0u, l);
+        if (i < nq) xq[i] = wv_chunk(pool + read_lane(qbase, (int)i), read_lane(qlen, (int)i), read_lane(qtop, (int)i), 0u, l);
 #pragma unroll
     for (uint32_t u = 1; u < SEG_SHORT_U; ++u)
         if (u < nu && read_lane(uq, (int)u) == SEG_SHORT_Q)
-            xu[u] = wv_chunk(pool + read_lane(ubase, (int)u), read_lane(ulen, (int)u), read_lane(uat, (int)u), l);
+            xu[u] = wv_chunk(pool + read_lane(ubase, (int)u), read_lane(ulen, (int)u), read_lane(utop, (int)u),
+                             read_lane(uat, (int)u), l);
 
     uint32_t o = 0;
     for (;;) {
@@ -377,7 +394,8 @@ __device__ __forceinline__ uint32_t place_short(const SegGeom &g, const SegSpan 
             for (uint32_t k = 1; k < SEG_SHORT_Q; ++k)
                 if (i == k) x = xq[k];
             uint32_t at = read_lane(qat, (int)i), idx;
-            const uint32_t a = wv_fit(pool + read_lane(qbase, (int)i), read_lane(qlen, (int)i), o, s, l, at, x, idx);
+            const uint32_t a = wv_fit(pool + read_lane(qbase, (int)i), read_lane(qlen, (int)i), read_lane(qtop, (int)i), o, s,
+                                      l, at, x, idx);
 #pragma unroll
             for (uint32_t k = 0; k < SEG_SHORT_Q; ++k)
                 if (i == k) xq[k] = x;
@@ -405,11 +423,16 @@ __device__ __forceinline__ uint32_t place_short(const SegGeom &g, const SegSpan 
             if (!asked && u == k) x = xu[k];
         const uint32_t at = asked ? read_lane(qat, (int)(qi & (SEG_SHORT_Q - 1))) : read_lane(uat, (int)u);
         const uint32_t pos = read_lane(qidx, (int)(qi & (SEG_SHORT_Q - 1)));
-        const uint32_t nlen = wv_carve(pool + read_lane(ubase, (int)u), read_lane(ulen, (int)u), read_lane(ucap, (int)u),
-                                       o, en, asked, pos, asked || at == 0, l, at, x);
-        if (l == u) ulen = nlen;
+        uint32_t nlen = read_lane(ulen, (int)u), ntop = read_lane(utop, (int)u);
+        wv_carve(pool + read_lane(ubase, (int)u), nlen, ntop, read_lane(ucap, (int)u), o, en, asked, pos, asked || at == 0,
+                 l, at, x);
+        if (l == u) {
+            ulen = nlen;
+            utop = ntop;
+        }
     }
     if (l >= 1 && l < nu && ulen != ulen0) lens[uid] = ulen;
+    if (l >= 1 && l < nu && utop != utop0) tops[uid] = utop;
     // the wave's later reads of these lists come after these writes (same wave: in order)
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     return o;
@@ -419,20 +442,22 @@ __device__ __forceinline__ uint32_t place_short(const SegGeom &g, const SegSpan 
 // wave while the others place the next group (nothing but a variable that lives through the
 // whole time line asks that list, and such a variable waits for this).
 __device__ __forceinline__ void every_apply(const SegGeom &g, const uint32_t *__restrict__ lst, uint64_t *pool,
-                                            uint32_t *lens, const uint4 *pend, uint32_t n_pend, uint32_t l)
+                                            uint32_t *lens, uint32_t *tops, const uint4 *pend, uint32_t n_pend,
+                                            uint32_t l)
 {
     const uint32_t id = 2 * g.K + g.T;
     const uint32_t base = read_lane(lst[id], 0), cap = read_lane(lst[id + 1], 0) - base;
-    const uint32_t len0 = read_lane(lens[id], 0);
-    uint32_t len = len0;
+    const uint32_t len0 = read_lane(lens[id], 0), top0 = read_lane(tops[id], 0);
+    uint32_t len = len0, top = top0;
     uint64_t *L = pool + base;
     for (uint32_t m = 0; m < n_pend; ++m) {
         const uint4 pe = pend[m];
         const uint32_t o = read_lane(pe.x, 0), en = read_lane(pe.y, 0), at = (read_lane(pe.z, 0) && len > (uint32_t)WAVE) ? len - WAVE : 0u;
-        const uint64_t x = wv_chunk(L, len, at, l);
-        len = wv_carve(L, len, cap, o, en, false, 0u, at == 0, l, at, x);
+        const uint64_t x = wv_chunk(L, len, top, at, l);
+        wv_carve(L, len, top, cap, o, en, false, 0u, at == 0, l, at, x);
     }
     if (l == 0 && len != len0) lens[id] = len;
+    if (l == 0 && top != top0) tops[id] = top;
 }
 
 // ---------------------------------------------------------------------------
@@ -447,7 +472,7 @@ struct SegArgs {
     PlanHeader *hdr;
     const uint32_t *lst;         // [n_lists + 1] start of every list inside a slot
     uint64_t *pool;              // [slots][seg_need]
-    uint32_t *lens;              // [slots][dir_cap]
+    uint32_t *lens;              // [slots][2 dir_cap]: lengths, then starts of the topmost ranges
     uint32_t dir_cap;
     uint64_t *offs;              // [B][n] in rank order
     uint64_t *fps;               // [B]
@@ -485,7 +510,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
     uint32_t trial_rounds = 0, trial_vars = 0;         // of the variables all threads place together ...
     uint32_t short_rounds = 0, short_vars = 0;         // ... and of those this wave places alone
     uint64_t *pool = A.pool + (size_t)blockIdx.x * hdr->seg_need;
-    uint32_t *lens = A.lens + (size_t)blockIdx.x * A.dir_cap;
+    uint32_t *lens = A.lens + (size_t)blockIdx.x * 2 * A.dir_cap;    // per slot: the lists' lengths ...
+    uint32_t *tops = lens + A.dir_cap;                               // ... and where their topmost ranges start
     const uint32_t *__restrict__ lst = A.lst;
 
     // The workgroups take orderings from a common counter, so that one that drew quick orderings goes
@@ -508,8 +534,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
         uint64_t *offs = A.offs + (size_t)b * A.n;
         // every list starts as one range: the whole address space
         for (uint32_t j = tid; j < nl; j += SEG_THREADS) {
-            pool[lst[j]] = seg_pack(0u, SEG_INF);
             lens[j] = 1;
+            tops[j] = 0;
         }
         __syncthreads();
         uint32_t fp = 0, flip = 0;
@@ -546,7 +572,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                         const uint32_t aq = read_lane(rec.x, (int)q), fq = read_lane(rec.y, (int)q), sq = read_lane(rec.z, (int)q);
                         const SegSpan sq_ = seg_span(g, aq, fq);
                         const bool lq = fq - aq > 1;
-                        const uint32_t o = place_short(g, sq_, sq_.n_query(), sq_.n_update(), sq, lq, l, lst, pool, lens, short_rounds);
+                        const uint32_t o = place_short(g, sq_, sq_.n_query(), sq_.n_update(), sq, lq, l, lst, pool, lens, tops, short_rounds);
                         if (lq) ++short_vars;
                         fp = max(fp, o + sq);
                         if (l == 0) {
@@ -554,7 +580,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                             s_pend[ppar ^ 1][wave] = make_uint4(o, o + sq, lq ? 1u : 0u, 0u);
                         }
                     } else if (wave == SEG_WAVES - 1 && pend) {
-                        every_apply(g, lst, pool, lens, s_pend[ppar], pend, l);
+                        every_apply(g, lst, pool, lens, tops, s_pend[ppar], pend, l);
                     }
                     __syncthreads();
                     ppar ^= 1;
@@ -569,7 +595,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 const bool first_cand = nq >= 8;
                 const bool drain_late = pend != 0 && first_cand && nq <= SEG_THREADS - WAVE;
                 if (pend && !drain_late) {
-                    if (wave == SEG_WAVES - 1) every_apply(g, lst, pool, lens, s_pend[ppar], pend, l);
+                    if (wave == SEG_WAVES - 1) every_apply(g, lst, pool, lens, tops, s_pend[ppar], pend, l);
                     __syncthreads();
                 }
                 // lowest address that is free in every list of the variable: every thread asks its
@@ -580,21 +606,20 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 uint32_t o = 0;
                 // what a thread needs of its first list in every round, and of the first list it will
                 // take the block out of, is read once, ahead of the searches
-                uint32_t q_len = 0, q_base = 0, q_top = 0, u_len = 0, u_base = 0, u_cap = 0;
-                uint64_t u_tope = 0;                  // the topmost range of that list
+                uint32_t q_len = 0, q_base = 0, q_top = 0, u_len = 0, u_base = 0, u_cap = 0, u_top = 0;
                 if (tid < nq) {
                     const uint32_t id = seg_query_list(g, sp, tid);
                     q_len = lens[id];
+                    q_top = tops[id];
                     q_base = lst[id];
                 }
                 if (tid < nu) {
                     const uint32_t id = seg_update_list(g, sp, tid);
                     u_len = lens[id];
+                    u_top = tops[id];
                     u_base = lst[id];
                     u_cap = lst[id + 1] - u_base;
                 }
-                if (tid < nq && longv && q_len > 8) q_top = seg_start(pool[q_base + q_len - 1]);
-                if (tid < nu && longv) u_tope = pool[u_base + u_len - 1];
                 // A first candidate from one list, the one with most in it (the segment in the
                 // middle of the lifetime), read by one wave 64 entries at a time: asked from there,
                 // the others are spared the climb from address 0 over everything that does not
@@ -603,14 +628,14 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 uint32_t x_last = 0xFFFFFFFFu, he_last = 0;     // this thread's first list: its last answer and where that range ends
                 if (first_cand) {
                     uint32_t first = 0;
-                    if (drain_late && wave == SEG_WAVES - 1) every_apply(g, lst, pool, lens, s_pend[ppar], pend, l);
+                    if (drain_late && wave == SEG_WAVES - 1) every_apply(g, lst, pool, lens, tops, s_pend[ppar], pend, l);
                     if (wave == 0) {
                         const uint32_t id = seg_query_list(g, sp, sp.nf / 2);
-                        const uint32_t len = read_lane(lens[id], 0);
+                        const uint32_t len = read_lane(lens[id], 0), top = read_lane(tops[id], 0);
                         const uint64_t *L = pool + read_lane(lst[id], 0);
                         uint32_t at = 0, idx;
-                        uint64_t x = wv_chunk(L, len, 0u, l);
-                        first = wv_fit(L, len, 0u, s, l, at, x, idx);
+                        uint64_t x = wv_chunk(L, len, top, 0u, l);
+                        first = wv_fit(L, len, top, 0u, s, l, at, x, idx);
                     }
                     if (l == 0) s_max[flip][wave] = first;
                     __syncthreads();
@@ -619,7 +644,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                     have = o > 0;                     // (then start where the candidate would be, as in later rounds)
                     if (drain_late && tid == 0) {     // thread 0's list to write is the list of everything
                         u_len = lens[2 * g.K + g.T];
-                        if (longv) u_tope = pool[u_base + u_len - 1];
+                        u_top = tops[2 * g.K + g.T];
                     }
                 }
                 pend = 0;
@@ -629,11 +654,12 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                         // the range that answered last holds the new candidate as well: nothing to read
                         if (j == 0 && have && x_last <= o && he_last - o >= s && he_last >= o) continue;
                         // so does the topmost range (long-lived blocks end up high)
-                        if (j == 0 && have && q_top != 0 && o >= q_top) continue;
-                        uint32_t len = q_len, base = q_base;
+                        if (j == 0 && o >= q_top) continue;
+                        uint32_t len = q_len, base = q_base, top = q_top;
                         if (j > 0) {
                             const uint32_t id = seg_query_list(g, sp, i);
                             len = lens[id];
+                            top = tops[id];
                             base = lst[id];
                         }
                         // Where to look first.  The first round asks from address 0 and is answered
@@ -646,14 +672,13 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                         if (have) {
                             if (j < SEG_MEMO) idx = memo[j];
                             if (longv && len > 8) {
-                                const uint32_t top = j > 0 ? seg_start(L[len - 1]) : q_top;
                                 if (top) {
                                     const uint64_t at = (uint64_t)len * ((uint64_t)o + s) / top;
                                     idx = max(idx, (uint32_t)(at < len - 1 ? at : len - 1));
                                 }
                             }
                         }
-                        const uint32_t x = seg_fit(L, len, o, s, idx, he);
+                        const uint32_t x = seg_fit(L, len, top, o, s, idx, he);
                         if (j < SEG_MEMO) memo[j] = idx;
                         if (j == 0) {
                             x_last = x;
@@ -684,7 +709,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                 for (uint32_t i0 = 0; i0 < nu; i0 += SEG_THREADS) {
                     const uint32_t i = i0 + tid;
                     const bool mine = i < nu;
-                    uint32_t base = u_base, cap = u_cap, len = u_len, id = 0;
+                    uint32_t base = u_base, cap = u_cap, len = u_len, top = u_top, id = 0;
                     SegCarve c;
                     c.i = c.j = 0;
                     c.delta = 0;
@@ -694,35 +719,32 @@ __global__ __launch_bounds__(SEG_THREADS) void k_place_seg(SegArgs A)
                             base = lst[id];
                             cap = lst[id + 1] - base;
                             len = lens[id];
+                            top = tops[id];
                         }
-                        // Where to look first.  A list that was asked: the range that answered holds
-                        // the block.  Otherwise long-lived blocks end up high, one-step ones low (the
-                        // place the address would have if the ranges were spread evenly below the
-                        // top: measured worse).
+                        // Where to look first, if the block is not inside the topmost range (as most
+                        // long-lived blocks are: then nothing is read).  A list that was asked: the
+                        // range that answered holds the block.  Otherwise long-lived blocks end up
+                        // high, one-step ones low (the place the address would have if the ranges
+                        // were spread evenly below the top: measured worse).
                         uint32_t hint = longv ? len - 1 : 0u;
                         const uint32_t q = seg_update_query(sp, i);
                         if (q < SEG_THREADS) hint = s_pos[q];
-                        if (i0 == 0 && longv && seg_start(u_tope) <= o) {
-                            // inside the topmost range, as most long-lived blocks are: nothing to read
-                            c.i = len - 1;
-                            c.j = len;
-                            c.hs = seg_start(u_tope);
-                            c.last_end = SEG_INF;
-                            c.delta = c.hs < o ? 1 : 0;
-                        } else {
-                            c = seg_carve_plan(pool + base, len, o, en, hint);
-                        }
+                        c = seg_carve_plan(pool + base, len, top, o, en, hint);
                         // a list never outgrows its room (it sees at most cap - 1 blocks); the check
                         // keeps the stores inside the list whatever happens
                         if (c.delta > 0 && len + 1 > cap) c.j = c.i;
                     }
                     const bool act = c.j != c.i;
-                    const uint32_t tail = act && c.delta != 0 ? len - c.j : 0u;
+                    // of the entries from c.j on, those in memory (all but the last) move
+                    const uint32_t mem = len - 1;
+                    const uint32_t tail = act && c.delta != 0 && c.j < mem ? mem - c.j : 0u;
                     if (tail > 0 && tail <= SEG_TAIL_SELF) seg_carve_shift(pool + base, len, c.j, c.delta);
-                    wv_shift_lanes(pool, base, tail > SEG_TAIL_SELF ? tail : 0u, c.delta > 0 ? len : c.j, c.delta, l);
+                    wv_shift_lanes(pool, base, tail > SEG_TAIL_SELF ? tail : 0u, c.delta > 0 ? mem : c.j, c.delta, l);
                     if (act) {
-                        seg_carve_finish(pool + base, c, o, en);
-                        if (c.delta != 0) lens[id] = (uint32_t)((int32_t)len + c.delta);
+                        const uint32_t new_len = (uint32_t)((int32_t)len + c.delta), top0 = top;
+                        seg_carve_finish(pool + base, new_len, top, c, o, en);
+                        if (c.delta != 0) lens[id] = new_len;
+                        if (top != top0) tops[id] = top;
                     }
                 }
                 __syncthreads();

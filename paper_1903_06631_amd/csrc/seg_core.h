@@ -4,9 +4,12 @@
 // host-side bounds checker.
 //
 // A list holds the free address ranges with respect to some set of placed blocks, sorted by
-// address, one 64-bit word each: start << 32 | end, in granules.  The last entry always is the
-// range above the highest block, with end = SEG_INF.  Starts and ends ascend strictly
-// (start_i < end_i < start_{i+1}), so a list can be binary searched by end.
+// address, one 64-bit word each: start << 32 | end, in granules.  Starts and ends ascend strictly
+// (start_i < end_i < start_{i+1}), so a list can be binary searched by end.  The last of a list's
+// `len` >= 1 ranges is the one above the highest block, with end = SEG_INF; of that one only
+// the start is kept, apart from the others (`top`, in an array of its own with one word per list):
+// long-lived blocks go there nearly always, and then neither the question nor the change touches
+// the list's memory.  L holds the len - 1 ranges below.
 #pragma once
 #include <stdint.h>
 
@@ -26,12 +29,18 @@ LAP_HD uint64_t seg_pack(uint32_t start, uint32_t end) { return ((uint64_t)start
 LAP_HD uint32_t seg_start(uint64_t x) { return (uint32_t)(x >> 32); }
 LAP_HD uint32_t seg_end(uint64_t x) { return (uint32_t)x; }
 
+// entry i < len of a list
+LAP_HD uint64_t seg_entry(const uint64_t *L, uint32_t len, uint32_t top, uint32_t i)
+{
+    return i + 1 < len ? SEG_LD(L, i) : seg_pack(top, SEG_INF);
+}
+
 // Index of the first of the `len` >= 1 entries whose end is >= key (key < SEG_INF or the answer is
 // the last entry: its end is SEG_INF).  The search runs outward from `hint` in doubling steps and
 // finishes with a binary search, so an answer near the hint costs two or three probes.  (Probing
 // eight ways at a time shortens the chain of dependent reads but reads more: measured slower,
 // the lists' scattered reads are bound by their number, not by their latency.)
-LAP_HD uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uint32_t hint)
+LAP_HD uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t top, uint32_t key, uint32_t hint)
 {
     uint32_t lo, hi;                         // the answer lies in [lo, hi]
     if (hint == SEG_NOHINT) {                // nothing known: plain binary search
@@ -41,13 +50,13 @@ LAP_HD uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uin
         hint = len - 1;
     }
     if (hint == SEG_NOHINT) {
-    } else if (seg_end(SEG_LD(L, hint)) >= key) {
+    } else if (seg_end(seg_entry(L, len, top, hint)) >= key) {
         lo = 0;
         hi = hint;
         uint32_t step = 1;
         while (hi > 0) {
             const uint32_t p = hi > step ? hi - step : 0;
-            if (seg_end(SEG_LD(L, p)) >= key) {
+            if (seg_end(SEG_LD(L, p)) >= key) {          // p < hint <= len - 1: in memory
                 hi = p;
                 step <<= 1;
             } else {
@@ -61,7 +70,7 @@ LAP_HD uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uin
         uint32_t step = 1;
         while (lo < hi) {
             const uint32_t p = (hi - lo > step - 1) ? lo + step - 1 : hi;
-            if (seg_end(SEG_LD(L, p)) >= key) {
+            if (seg_end(seg_entry(L, len, top, p)) >= key) {
                 hi = p;
                 break;
             }
@@ -70,7 +79,7 @@ LAP_HD uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uin
         }
     }
     while (lo < hi) {
-        const uint32_t mid = lo + ((hi - lo) >> 1);
+        const uint32_t mid = lo + ((hi - lo) >> 1);      // mid < hi <= len - 1: in memory
         if (seg_end(SEG_LD(L, mid)) >= key) hi = mid; else lo = mid + 1;
     }
     return lo;
@@ -79,15 +88,20 @@ LAP_HD uint32_t seg_lower_end(const uint64_t *L, uint32_t len, uint32_t key, uin
 // Lowest address >= o at which s granules are free (o + s < SEG_INF).  idx: in, where to start
 // looking; out, the entry that holds the answer.  hole_end receives that entry's end (where the
 // free range around the answer stops).
-LAP_HD uint32_t seg_fit(const uint64_t *L, uint32_t len, uint32_t o, uint32_t s, uint32_t &idx,
-                               uint32_t &hole_end)
+LAP_HD uint32_t seg_fit(const uint64_t *L, uint32_t len, uint32_t top, uint32_t o, uint32_t s, uint32_t &idx,
+                        uint32_t &hole_end)
 {
-    uint32_t i = seg_lower_end(L, len, o + s, idx);
+    if (o >= top) {                          // inside the topmost range: nothing to read
+        idx = len - 1;
+        hole_end = SEG_INF;
+        return o;
+    }
+    uint32_t i = seg_lower_end(L, len, top, o + s, idx);
     for (;;) {
         // four entries per step: their reads do not wait for one another (past the end, the last
         // entry again, which always fits: the loop ends inside the list)
         uint64_t x[4];
-        for (uint32_t k = 0; k < 4; ++k) x[k] = SEG_LD(L, i + k < len ? i + k : len - 1);
+        for (uint32_t k = 0; k < 4; ++k) x[k] = seg_entry(L, len, top, i + k < len ? i + k : len - 1);
         for (uint32_t k = 0; k < 4; ++k) {
             const uint32_t st = seg_start(x[k]), en = seg_end(x[k]);
             const uint32_t from = st > o ? st : o;
@@ -110,11 +124,19 @@ struct SegCarve {
     int32_t delta;           // what the length changes by: +1 (one range becomes two), 0, or -(ranges that go)
 };
 
-LAP_HD SegCarve seg_carve_plan(const uint64_t *L, uint32_t len, uint32_t o, uint32_t e, uint32_t hint)
+LAP_HD SegCarve seg_carve_plan(const uint64_t *L, uint32_t len, uint32_t top, uint32_t o, uint32_t e, uint32_t hint)
 {
     SegCarve c;
-    c.i = seg_lower_end(L, len, o + 1, hint);                    // first range that ends above o
-    const uint64_t x = SEG_LD(L, c.i);
+    if (o >= top) {                                              // inside the topmost range: nothing to read
+        c.i = len - 1;
+        c.j = len;
+        c.hs = top;
+        c.last_end = SEG_INF;
+        c.delta = top < o ? 1 : 0;
+        return c;
+    }
+    c.i = seg_lower_end(L, len, top, o + 1, hint);               // first range that ends above o
+    const uint64_t x = seg_entry(L, len, top, c.i);
     c.hs = seg_start(x);
     c.last_end = seg_end(x);
     c.j = c.i;
@@ -123,7 +145,7 @@ LAP_HD SegCarve seg_carve_plan(const uint64_t *L, uint32_t len, uint32_t o, uint
     uint32_t j = c.i + 1;
     for (bool more = j < len; more;) {                           // four entries per step, as in seg_fit
         uint64_t y[4];
-        for (uint32_t k = 0; k < 4; ++k) y[k] = SEG_LD(L, j + k < len ? j + k : len - 1);
+        for (uint32_t k = 0; k < 4; ++k) y[k] = seg_entry(L, len, top, j + k < len ? j + k : len - 1);
         for (uint32_t k = 0; k < 4 && more; ++k) {
             if (seg_start(y[k]) >= e) {
                 more = false;
@@ -140,12 +162,14 @@ LAP_HD SegCarve seg_carve_plan(const uint64_t *L, uint32_t len, uint32_t o, uint
     return c;
 }
 
-// entries j .. len-1 move by delta (+1, or down by -delta <= j), four per step: all reads of a
-// step come before its writes, and no later step reads what an earlier one wrote
+// The entries j .. len-1 move by delta (+1, or down by -delta <= j); those in memory (all but the
+// last) four per step: all reads of a step come before its writes, and no later step reads
+// what an earlier one wrote.
 LAP_HD void seg_carve_shift(uint64_t *L, uint32_t len, uint32_t j, int32_t delta)
 {
+    const uint32_t mem = len - 1;                                // entries 0 .. mem-1 are in memory
     if (delta > 0) {
-        for (uint32_t q = len; q > j;) {
+        for (uint32_t q = mem; q > j;) {
             const uint32_t m = q - j < 4 ? q - j : 4;
             uint64_t v[4];
             for (uint32_t k = 0; k < 4; ++k)
@@ -156,8 +180,8 @@ LAP_HD void seg_carve_shift(uint64_t *L, uint32_t len, uint32_t j, int32_t delta
         }
     } else if (delta < 0) {
         const uint32_t d = (uint32_t)-delta;
-        for (uint32_t q = j; q < len;) {
-            const uint32_t m = len - q < 4 ? len - q : 4;
+        for (uint32_t q = j; q < mem;) {
+            const uint32_t m = mem - q < 4 ? mem - q : 4;
             uint64_t v[4];
             for (uint32_t k = 0; k < 4; ++k)
                 if (k < m) v[k] = SEG_LD(L, q + k);
@@ -168,23 +192,30 @@ LAP_HD void seg_carve_shift(uint64_t *L, uint32_t len, uint32_t j, int32_t delta
     }
 }
 
-LAP_HD void seg_carve_finish(uint64_t *L, const SegCarve &c, uint32_t o, uint32_t e)
+// new_len = the length after the change; the last entry's start goes to `top`, the others to memory
+LAP_HD void seg_carve_finish(uint64_t *L, uint32_t new_len, uint32_t &top, const SegCarve &c, uint32_t o, uint32_t e)
 {
     uint32_t w = c.i;
-    if (c.hs < o) L[w++] = seg_pack(c.hs, o);
-    if (c.last_end > e) L[w++] = seg_pack(e, c.last_end);
+    if (c.hs < o) {                                              // (never the last entry: one that ends above e follows,
+        L[w] = seg_pack(c.hs, o);                                //  written below or already there)
+        ++w;
+    }
+    if (c.last_end > e) {
+        if (w + 1 < new_len) L[w] = seg_pack(e, c.last_end); else top = e;
+    }
 }
 
-// All three.  A list grows by at most one entry per call; `cap` is the room it has.  Returns false,
-// and leaves the list alone, if it would outgrow cap.
-LAP_HD bool seg_carve(uint64_t *L, uint32_t &len, uint32_t cap, uint32_t o, uint32_t e, uint32_t hint)
+// All three.  A list grows by at most one entry per call; `cap` is the room it has (entries in
+// memory + 1).  Returns false, and leaves the list alone, if it would outgrow cap.
+LAP_HD bool seg_carve(uint64_t *L, uint32_t &len, uint32_t &top, uint32_t cap, uint32_t o, uint32_t e, uint32_t hint)
 {
-    const SegCarve c = seg_carve_plan(L, len, o, e, hint);
+    const SegCarve c = seg_carve_plan(L, len, top, o, e, hint);
     if (c.j == c.i) return true;
     if (c.delta > 0 && len + 1 > cap) return false;
     seg_carve_shift(L, len, c.j, c.delta);
-    seg_carve_finish(L, c, o, e);
-    len = (uint32_t)((int32_t)len + c.delta);
+    const uint32_t new_len = (uint32_t)((int32_t)len + c.delta);
+    seg_carve_finish(L, new_len, top, c, o, e);
+    len = new_len;
     return true;
 }
 

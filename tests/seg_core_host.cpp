@@ -19,9 +19,13 @@ int seg_host_unit(uint32_t seed, uint32_t iters, uint32_t max_blocks, uint32_t s
     std::mt19937 rng(seed);
     for (uint32_t it = 0; it < iters; ++it) {
         std::vector<char> occ(space, 0);
-        std::vector<uint64_t> L(max_blocks + 2);
-        uint32_t len = 1, cap = 1;
-        L[0] = seg_pack(0, SEG_INF);
+        std::vector<uint64_t> L(max_blocks + 2);             // the ranges below the topmost one
+        uint32_t len = 1, cap = 1, top = 0;
+        auto full = [&]() {                                  // the list as a whole: memory, then (top, SEG_INF)
+            std::vector<uint64_t> all(L.begin(), L.begin() + (len - 1));
+            all.push_back(seg_pack(top, SEG_INF));
+            return all;
+        };
         const uint32_t nb = rng() % (max_blocks + 1);
         for (uint32_t k = 0; k < nb; ++k) {
             const uint32_t o = rng() % (space - 1);
@@ -29,7 +33,7 @@ int seg_host_unit(uint32_t seed, uint32_t iters, uint32_t max_blocks, uint32_t s
             if (e > space) e = space;
             ++cap;                                           // a block more: an entry more of room
             const uint32_t hint = rng() % 3 == 0 ? SEG_NOHINT : rng() % (len + 2);
-            if (!seg_carve(L.data(), len, cap, o, e, hint)) return 1;
+            if (!seg_carve(L.data(), len, top, cap, o, e, hint)) return 1;
             for (uint32_t q = o; q < e; ++q) occ[q] = 1;
             std::vector<uint64_t> want;                      // the free runs of the bitmap
             for (uint32_t q = 0; q < space;) {
@@ -39,12 +43,13 @@ int seg_host_unit(uint32_t seed, uint32_t iters, uint32_t max_blocks, uint32_t s
                 want.push_back(seg_pack(st, q == space ? SEG_INF : q));
             }
             if (want.empty() || seg_end(want.back()) != SEG_INF) want.push_back(seg_pack(space, SEG_INF));
-            if (std::vector<uint64_t>(L.begin(), L.begin() + len) != want) return 2;
+            if (full() != want) return 2;
         }
         for (int k = 0; k < 16; ++k) {
             const uint32_t o = rng() % space, s = 1 + rng() % std::max<uint32_t>(1, space / 6);
             uint32_t idx = rng() % 3 == 0 ? SEG_NOHINT : rng() % (len + 2), he = 0;
-            const uint32_t got = seg_fit(L.data(), len, o, s, idx, he);
+            const std::vector<uint64_t> F = full();
+            const uint32_t got = seg_fit(L.data(), len, top, o, s, idx, he);
             uint32_t want = o;
             for (;;) {
                 bool ok = true;
@@ -53,11 +58,11 @@ int seg_host_unit(uint32_t seed, uint32_t iters, uint32_t max_blocks, uint32_t s
                 ++want;
             }
             if (got != want) return 3;
-            if (idx >= len || seg_start(L[idx]) > got || seg_end(L[idx]) - got < s || he != seg_end(L[idx])) return 4;
+            if (idx >= len || seg_start(F[idx]) > got || seg_end(F[idx]) - got < s || he != seg_end(F[idx])) return 4;
             const uint32_t key = rng() % (space + 4);
-            const uint32_t at = seg_lower_end(L.data(), len, key, rng() % 2 ? SEG_NOHINT : rng() % (len + 3));
+            const uint32_t at = seg_lower_end(L.data(), len, top, key, rng() % 2 ? SEG_NOHINT : rng() % (len + 3));
             uint32_t lin = 0;
-            while (seg_end(L[lin]) < key) ++lin;
+            while (seg_end(F[lin]) < key) ++lin;
             if (at != lin) return 5;
         }
     }
@@ -97,7 +102,7 @@ int seg_host_place(uint32_t n, uint32_t T, const uint32_t *size_granules, const 
     *pool_entries = lst[nl];
     std::vector<uint64_t> pool(lst[nl]);
     std::vector<uint32_t> lens(nl, 1);
-    for (uint32_t j = 0; j < nl; ++j) pool[lst[j]] = seg_pack(0, SEG_INF);
+    std::vector<uint32_t> tops(nl, 0);
     uint64_t rounds = 0;
     for (uint32_t r = 0; r < n; ++r) {
         const uint32_t v = perm[r], a = alloc[v], f = free_[v], s = size_granules[v];
@@ -117,14 +122,14 @@ int seg_host_place(uint32_t n, uint32_t T, const uint32_t *size_granules, const 
                 if (have) {                                  // as in the kernel: last answer, or the evenly-spread estimate
                     idx = memo[i];
                     if (longv && len > 8) {
-                        const uint32_t top = seg_start(L[len - 1]);
+                        const uint32_t top = tops[id];
                         if (top) {
                             const uint64_t at = (uint64_t)len * ((uint64_t)o + s) / top;
                             idx = std::max(idx, (uint32_t)(at < len - 1 ? at : len - 1));
                         }
                     }
                 }
-                best = std::max(best, seg_fit(L, len, o, s, idx, he));
+                best = std::max(best, seg_fit(L, len, tops[id], o, s, idx, he));
                 memo[i] = idx;
             }
             have = true;
@@ -134,7 +139,7 @@ int seg_host_place(uint32_t n, uint32_t T, const uint32_t *size_granules, const 
         off_granules[v] = o;
         for (uint32_t i = 0; i < nu; ++i) {
             const uint32_t id = seg_update_list(g, sp, i);
-            if (!seg_carve(&pool[lst[id]], lens[id], cnt[id] + 1, o, o + s, longv ? lens[id] - 1 : 0u)) return 3;
+            if (!seg_carve(&pool[lst[id]], lens[id], tops[id], cnt[id] + 1, o, o + s, longv ? lens[id] - 1 : 0u)) return 3;
         }
     }
     *rounds_out = rounds;
