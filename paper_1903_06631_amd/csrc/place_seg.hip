@@ -21,6 +21,11 @@
 // lifetime / w + w lists instead of `lifetime` per-step lists; w is chosen per trace to make
 // the total smallest.
 //
+// A variable with few lists (two thirds of them: one- and two-step variables) is worked on by one
+// wave instead, 64 entries per read, up to three such variables side by side (further down).  The
+// topmost range of every list is kept apart, one word per list (seg_core.h): long-lived blocks go
+// there nearly always, and then the list's memory is not touched.
+//
 // One workgroup of 256 threads works on one ordering at a time in its own slot of the list
 // pool and then takes the next ordering from a common counter; the number of slots is what the
 // workspace has room for.  Results are identical to placing the variables one by one in rank
