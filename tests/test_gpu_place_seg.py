@@ -92,6 +92,60 @@ def test_segment_lists_explicit_permutation_and_more_orderings_than_slots(lap, o
     _check(lap, oracle_mod, tr, kinds, seeds, explicit_np=explicit)
 
 
+def _unit_holes_trace(M, fillers=70):
+    """Two-step variables A_i (steps 0-1) and one-step variables B_i (step 0) of one unit each, placed in the
+    order A_0 B_0 A_1 B_1 ..., land at addresses 0, 1, 2, 3, ...: at step 1 the A's then leave M holes of one
+    unit between them.  What follows lives at step 1: a variable of two units has to pass all of those holes,
+    variables of one unit fill them one by one (each time a range vanishes from a list of M), variables of
+    steps 1-2 ask three lists.  `fillers` long-lived variables elsewhere on the time line keep the sum of the
+    lifetimes above what per-step lists take.  Returns the trace and the rank order."""
+    from traces.dnn import Trace
+    U = 512
+    size, alloc, free = [], [], []
+    def add(units, a, f):
+        size.append(units * U); alloc.append(a); free.append(f)
+        return len(size) - 1
+    order = []
+    for i in range(M):
+        order.append(add(1, 0, 2))
+        order.append(add(1, 0, 1))
+    order.append(add(2, 1, 2))                       # walks over M unit holes to the top
+    for j in range(150):
+        order.append(add(1, 1, 2))                   # fills the lowest hole exactly
+        if j % 10 == 0:
+            order.append(add(2, 1, 2))
+        if j % 7 == 0:
+            order.append(add(1, 1, 3))               # steps 1-2
+    order.append(add(3, 0, 2))
+    T = 4099
+    for k in range(fillers):
+        order.insert((k * 977) % len(order), add(5 + k % 3, 3 + (k % 5), T - (k % 7)))
+    n = len(size)
+    a, f = np.asarray(alloc, np.uint32), np.asarray(free, np.uint32)
+    tr = Trace(name="unit-holes", n_steps=T, size=np.asarray(size, np.uint64), alloc=a, free=f,
+               gap_lo=a.copy(), gap_hi=(f - 1).astype(np.uint32), meta={"cfg": 0})
+    assert sorted(order) == list(range(n))
+    return tr, np.asarray(order, np.uint32)
+
+
+def test_lists_of_many_thousand_ranges(lap, oracle_mod):
+    """Lists far longer than what the random traces grow (20 000 ranges in one list): the one-wave path's
+    searches take two 64-way sampling levels, its walks pass hundreds of chunks, and a range that vanishes or
+    splits low in the list moves a tail of thousands of entries."""
+    tr, order = _unit_holes_trace(20000)
+    assert oracle_mod.validate_trace(tr) == 0
+    assert int((tr.free.astype(np.int64) - tr.alloc).sum()) + tr.n_steps > 6 * tr.n_vars      # no per-step lists
+    kinds, seeds = make_orderings(6)
+    kinds, seeds = kinds[3:6].copy(), seeds[3:6]                  # two seeded shuffles and the order above
+    kinds[2] = 5
+    explicit = {2: order}
+    _check(lap, oracle_mod, tr, kinds, seeds, explicit_np=explicit)
+    # the explicit order really leaves the holes: the first variable of two units sits above all A's
+    perm, off, _ = oracle_all_orderings(oracle_mod, tr, kinds, seeds, explicit, which=[2])[2]
+    two_units = int(order[np.flatnonzero((tr.size[order] == 1024) & (tr.alloc[order] == 1))[0]])
+    assert off[two_units] == (2 * 20000 - 1) * 512
+
+
 @pytest.mark.parametrize("cfg", [1, 3])
 def test_segment_lists_configs(lap, oracle_mod, cfg):
     tr = make_config(cfg)
