@@ -50,7 +50,7 @@ size_t ws_plan_lists(uint32_t n, uint32_t T, uint32_t B)
     const size_t bn = (size_t)B * n;
     const size_t wide = 3 * up(bn * 8);
     const size_t fast = 4 * up(bn * 8) + 4 * up((size_t)B * lap::PLAN_REC * 8) + up((size_t)B * plan_list_cap(n) * 8) +
-                        2 * up((size_t)B * T * 4);
+                        up((size_t)B * T * 4) + up((size_t)B * T * 8);       // per-step lists: sorted counts; unsorted counts and top holes
     const size_t seg = up(seg_pool_entries(n, B) * 8);
     return std::max(wide, std::max(fast, seg));
 }
@@ -402,7 +402,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     const uint64_t capL = plan_list_cap(n);
     uint64_t *f_L = cf.take<uint64_t>((size_t)B * capL);
     uint32_t *l_ns = cf.take<uint32_t>((size_t)B * T);
-    uint32_t *l_nu = cf.take<uint32_t>((size_t)B * T);
+    uint32_t *l_nu = cf.take<uint32_t>((size_t)B * T * 2);     // [B][T] unsorted counts, then [B][T] starts of the top holes
 
     // The descriptors are split into three arrays; they reach the device inside kernel arguments,
     // so nothing on the host has to outlive this call and nothing waits.
@@ -430,7 +430,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
                                  seg_pool_entries(n, B), st));
     // per-step entry counts start at zero (cleared as 64-bit words, the regions are padded)
     LAP_HIP(lap::launch_fill_u64((uint64_t *)l_ns, ((size_t)B * T + 1) / 2, 0, st));
-    LAP_HIP(lap::launch_fill_u64((uint64_t *)l_nu, ((size_t)B * T + 1) / 2, 0, st));
+    LAP_HIP(lap::launch_fill_u64((uint64_t *)l_nu, (size_t)B * T, 0, st));
     {
         int trial_b = -1;                   // the first first-fit ordering shows how the segment lists' searches go
         for (uint32_t b = 0; b < B && trial_b < 0; ++b)

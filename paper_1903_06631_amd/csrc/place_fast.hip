@@ -495,7 +495,8 @@ struct FastArgs {
     uint64_t *r_oe[2];           // [B][REC] x 2  ALL recent list, two buffers
     void *r_life[2];
     uint64_t *L;                 // [B][capL]   per-step lists, packed blocks
-    uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts
+    uint32_t *l_ns, *l_nu;       // [B][T]      sorted / unsorted entry counts; behind l_nu, [B][T] again: where
+                                 //             the top (unbounded) hole of every list starts
     uint64_t capL;
     uint64_t *offs;              // [B][n] in rank order
     uint64_t *fps;               // [B]
@@ -731,7 +732,7 @@ constexpr uint32_t FIT_MEMO = 4;
 constexpr uint32_t FIT_WORDS = 5;   // per step: answer, end of its hole, its index, list start, index of the top hole
 static_assert(FIT_MEMO * FIT_WORDS * WAVE * sizeof(uint32_t) <= LH * sizeof(uint64_t), "the memo must fit the wave's list slice");
 __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ L, const uint32_t *__restrict__ lstart,
-                                                   const uint32_t *l_ns, uint32_t a, uint32_t f, uint32_t o,
+                                                   const uint32_t *l_ns, const uint32_t *l_top, uint32_t a, uint32_t f, uint32_t o,
                                                    uint32_t s, bool &valid0, bool &valid_rest, uint32_t *memo)
 {
     // oq: the offset asked for, need = oq + s; from: holes below this index are known to end
@@ -810,7 +811,13 @@ __device__ __forceinline__ uint32_t steps_fit_pass(const uint64_t *__restrict__ 
                     if (kept) { mk[3 * WAVE] = base; mk[4 * WAVE] = top; }
                 }
                 uint32_t idx, end;
-                at = search(base, top, oq, need, from_idx, from_idx != 0, idx, end);
+                if (oq >= l_top[t]) {           // inside the top hole, where multi-step blocks nearly always go: no list read
+                    at = oq;
+                    idx = top;
+                    end = NONE32;
+                } else {
+                    at = search(base, top, oq, need, from_idx, from_idx != 0, idx, end);
+                }
                 if (kept) { mk[0] = at; mk[WAVE] = end; mk[2 * WAVE] = idx; }
             }
         }
@@ -946,6 +953,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
     uint64_t *L = A.L + (size_t)b * A.capL;
     uint32_t *l_ns = A.l_ns + (size_t)b * T;
     uint32_t *l_nu = A.l_nu + (size_t)b * T;
+    uint32_t *l_top = A.l_nu + (size_t)gridDim.x * T + (size_t)b * T;
     uint64_t *offs = A.offs + (size_t)b * n;
 
     // variables that will still query ALL: every one when there are no per-step lists
@@ -971,6 +979,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
         for (uint32_t t = threadIdx.x; t < T; t += PW * WAVE) {
             L[A.lstart[t]] = pk(0u, NONE32);
             l_ns[t] = 1;
+            l_top[t] = 0;
         }
     }
     __syncthreads();
@@ -995,6 +1004,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 if (wb_one != NONE32 && (wb_one < wb_from || wb_one >= wb_to)) Lt[wb_one] = hl[wb_one];
                 l_ns[cur_t] = cnt;
                 l_nu[cur_t] = 0;
+                l_top[cur_t] = (uint32_t)(hl[cnt - 1] >> 32);
             }
             wmask |= 1ull << ((cur_t / PW) & 63);
         }
@@ -1118,7 +1128,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         // stand for them.  Passes repeat until no step moves the candidate.
                         uint32_t os = o2;
                         for (;;) {
-                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, va, vf, os, vs, valid0, valid_rest, (uint32_t *)hl);
+                            uint32_t c = steps_fit_pass(L, A.lstart, l_ns, l_top, va, vf, os, vs, valid0, valid_rest, (uint32_t *)hl);
                             c = wave_reduce_max32(c);
                             if (l == 0) s_sf[flip][wave] = c;
                             __syncthreads();
@@ -1327,6 +1337,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                         wave_fence();
                         if (l == 0) { Lt[h] = pk(o + vs, (uint32_t)x - vs); l_ns[t] = nh; l_nu[t] = 0; }
                         wave_fence();
+                        if (l == 0) l_top[t] = (uint32_t)(Lt[nh - 1] >> 32);
                         if (one_step && a == t) { pns = nh; pnu = 0; }
                     }
                     fp = max(fp, o + vs);
