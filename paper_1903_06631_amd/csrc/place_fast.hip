@@ -1192,17 +1192,33 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 }
                 if (multi_left > 1) ++np_multi;
                 if (mode1) {
+                    // The block enters the list of every step it covers.  Where it lies in the list's
+                    // top hole (nearly always) and no block is waiting there, it is taken out right
+                    // away: the top hole moves up, and a hole may be left below it.  Otherwise it waits
+                    // in the list's unsorted tail for the next one-step variable of that step.
                     const uint64_t x = pk(o, en);
                     for (uint32_t t = va + wave * WAVE + l; t < vf; t += PW * WAVE) {
-                        const uint32_t k = l_ns[t] + l_nu[t];
-                        L[A.lstart[t] + k] = x;
-                        l_nu[t] = l_nu[t] + 1;
+                        const uint32_t ns = l_ns[t], nu = l_nu[t], tp = l_top[t];
+                        uint64_t *Lt = L + A.lstart[t];
+                        if (nu == 0 && o >= tp) {
+                            uint32_t k = ns - 1;
+                            if (o > tp) {
+                                Lt[k] = pk(tp, o - tp);
+                                ++k;
+                                l_ns[t] = k + 1;
+                            }
+                            Lt[k] = pk(en, NONE32 - en);
+                            l_top[t] = en;
+                        } else {
+                            Lt[ns + nu] = x;
+                            l_nu[t] = nu + 1;
+                        }
                     }
                 }
                 --multi_left;
                 __syncthreads();
                 // the tails of the steps it covers grew: refresh the counts of the ranks to come
-                if (own && (uint32_t)l > p && a >= va && a < vf) pnu = l_nu[a];
+                if (own && (uint32_t)l > p && a >= va && a < vf) { pns = l_ns[a]; pnu = l_nu[a]; }
                 ++p;
             } else {
                 // ---- a run of one-step variables: each wave takes the steps it owns --------
