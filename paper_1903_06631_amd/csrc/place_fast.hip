@@ -1234,127 +1234,210 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                 // current one is being placed
                 uint64_t pf[LH / WAVE];
                 uint32_t pf_t = NONE32;
+                uint64_t fc = 0;                    // ... or, for the short path below, its first 64 holes only
+                uint32_t fc_t = NONE32;
+                uint32_t fail_t = NONE32;           // step whose last variable needed the full path
 #pragma unroll
                 for (int c = 0; c < (int)(LH / WAVE); ++c) pf[c] = 0;
                 while (mine) {
-                    const int j = __ffsll((unsigned long long)mine) - 1;
+                    int j = __ffsll((unsigned long long)mine) - 1;
                     mine &= mine - 1;
-                    const uint32_t t = read_lane(a, j), vs = read_lane(s, j);
-                    uint32_t o;
-                    if (t != cur_t) {
-                        writeback(one_step ? a : NONE32);
-                        cur_t = NONE32;
-                        const uint32_t base = read_lane(plb, j);
-                        const uint32_t ns = read_lane(pns, j), nu = read_lane(pnu, j), tot = ns + nu;
-                        if (pf_t != t && (wmask & (1ull << ((t / PW) & 63)))) { wave_fence(); wmask = 0; }
-                        if (tot + 1 <= LH) {
-                            if (pf_t == t) {
-                                lds_from_regs<0>(hl, pf, tot, l);
-                            } else {
-                                // not fetched ahead (the first of a run, mostly): all its chunks are
-                                // asked for before the first is waited for
-                                const uint64_t *Lt = L + base;
-                                uint32_t done = 0;
-                                if (tot <= 4 * WAVE) {
-                                    uint64_t y[4];
-#pragma unroll
-                                    for (int c = 0; c < 4; ++c) {
-                                        const uint32_t idx = c * WAVE + l;
-                                        y[c] = idx < tot ? Lt[idx] : 0ull;
-                                    }
-#pragma unroll
-                                    for (int c = 0; c < 4; ++c) {
-                                        const uint32_t idx = c * WAVE + l;
-                                        if (idx < tot) hl[idx] = y[c];
-                                    }
-                                    done = tot;
-                                }
-                                for (uint32_t idx = done + l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
+                    const uint32_t t = read_lane(a, j);
+                    uint32_t vs = read_lane(s, j), o;
+                    // Nearly every one-step variable finds its hole among the first few of its
+                    // step's list (at the benchmark's configuration 97 % among the first 16) and
+                    // takes its lower end: the first 64 holes, fetched ahead while the variable
+                    // before was placed, one ballot, one entry written back.  Everything else
+                    // (blocks waiting in the list's tail, no fit among the first 64, a hole used up,
+                    // the list already in LDS, best-fit) takes the full path below.
+                    bool placed = false;
+                    const bool same_next = mine != 0 && read_lane(a, __ffsll((unsigned long long)mine) - 1) == t;
+                    if (!BEST && t != cur_t && read_lane(pnu, j) == 0) {
+                        const uint32_t base = read_lane(plb, j), ns = read_lane(pns, j);
+                        uint64_t y = fc;
+                        if (fc_t != t) {
+                            if (wmask & (1ull << ((t / PW) & 63))) { wave_fence(); wmask = 0; }
+                            y = (uint32_t)l < ns ? L[base + l] : 0ull;
+                        }
+                        fc_t = NONE32;
+                        if (mine && !same_next) {   // the next variable's first holes, unless a store to them may be under way
+                            const int jn = __ffsll((unsigned long long)mine) - 1;
+                            const uint32_t tn = read_lane(a, jn);
+                            if (tn != t && tn != cur_t && read_lane(pnu, jn) == 0 && !(wmask & (1ull << ((tn / PW) & 63)))) {
+                                fc = (uint32_t)l < read_lane(pns, jn) ? L[read_lane(plb, jn) + l] : 0ull;
+                                fc_t = tn;
                             }
-                            lds_sync();
-                            // carve the multi-step blocks that arrived since out of the holes.  The tail
-                            // is taken into registers 64 entries at a time (lane i holds entry i); the
-                            // holes may then grow over its place: k blocks add at most k holes, and
-                            // the next 64 start 64 entries further up.
-                            uint32_t nh = ns;
-                            for (uint32_t tb = 0; tb < nu; tb += WAVE) {
-                                const uint32_t m = min(nu - tb, (uint32_t)WAVE);
-                                const uint64_t te = (uint32_t)l < m ? hl[ns + tb + l] : 0ull;
+                        }
+                        const uint64_t m = ballot((uint32_t)l < ns && (uint32_t)y >= vs);
+                        if (m) {
+                            const int h = __ffsll((unsigned long long)m) - 1;
+                            const uint64_t x = read_lane64(y, h);
+                            if ((uint32_t)x != vs) {              // the hole shrinks from below
+                                o = (uint32_t)(x >> 32);
+                                const uint64_t z = pk(o + vs, (uint32_t)x - vs);
+                                if (l == 0) {
+                                    L[base + h] = z;
+                                    if ((uint32_t)h + 1 == ns) l_top[t] = o + vs;
+                                }
+                                if (l == h) y = z;
+                                // The wave's next variables of the same step (in orders that keep a
+                                // step's variables together, all of them) are placed from these
+                                // registers, nothing read: a ballot, one entry stored.
+                                while (mine) {
+                                    const int jn = __ffsll((unsigned long long)mine) - 1;
+                                    if (read_lane(a, jn) != t) break;
+                                    const uint32_t vn = read_lane(s, jn);
+                                    const uint64_t mn = ballot((uint32_t)l < ns && (uint32_t)y >= vn);
+                                    if (!mn) break;
+                                    const int hn = __ffsll((unsigned long long)mn) - 1;
+                                    const uint64_t xn = read_lane64(y, hn);
+                                    if ((uint32_t)xn == vn) break;
+                                    fp = max(fp, o + vs);       // the one before is done
+                                    if (l == j) res = o;
+                                    mine &= mine - 1;
+                                    j = jn;
+                                    vs = vn;
+                                    o = (uint32_t)(xn >> 32);
+                                    const uint64_t zn = pk(o + vn, (uint32_t)xn - vn);
+                                    if (l == 0) {
+                                        L[base + hn] = zn;
+                                        if ((uint32_t)hn + 1 == ns) l_top[t] = o + vn;
+                                    }
+                                    if (l == hn) y = zn;
+                                }
+                                wmask |= 1ull << ((t / PW) & 63);
+                                pf_t = NONE32;      // (a whole list fetched ahead by the full path is stale now, if it is this one)
+                                fail_t = NONE32;
+                                placed = true;
+                            }
+                        }
+                    }
+                    if (!placed) {
+                        fc_t = NONE32;
+                        if (t != cur_t) {
+                            writeback(one_step ? a : NONE32);
+                            cur_t = NONE32;
+                            const uint32_t base = read_lane(plb, j);
+                            const uint32_t ns = read_lane(pns, j), nu = read_lane(pnu, j), tot = ns + nu;
+                            if (pf_t != t && (wmask & (1ull << ((t / PW) & 63)))) { wave_fence(); wmask = 0; }
+                            if (tot + 1 <= LH) {
+                                if (pf_t == t) {
+                                    lds_from_regs<0>(hl, pf, tot, l);
+                                } else {
+                                    // not fetched ahead (the first of a run, mostly): all its chunks are
+                                    // asked for before the first is waited for
+                                    const uint64_t *Lt = L + base;
+                                    uint32_t done = 0;
+                                    if (tot <= 4 * WAVE) {
+                                        uint64_t y[4];
+    #pragma unroll
+                                        for (int c = 0; c < 4; ++c) {
+                                            const uint32_t idx = c * WAVE + l;
+                                            y[c] = idx < tot ? Lt[idx] : 0ull;
+                                        }
+    #pragma unroll
+                                        for (int c = 0; c < 4; ++c) {
+                                            const uint32_t idx = c * WAVE + l;
+                                            if (idx < tot) hl[idx] = y[c];
+                                        }
+                                        done = tot;
+                                    }
+                                    for (uint32_t idx = done + l; idx < tot; idx += WAVE) hl[idx] = Lt[idx];
+                                }
                                 lds_sync();
-                                for (uint32_t i = 0; i < m; ++i) {
-                                    const uint64_t x = read_lane64(te, (int)i);
-                                    nh = h_carve(hl, nh, (uint32_t)(x >> 32), (uint32_t)x, wb_from, wb_to);
+                                // carve the multi-step blocks that arrived since out of the holes.  The tail
+                                // is taken into registers 64 entries at a time (lane i holds entry i); the
+                                // holes may then grow over its place: k blocks add at most k holes, and
+                                // the next 64 start 64 entries further up.
+                                uint32_t nh = ns;
+                                for (uint32_t tb = 0; tb < nu; tb += WAVE) {
+                                    const uint32_t m = min(nu - tb, (uint32_t)WAVE);
+                                    const uint64_t te = (uint32_t)l < m ? hl[ns + tb + l] : 0ull;
+                                    lds_sync();
+                                    for (uint32_t i = 0; i < m; ++i) {
+                                        const uint64_t x = read_lane64(te, (int)i);
+                                        nh = h_carve(hl, nh, (uint32_t)(x >> 32), (uint32_t)x, wb_from, wb_to);
+                                    }
                                 }
+                                cur_t = t;
+                                cur_base = base;
+                                cnt = nh;
                             }
-                            cur_t = t;
-                            cur_base = base;
-                            cnt = nh;
                         }
-                    }
-                    pf_t = NONE32;
-                    if (mine) {
-                        const int jn = __ffsll((unsigned long long)mine) - 1;
-                        const uint32_t tn = read_lane(a, jn);
-                        const uint32_t totn = read_lane(pns, jn) + read_lane(pnu, jn);
-                        if (tn != t && totn + 1 <= LH && !(wmask & (1ull << ((tn / PW) & 63)))) {
-                            regs_from_global<0>(pf, L + read_lane(plb, jn), totn, l);
-                            pf_t = tn;
+                        pf_t = NONE32;
+                        if (mine) {
+                            const int jn = __ffsll((unsigned long long)mine) - 1;
+                            const uint32_t tn = read_lane(a, jn);
+                            const uint32_t totn = read_lane(pns, jn) + read_lane(pnu, jn);
+                            if (tn != t && totn + 1 <= LH && !(wmask & (1ull << ((tn / PW) & 63)))) {
+                                regs_from_global<0>(pf, L + read_lane(plb, jn), totn, l);
+                                pf_t = tn;
+                            }
                         }
-                    }
-                    if (cur_t == t) {
-                        const uint32_t h = BEST ? h_best_fit(hl, cnt, vs) : h_first_fit(hl, cnt, vs);
-                        const uint64_t x = uniform64(hl[h]);
-                        o = (uint32_t)(x >> 32);
-                        lds_sync();
-                        if ((uint32_t)x == vs) {         // used up: the hole leaves the list
-                            h_delete(hl, cnt, h);
-                            --cnt;
-                            wb_from = min(wb_from, h);   // (a lone entry above h moved down: now inside)
-                            wb_to = max(wb_to, cnt);
-                        } else {
-                            if (l == 0) hl[h] = pk(o + vs, (uint32_t)x - vs);
+                        if (cur_t == t) {
+                            const uint32_t h = BEST ? h_best_fit(hl, cnt, vs) : h_first_fit(hl, cnt, vs);
+                            const uint64_t x = uniform64(hl[h]);
+                            o = (uint32_t)(x >> 32);
                             lds_sync();
-                            if (h >= wb_from && h < wb_to) {
-                                // inside the range already
-                            } else if (wb_one == NONE32 || wb_one == h) {
-                                wb_one = h;
-                            } else {                     // a second lone entry: widen the range over both
-                                wb_from = min(wb_from, min(h, wb_one));
-                                wb_to = max(wb_to, max(h, wb_one) + 1);
-                                wb_one = NONE32;
-                            }
-                        }
-                    } else {
-                        // list too long for the LDS area: same steps directly in global memory
-                        uint64_t *Lt = L + A.lstart[t];
-                        uint32_t nh = l_ns[t];
-                        for (uint32_t nt = l_nu[t]; nt > 0; --nt) {
-                            const uint64_t xb = Lt[nh + nt - 1];
-                            const uint32_t bo = (uint32_t)(xb >> 32), be = (uint32_t)xb;
-                            const uint32_t h = mem_find_hole(Lt, nh, bo);
-                            const uint64_t x = Lt[h];
-                            const uint32_t st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
-                            wave_fence();
-                            if (bo == st) {
-                                if (l == 0) Lt[h] = pk(be, hend - be);
+                            if ((uint32_t)x == vs) {         // used up: the hole leaves the list
+                                h_delete(hl, cnt, h);
+                                --cnt;
+                                wb_from = min(wb_from, h);   // (a lone entry above h moved down: now inside)
+                                wb_to = max(wb_to, cnt);
                             } else {
-                                if (l == 0) Lt[h] = pk(st, bo - st);
-                                if (be != hend) {
-                                    wave_fence();
-                                    insert_at32(Lt, nullptr, nh + nt - 1, h + 1, pk(be, hend - be), 0);
-                                    ++nh;
+                                if (l == 0) hl[h] = pk(o + vs, (uint32_t)x - vs);
+                                lds_sync();
+                                if (h >= wb_from && h < wb_to) {
+                                    // inside the range already
+                                } else if (wb_one == NONE32 || wb_one == h) {
+                                    wb_one = h;
+                                } else {                     // a second lone entry: widen the range over both
+                                    wb_from = min(wb_from, min(h, wb_one));
+                                    wb_to = max(wb_to, max(h, wb_one) + 1);
+                                    wb_one = NONE32;
                                 }
                             }
+                        } else {
+                            // list too long for the LDS area: same steps directly in global memory
+                            uint64_t *Lt = L + A.lstart[t];
+                            uint32_t nh = l_ns[t];
+                            for (uint32_t nt = l_nu[t]; nt > 0; --nt) {
+                                const uint64_t xb = Lt[nh + nt - 1];
+                                const uint32_t bo = (uint32_t)(xb >> 32), be = (uint32_t)xb;
+                                const uint32_t h = mem_find_hole(Lt, nh, bo);
+                                const uint64_t x = Lt[h];
+                                const uint32_t st = (uint32_t)(x >> 32), hend = st + (uint32_t)x;
+                                wave_fence();
+                                if (bo == st) {
+                                    if (l == 0) Lt[h] = pk(be, hend - be);
+                                } else {
+                                    if (l == 0) Lt[h] = pk(st, bo - st);
+                                    if (be != hend) {
+                                        wave_fence();
+                                        insert_at32(Lt, nullptr, nh + nt - 1, h + 1, pk(be, hend - be), 0);
+                                        ++nh;
+                                    }
+                                }
+                                wave_fence();
+                            }
+                            const uint32_t h = BEST ? h_best_fit(Lt, nh, vs) : mem_first_fit(Lt, nh, vs);
+                            const uint64_t x = Lt[h];
+                            o = (uint32_t)(x >> 32);
                             wave_fence();
+                            if (l == 0) { Lt[h] = pk(o + vs, (uint32_t)x - vs); l_ns[t] = nh; l_nu[t] = 0; }
+                            wave_fence();
+                            if (l == 0) l_top[t] = (uint32_t)(Lt[nh - 1] >> 32);
+                            if (one_step && a == t) { pns = nh; pnu = 0; }
                         }
-                        const uint32_t h = BEST ? h_best_fit(Lt, nh, vs) : mem_first_fit(Lt, nh, vs);
-                        const uint64_t x = Lt[h];
-                        o = (uint32_t)(x >> 32);
-                        wave_fence();
-                        if (l == 0) { Lt[h] = pk(o + vs, (uint32_t)x - vs); l_ns[t] = nh; l_nu[t] = 0; }
-                        wave_fence();
-                        if (l == 0) l_top[t] = (uint32_t)(Lt[nh - 1] >> 32);
-                        if (one_step && a == t) { pns = nh; pnu = 0; }
+                    }
+                    // A run of one step's variables goes back to the registers after the odd one that
+                    // needed the full path (unless the one before needed it too).
+                    if (!BEST && !placed && same_next && cur_t == t) {
+                        if (fail_t != t) {
+                            fail_t = t;
+                            writeback(one_step ? a : NONE32);
+                            cur_t = NONE32;
+                        }
                     }
                     fp = max(fp, o + vs);
                     if (l == j) res = o;
