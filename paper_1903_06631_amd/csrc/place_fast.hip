@@ -1260,19 +1260,21 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                             y = (uint32_t)l < ns ? L[base + l] : 0ull;
                         }
                         fc_t = NONE32;
-                        if (mine && !same_next) {   // the next variable's first holes, unless a store to them may be under way
-                            const int jn = __ffsll((unsigned long long)mine) - 1;
-                            const uint32_t tn = read_lane(a, jn);
-                            if (tn != t && tn != cur_t && read_lane(pnu, jn) == 0 && !(wmask & (1ull << ((tn / PW) & 63)))) {
-                                fc = (uint32_t)l < read_lane(pns, jn) ? L[read_lane(plb, jn) + l] : 0ull;
-                                fc_t = tn;
-                            }
-                        }
                         const uint64_t m = ballot((uint32_t)l < ns && (uint32_t)y >= vs);
                         if (m) {
                             const int h = __ffsll((unsigned long long)m) - 1;
                             const uint64_t x = read_lane64(y, h);
                             if ((uint32_t)x != vs) {              // the hole shrinks from below
+                                // the next variable's first holes are asked for only now that this
+                                // one's have arrived: the wait for these must not take in that read
+                                if (mine && !same_next) {
+                                    const int jn = __ffsll((unsigned long long)mine) - 1;
+                                    const uint32_t tn = read_lane(a, jn);
+                                    if (tn != t && tn != cur_t && read_lane(pnu, jn) == 0 && !(wmask & (1ull << ((tn / PW) & 63)))) {
+                                        fc = (uint32_t)l < read_lane(pns, jn) ? L[read_lane(plb, jn) + l] : 0ull;
+                                        fc_t = tn;
+                                    }
+                                }
                                 o = (uint32_t)(x >> 32);
                                 const uint64_t z = pk(o + vs, (uint32_t)x - vs);
                                 if (l == 0) {
