@@ -1243,7 +1243,7 @@ __global__ __launch_bounds__(PW *WAVE, 4) void k_place_fast(FastArgs A)
                     int j = __ffsll((unsigned long long)mine) - 1;
                     mine &= mine - 1;
                     const uint32_t t = read_lane(a, j);
-                    uint32_t vs = read_lane(s, j), o;
+                    uint32_t vs = read_lane(s, j), o = 0;
                     // Nearly every one-step variable finds its hole among the first few of its
                     // step's list (at the benchmark's configuration 97 % among the first 16) and
                     // takes its lower end: the first 64 holes, fetched ahead while the variable
