@@ -124,6 +124,26 @@ def test_plan_pool_per_step_lists(lap, oracle_mod, seed, n, T, frac, max_life):
     _check_plan(lap, oracle_mod, tr, kinds, seeds)
 
 
+@pytest.mark.parametrize("seed,n,T,frac,max_life,sizes", [
+    (0, 6000, 40, 0.95, 3, [1]),                       # every hole an exact fit for the next variable: holes used up all the time
+    (1, 9000, 12, 0.99, 2, [1, 2]),                    # few steps: long runs of one step's variables in every ordering
+    (2, 12000, 60, 0.8, 6, [1, 1, 2, 3, 5, 8, 13, 64]),  # lists of more than 64 holes: fits beyond the first 64
+    (3, 4000, 1, 1.0, 2, [1, 3, 7]),                   # one step: one list, one wave
+    (4, 8000, 300, 0.9, 10, [7, 9, 100, 1000]),
+])
+def test_plan_pool_one_step_short_path(lap, oracle_mod, seed, n, T, frac, max_life, sizes):
+    """The one-step variables' short path (the first 64 holes of the step's list in registers, one entry
+    stored) and what it hands to the full path: holes used up, no fit among the first 64, runs of one step's
+    variables (the alloc-ascending order places whole steps from the registers), blocks of multi-step variables
+    taken out of the top holes at once or left in the tails."""
+    tr = random_trace(1700 + seed, n, T, size_choices=sizes, one_step_frac=frac, max_life=max_life)
+    assert int((tr.free.astype(np.int64) - tr.alloc).sum()) + tr.n_steps <= 6 * tr.n_vars     # per-step lists in use
+    kinds, seeds = make_orderings(12)
+    kinds = kinds.copy(); kinds[6] = 6
+    _check_plan(lap, oracle_mod, tr, kinds, seeds)
+    _check_plan(lap, oracle_mod, tr, kinds[:6], seeds[:6], fits=[b % 2 for b in range(6)])
+
+
 def test_plan_pool_64bit_offsets(lap, oracle_mod):
     """Sizes whose sum does not fit 2^32 granules take the 64-bit path."""
     tr = random_trace(31, 900, 25, granule=1)
