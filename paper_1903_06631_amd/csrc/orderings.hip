@@ -73,11 +73,12 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
                                                         uint32_t *perm_all, uint32_t *tmp_all)
 {
     __shared__ uint32_t hist[SW][256];
-    __shared__ uint32_t gbase[256], tile_off[256];
+    __shared__ uint32_t tile_off[256];       // per digit: address in dst minus position in the staged tile
     __shared__ uint32_t stage[TS];
+    __shared__ uint8_t stage_d[TS];          // the digit of every staged index
     __shared__ uint32_t wtot[SW];
-    __shared__ uint32_t s_skip;
-    __shared__ uint32_t hist_all[4][256];    // seeded kinds: the digit counts of all their passes, counted in one sweep
+    __shared__ uint64_t s_or[SW], s_and[SW];
+    __shared__ uint32_t hist_all[8][256];    // the digit counts of all passes, counted in one sweep
     const uint32_t b = blockIdx.x;
     const int l = lane_id();
     const uint32_t tid = threadIdx.x, w = tid / WAVE;
@@ -93,8 +94,12 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
         for (uint32_t i = tid; i < n; i += SW * WAVE) perm[i] = min(src[i], n - 1);
         return;
     }
+    // The few orderings by a fixed heuristic need more passes than the many seeded ones that share
+    // their compute units, and the launch ends with the slowest workgroup: their waves go first.
+    if (kind < 4) __builtin_amdgcn_s_setprio(3);
 
-    // exclusive scan over the 256 digit owners (thread d owns digit d); returns the value before d
+    // exclusive scan over the 256 digit owners (thread d owns digit d); returns the value before d.
+    // The callers pass a workgroup barrier between one call and the next.
     auto scan256 = [&](uint32_t v) -> uint32_t {
         uint32_t incl = v;
 #pragma unroll
@@ -106,7 +111,6 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
         __syncthreads();
         uint32_t run = incl - v;
         for (uint32_t k = 0; k < w; ++k) run += wtot[k];
-        __syncthreads();
         return run;
     };
 
@@ -115,54 +119,47 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     uint32_t *dst = perm;
     const uint64_t lt_mask = (1ull << l) - 1ull;
     const int first_pass = (kind == 4) ? (n <= (1u << 22) ? 5 : 4) : (kind == 6) ? 4 : 0;
-    if (first_pass) {
-        // How often a digit occurs does not depend on the order of the ranks, so the counts of all
-        // the passes of a seeded kind come from one sweep over the variables in index order (no
-        // read of the ranks at all) instead of one sweep per pass.
-        for (int q = 0; q < 8 - first_pass; ++q) hist_all[q][tid] = 0;
-        __syncthreads();
+    // Key bits that differ between variables: a pass whose digit has none of them moves nothing.
+    // The seeded kinds sort their top digits whatever the keys are.
+    uint64_t vary = ~0ull << (first_pass * 8);
+    if (!first_pass) {
+        uint64_t o = 0, a = ~0ull;
         for (uint32_t i = tid; i < n; i += SW * WAVE) {
             const uint64_t key = order_key(kind, seed, i, size, alloc, free_);
-            for (int q = 0; q < 8 - first_pass; ++q)
-                atomicAdd(&hist_all[q][(uint32_t)(key >> ((first_pass + q) * 8)) & 255u], 1u);
+            o |= key; a &= key;
         }
+#pragma unroll
+        for (int dlt = 1; dlt < WAVE; dlt <<= 1) {
+            o |= (uint64_t)__shfl_xor((unsigned long long)o, dlt, WAVE);
+            a &= (uint64_t)__shfl_xor((unsigned long long)a, dlt, WAVE);
+        }
+        if (l == 0) { s_or[w] = o; s_and[w] = a; }
         __syncthreads();
+        o = 0; a = ~0ull;
+#pragma unroll
+        for (int k = 0; k < SW; ++k) { o |= s_or[k]; a &= s_and[k]; }
+        const uint64_t v = o ^ a;               // alike in all lanes: to scalar registers
+        vary = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
+               (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
     }
+    // How often a digit occurs does not depend on the order of the ranks, so the counts of all
+    // the passes come from one sweep over the variables in index order (no read of the ranks
+    // at all) instead of one sweep per pass.
+#pragma unroll
+    for (int q = 0; q < 8; ++q) hist_all[q][tid] = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < n; i += SW * WAVE) {
+        const uint64_t key = order_key(kind, seed, i, size, alloc, free_);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if ((vary >> (q * 8)) & 255u) atomicAdd(&hist_all[q][(uint32_t)(key >> (q * 8)) & 255u], 1u);
+    }
+    __syncthreads();
     for (int pass = first_pass; pass < 8; ++pass) {
         const int shift = pass * 8;
-        uint32_t tot = 0;
-        if (first_pass) {
-            tot = hist_all[pass - first_pass][tid];
-        } else {
-            // ---- histogram of this pass's digit over all ranks (thread-strided, independent loads)
-            hist[w][l] = 0; hist[w][l + 64] = 0; hist[w][l + 128] = 0; hist[w][l + 192] = 0;
-            __syncthreads();
-            for (uint32_t base = 0; base < n; base += 4 * SW * WAVE) {
-                uint32_t iv[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint32_t r = base + u * SW * WAVE + tid;
-                    iv[u] = r < n ? (cur ? cur[r] : r) : 0u;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint32_t r = base + u * SW * WAVE + tid;
-                    if (r < n) {
-                        const uint32_t d = (uint32_t)(order_key(kind, seed, iv[u], size, alloc, free_) >> shift) & 255u;
-                        atomicAdd(&hist[w][d], 1u);
-                    }
-                }
-            }
-            __syncthreads();
-#pragma unroll
-            for (int k = 0; k < SW; ++k) tot += hist[k][tid];
-        }
-        if (tid == 0) s_skip = 0;
-        __syncthreads();
-        if (tot == n) s_skip = 1;                     // every key has this digit: nothing moves
-        gbase[tid] = scan256(tot);
-        __syncthreads();
-        if (s_skip) continue;
+        if (!((vary >> shift) & 255u)) continue;      // every key has the same digit: nothing moves
+        // thread d keeps, in a register, where the next entry of digit d goes in dst
+        uint32_t gb = scan256(hist_all[pass][tid]);
 
         // ---- tiles
         for (uint32_t tb = 0; tb < n; tb += TS) {
@@ -189,7 +186,8 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
 #pragma unroll
             for (int k = 0; k < SW; ++k) { c[k] = hist[k][tid]; ttot += c[k]; }
             uint32_t run = scan256(ttot);
-            tile_off[tid] = run;
+            tile_off[tid] = gb - run;
+            gb += ttot;
 #pragma unroll
             for (int k = 0; k < SW; ++k) { hist[k][tid] = run; run += c[k]; }
             __syncthreads();
@@ -206,25 +204,22 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
                 }
                 const uint32_t rank = (uint32_t)__popcll(same & lt_mask);
                 const uint32_t cnt = (uint32_t)__popcll(same);
-                uint32_t pos = 0;
-                if (act) pos = hist[w][d] + rank;
-                wave_lds_sync();
-                if (act && rank == 0) hist[w][d] += cnt;
-                wave_lds_sync();
-                if (act) stage[pos] = iv[k];
+                // The first lane of every group of equal digits takes the group's positions.  The LDS unit
+                // serves a wave's requests in the order they were issued, so the sub-tiles take theirs in
+                // order without waiting for one another.
+                uint32_t base = 0;
+                if (act && rank == 0) base = atomicAdd(&hist[w][d], cnt);
+                const uint32_t pos = (uint32_t)__shfl((int)base, act ? __builtin_ctzll(same) : 0, WAVE) + rank;
+                if (act) { stage[pos] = iv[k]; stage_d[pos] = (uint8_t)d; }
+                if ((k & 3) == 3) __builtin_amdgcn_sched_barrier(0);     // four sub-tiles in flight, not all
             }
             __syncthreads();
-            // the staged tile, grouped by digit, goes out: equal digits to consecutive addresses
+            // The staged tile, grouped by digit, goes out: equal digits to consecutive addresses.  The
+            // next tile's first barrier comes before anything read here is written again.
             const uint32_t tn = min(TS, n - tb);
-            for (uint32_t p = tid; p < tn; p += SW * WAVE) {
-                const uint32_t i = stage[p];
-                const uint32_t d = (uint32_t)(order_key(kind, seed, i, size, alloc, free_) >> shift) & 255u;
-                dst[gbase[d] + (p - tile_off[d])] = i;
-            }
-            __syncthreads();
-            gbase[tid] += ttot;
-            __syncthreads();
+            for (uint32_t p = tid; p < tn; p += SW * WAVE) dst[p + tile_off[stage_d[p]]] = stage[p];
         }
+        __syncthreads();                                      // the next pass reads what this one wrote
         cur = dst;
         dst = (dst == perm) ? tmp : perm;
     }
@@ -239,10 +234,15 @@ __global__ __launch_bounds__(SW *WAVE) void k_sort_perm(uint32_t n, const uint64
     // moves keeps the run's sorted bits, so the neighbours' run tests are not disturbed.
     __syncthreads();
     const int pshift = first_pass * 8;
-    for (uint32_t r = threadIdx.x; r < n; r += SW * WAVE) {
-        const uint64_t p0 = order_key(kind, seed, perm[r], size, alloc, free_) >> pshift;
-        if (r > 0 && (order_key(kind, seed, perm[r - 1], size, alloc, free_) >> pshift) == p0)
-            continue;                                                            // not a run's first rank
+    // A wave looks at 63 ranks per turn: lane 0 only hands the sorted bits of the rank before them to lane 1.
+    for (uint32_t base = w * 63u; base < n; base += SW * 63u) {
+        const uint32_t r = base + (uint32_t)l - 1u;
+        const bool have = r < n;                                                 // not so for rank "-1"
+        uint64_t p0 = 0;
+        if (have) p0 = order_key(kind, seed, perm[r], size, alloc, free_) >> pshift;
+        const uint64_t before = (uint64_t)__shfl_up((unsigned long long)p0, 1, WAVE);
+        if (l == 0 || !have) continue;
+        if (r > 0 && before == p0) continue;                                     // not a run's first rank
         uint32_t m = 1;
         while (r + m < n && (order_key(kind, seed, perm[r + m], size, alloc, free_) >> pshift) == p0) ++m;
         for (uint32_t x = 1; x < m; ++x) {
