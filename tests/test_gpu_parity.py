@@ -199,6 +199,19 @@ def test_plan_pool_seeded_orders_with_equal_leading_key_bits(lap, oracle_mod):
     _check_plan(lap, oracle_mod, tr, [4, 4, 4], seeds)
 
 
+@pytest.mark.parametrize("n", [2, 63, 64, 65, 127, 253, 257, 4095, 4096, 4097, 8193])
+def test_plan_pool_orders_around_wave_and_tile_sizes(lap, oracle_mod, n):
+    """every kind of order with the variable count at, just below and just above what a wave (64 ranks;
+    63 in the pass over runs of equal sorted bits), a workgroup (256) and a tile of the sort (4096) take;
+    few steps and few sizes, so most keys of the fixed kinds tie, and sizes whose keys differ only in
+    high bits next to ones that differ only in low bits"""
+    kinds = [0, 1, 2, 3, 4, 6, 4, 6]
+    seeds = [631 + 7 * b for b in range(len(kinds))]
+    for T, sizes in ((3, [1, 2]), (40, [1, 1, 2, 3, 5, 8, 13, 64, 1 << 20, (1 << 33) + 5])):
+        tr = random_trace(9000 + n, n, T, size_choices=sizes, one_step_frac=0.3)
+        _check_plan(lap, oracle_mod, tr, kinds, seeds)
+
+
 @pytest.mark.parametrize("seed,n,T", [(0, 1, 1), (1, 300, 12), (2, 5000, 60), (3, 70000, 3000)])
 def test_plan_pool_class_seeded_orders(lap, oracle_mod, seed, n, T):
     """shuffles inside size classes (kind 6), both fit policies"""
