@@ -13,6 +13,10 @@ already in a file are skipped.  The order of work puts a spread of 64 orderings 
 
     python tests/golden/make_fullsize_hashes.py --workers 6 [--jobs 5:first 4:first 5:best 4:best]
                                                 [--limit 5:first=1024 4:first=512 ...]
+                                                [--count 160] [--from-the-end]
+
+--count bounds the orderings of one run; --from-the-end takes the orderings after the first 64 in
+descending order, so that a second run on another machine does not repeat what the first one does.
 """
 import argparse
 import os
@@ -61,6 +65,8 @@ def main():
     ap.add_argument("--workers", type=int, default=4)
     ap.add_argument("--jobs", nargs="*", default=["5:first", "4:first", "5:best", "4:best"])
     ap.add_argument("--limit", nargs="*", default=[], help="job=count: at most this many orderings in that file")
+    ap.add_argument("--count", type=int, default=0, help="at most this many orderings in this run (0: no bound)")
+    ap.add_argument("--from-the-end", action="store_true")
     args = ap.parse_args()
     import oracle
     from helpers import fullsize_batch, fullsize_golden_path, read_fullsize_golden
@@ -77,6 +83,8 @@ def main():
                 fh.write(HEADER.format(cfg=cfg, fit=fit))
         done = read_fullsize_golden(cfg, best)
         first, rest = work_order(len(kinds), kinds)
+        if args.from_the_end:
+            rest = rest[::-1]
         room = limits.get(job, len(kinds)) - len(done)
         for ph, lst in enumerate((first, rest)):
             for b in lst:
@@ -84,6 +92,8 @@ def main():
                     phases[ph].append((cfg, best, b, int(kinds[b]), int(seeds[b])))
                     room -= 1
     tasks = phases[0] + phases[1]
+    if args.count:
+        tasks = tasks[: args.count]
     print(f"{len(tasks)} orderings to do", flush=True)
     with ProcessPoolExecutor(args.workers) as ex:
         futs = [ex.submit(one, *t) for t in tasks]
@@ -91,7 +101,7 @@ def main():
             cfg, best, b, kind, seed, fp, dig = f.result()
             with open(fullsize_golden_path(cfg, best), "a") as fh:
                 fh.write(f"{b} {kind} {seed} {fp} {dig}\n")
-            if k % 10 == 0:
+            if k % 10 == 0 or args.count:
                 print(f"{k + 1}/{len(tasks)} done", flush=True)
 
 
