@@ -53,7 +53,7 @@ def _digests(all_off, rows, chunk=64):
     return out
 
 
-def _full_size(lap, oracle_mod, cfg, best_fit, live_sample, all_steps_rows, step_stride):
+def _full_size(lap, oracle_mod, cfg, best_fit, live_sample, all_steps_rows, step_stride, stored_all=False):
     import torch
     from helpers import fullsize_batch, read_fullsize_golden
     tr = make_config(cfg)
@@ -71,6 +71,8 @@ def _full_size(lap, oracle_mod, cfg, best_fit, live_sample, all_steps_rows, step
     #    offsets, written by tests/golden/make_fullsize_hashes.py from the oracle alone)
     gold = read_fullsize_golden(cfg, best_fit)
     assert len(gold) >= 64, f"stored oracle results for cfg {cfg}: {len(gold)}"
+    if stored_all:
+        assert sorted(gold) == list(range(B)), f"cfg {cfg}: the oracle's result is stored for every ordering"
     assert {0, 1, 2, 3, 4, 6} <= {g[0] for g in gold.values()}, "every ordering kind is among them"
     rows = sorted(gold)
     for b in rows:
@@ -108,18 +110,19 @@ def _full_size(lap, oracle_mod, cfg, best_fit, live_sample, all_steps_rows, step
 
 
 def test_full_size_plan_transformer(lap, oracle_mod):
-    """Config 5, the benchmark's launch: 1024 orderings of 200 000 variables."""
+    """Config 5, the benchmark's launch: 1024 orderings of 200 000 variables, every one of them compared
+    with the oracle's stored result."""
     _full_size(lap, oracle_mod, 5, False, live_sample=[0, 1, 2, 3, 63, 127, 4, 5, 100, 333, 517, 640, 777, 901, 1000, 1023],
-               all_steps_rows=[], step_stride=1)
+               all_steps_rows=[], step_stride=1, stored_all=True)
 
 
 def test_full_size_plan_deep_chain(lap, oracle_mod):
     """Config 4: 4096 orderings of 50 000 variables on 14 000 steps (dense interval graph; the segment-list
-    kernel).  The pairwise check runs on every 61st allocation step for all orderings and on every step
-    for 16 of them.  (Best-fit is not run at this size: on a dense trace it looks at thousands of holes per
+    kernel), every one of them compared with the oracle's stored result.  The pairwise check runs on every
+    61st allocation step for all orderings and on every step for 16 of them.  (Best-fit is not run at this size: on a dense trace it looks at thousands of holes per
     variable and takes minutes per ordering.)"""
     _full_size(lap, oracle_mod, 4, False, live_sample=[0, 1, 2, 3, 63, 127, 4, 9, 800, 1500, 2048, 2600, 3100, 3600, 4000, 4095],
-               all_steps_rows=list(range(5, 4096, 273)), step_stride=61)
+               all_steps_rows=list(range(5, 4096, 273)), step_stride=61, stored_all=True)
 
 
 def test_full_size_best_fit_transformer(lap, oracle_mod):
