@@ -126,8 +126,9 @@ def test_full_size_plan_deep_chain(lap, oracle_mod):
 
 
 def test_full_size_best_fit_transformer(lap, oracle_mod):
-    """Config 5 with every ordering planned best-fit."""
-    _full_size(lap, oracle_mod, 5, True, live_sample=[0, 1, 2, 3, 63, 4, 6, 200, 700, 1023], all_steps_rows=[], step_stride=1)
+    """Config 5 with every ordering planned best-fit, every one of them compared with the oracle's stored result."""
+    _full_size(lap, oracle_mod, 5, True, live_sample=[0, 1, 2, 3, 63, 4, 6, 200, 700, 1023], all_steps_rows=[], step_stride=1,
+               stored_all=True)
 
 
 def test_full_size_plan_and_replay_of_swaps(lap, oracle_mod):
