@@ -26,6 +26,23 @@ def test_traffic_summaries_match_the_kernel_sources():
         assert 0.0 <= float(cv["valu_busy_pct"]) <= 100.0
 
 
+def test_every_stamped_summary_matches_the_kernel_sources():
+    """also the summaries bench.py does not read (the best-fit kernel's): a stamp names the sources of the
+    kernel family the file is named for"""
+    bench = _bench()
+    families = {"k_place_fast": ("place_fast.hip", "lap_dev.h"), "k_place_seg": ("place_seg.hip", "seg_core.h", "lap_dev.h")}
+    seen = 0
+    for name in sorted(os.listdir(os.path.join(ROOT, "profiles"))):
+        tv = bench.read_profile_values(os.path.join(ROOT, "profiles", name))
+        if "source_sha256_16" not in tv:
+            continue
+        fam = [f for f in families if name.startswith(f)]
+        assert fam, f"profiles/{name} carries a stamp but no known kernel family"
+        assert tv["source_sha256_16"] == bench.source_stamp(*families[fam[0]]), f"profiles/{name}: measure again"
+        seen += 1
+    assert seen >= 6
+
+
 def test_profiles_hold_text_summaries_only():
     for name in os.listdir(os.path.join(ROOT, "profiles")):
         assert name.endswith((".txt", ".md")), name
