@@ -348,6 +348,17 @@ float lap_profile_last_ms(int kernel_id);
 int lap_profile_ordering_ms(uint32_t n_vars, uint32_t n_steps, uint32_t B, const void *ws, size_t ws_bytes,
                             void *hip_stream, float *ms_host);
 
+/* The placement orders of the last lap_plan_pool call that used this workspace with these n_vars,
+ * n_steps and B (Section III-C: the heuristic order in which the variables are placed; kinds and
+ * tie rule as documented at lap_ordering): orders[b * n_vars + r] = the variable that ordering b
+ * placed r-th.  A device-to-device copy enqueued on the stream; the call does not wait.  What it
+ * returns before any lap_plan_pool call on the workspace, or after another call has used it, is
+ * unspecified (but never read or written out of bounds).
+ *   orders [B * n_vars] DEVICE out, caller-owned
+ * Errors: LAP_E_NULL, LAP_E_SIZE (a zero count), LAP_E_WORKSPACE, LAP_E_HIP. */
+int lap_plan_pool_orders(uint32_t n_vars, uint32_t n_steps, uint32_t B, const void *ws, size_t ws_bytes,
+                         void *hip_stream, uint32_t *orders);
+
 #ifdef __cplusplus
 }
 #endif

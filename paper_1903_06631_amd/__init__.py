@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     profile_enable,
     profile_last_ms,
     profile_ordering_ms,
+    plan_pool_orders,
     schedule_swaps,
     score_swaps,
     select_swaps,

@@ -14,7 +14,7 @@ _lib = None
 EXPORTS = [
     "lap_workspace_bytes", "lap_load_profile", "lap_load_profile_static", "lap_plan_pool", "lap_score_swaps", "lap_select_swaps",
     "lap_detect_iteration", "lap_schedule_swaps", "lap_simulate_swaps", "lap_evaluate_weights",
-    "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms", "lap_profile_ordering_ms", "lap_set_option",
+    "lap_validate_trace", "lap_status_string", "lap_profile_enable", "lap_profile_last_ms", "lap_profile_ordering_ms", "lap_plan_pool_orders", "lap_set_option",
 ]
 
 
@@ -96,6 +96,8 @@ def load_library():
     lib.lap_profile_ordering_ms.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p,
                                             C.c_void_p]
     lib.lap_profile_last_ms.restype = C.c_float
+    lib.lap_plan_pool_orders.restype = C.c_int
+    lib.lap_plan_pool_orders.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.lap_profile_last_ms.argtypes = [C.c_int]
     _lib = lib
     return lib
@@ -137,6 +139,19 @@ def profile_ordering_ms(dt, B: int) -> np.ndarray:
                                                 out.ctypes.data_as(C.c_void_p))
     if rc:
         raise LapError(rc, "lap_profile_ordering_ms")
+    return out
+
+
+def plan_pool_orders(dt, B: int):
+    """lap_plan_pool_orders: the placement orders of the last plan_pool call on this trace with B orderings,
+    int32 device tensor [B, N] (the bits of the uint32 variable indices)."""
+    torch = _torch()
+    ws, need = dt.workspace(1, B)
+    out = torch.empty((B, dt.n_vars), dtype=torch.int32, device=dt.device)
+    rc = load_library().lap_plan_pool_orders(dt.n_vars, dt.n_steps, B, ws.data_ptr(), need, _stream_ptr(dt.device),
+                                             out.data_ptr())
+    if rc:
+        raise LapError(rc, "lap_plan_pool_orders")
     return out
 
 

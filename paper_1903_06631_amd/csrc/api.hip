@@ -307,6 +307,27 @@ int lap_profile_ordering_ms(uint32_t n_vars, uint32_t n_steps, uint32_t B, const
     return LAP_OK;
 }
 
+int lap_plan_pool_orders(uint32_t n_vars, uint32_t n_steps, uint32_t B, const void *ws, size_t ws_bytes,
+                         void *hip_stream, uint32_t *orders)
+{
+    if (!orders) return LAP_E_NULL;
+    if (n_vars == 0 || n_steps == 0 || B == 0) return LAP_E_SIZE;
+    const int rc = check_ws(const_cast<void *>(ws), ws_bytes, ws_plan(n_vars, n_steps, B));
+    if (rc) return rc;
+    // same steps as lap_plan_pool takes to its `perm` region
+    Carver c(const_cast<void *>(ws));
+    c.take<lap::PlanHeader>(1);
+    c.take<uint32_t>((size_t)n_steps + 2);
+    c.take<uint32_t>((size_t)n_steps + 2);
+    c.take<uint32_t>(B);
+    c.take<uint32_t>(B);
+    c.take<uint64_t>(B);
+    c.take<uint64_t>(B);
+    const uint32_t *perm = c.take<uint32_t>((size_t)B * n_vars);
+    LAP_HIP(hipMemcpyAsync(orders, perm, (size_t)B * n_vars * 4, hipMemcpyDeviceToDevice, (hipStream_t)hip_stream));
+    return LAP_OK;
+}
+
 float lap_profile_last_ms(int id)
 {
     if (id < 0 || id >= LAP_K_COUNT || !g_ev_used[id]) return -1.0f;
@@ -376,7 +397,7 @@ int lap_plan_pool(const lap_trace *tr, const lap_ordering *ords, uint32_t B, uin
     uint32_t *fits = c.take<uint32_t>(B);
     uint64_t *seeds = c.take<uint64_t>(B);
     uint64_t *ticks = c.take<uint64_t>(B);          // (lap_profile_ordering_ms finds them by the same steps)
-    uint32_t *perm = c.take<uint32_t>(bn);
+    uint32_t *perm = c.take<uint32_t>(bn);          // (lap_plan_pool_orders likewise)
     uint32_t *tmp = c.take<uint32_t>(bn);
     uint64_t *fps_ws = c.take<uint64_t>(B);
     uint64_t *vrec = c.take<uint64_t>((size_t)n * 2);

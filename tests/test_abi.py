@@ -183,3 +183,10 @@ def test_options_and_ordering_durations_reject_on_the_host(lap):
     assert lib.lap_profile_ordering_ms(10, 5, 4, None, 1 << 30, None, p) == -3
     assert lib.lap_profile_ordering_ms(10, 5, 4, fake, 16, None, p) == -3             # workspace too small
     assert lib.lap_profile_ordering_ms(10, 5, 4, fake + 8, 1 << 30, None, p) == -3    # misaligned
+    # lap_plan_pool_orders: the same workspace checks, before anything is enqueued
+    assert lib.lap_plan_pool_orders(10, 5, 4, fake, 1 << 30, None, None) == -1
+    assert lib.lap_plan_pool_orders(10, 0, 4, fake, 1 << 30, None, fake) == -2
+    assert lib.lap_plan_pool_orders(10, 5, 0, fake, 1 << 30, None, fake) == -2
+    assert lib.lap_plan_pool_orders(10, 5, 4, None, 1 << 30, None, fake) == -3
+    assert lib.lap_plan_pool_orders(10, 5, 4, fake, 16, None, fake) == -3
+    assert lib.lap_plan_pool_orders(10, 5, 4, fake + 8, 1 << 30, None, fake) == -3

@@ -81,6 +81,13 @@ def _full_size(lap, oracle_mod, cfg, best_fit, live_sample, all_steps_rows, step
     wrong = [b for b in rows if dig[b] != gold[b][3] or int(fps[b]) != gold[b][2]]
     assert not wrong, f"cfg {cfg}: {len(wrong)} of {len(rows)} orderings differ from the oracle, first {wrong[:8]}"
 
+    # 1b. the orders themselves, rank by rank, for a spread of orderings with every kind among them
+    orders = lap.plan_pool_orders(dt, B)
+    for b in sorted(set(range(0, B, max(1, B // 40))) | {0, 1, 2, 3, 63, B - 1}):
+        want = oracle_mod.make_perm(tr, int(kinds[b]), int(seeds[b]))
+        assert np.array_equal(orders[b].cpu().numpy().view(np.uint32), want), f"cfg {cfg}: order of ordering {b}"
+    del orders
+
     # 2. a live sample recomputed by the oracle now (one ordering per host thread), element by element
     ref = oracle_all_orderings(oracle_mod, tr, kinds, seeds, which=live_sample, fits=fits)
     for b, (_, off, fp) in ref.items():

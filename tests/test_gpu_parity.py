@@ -199,6 +199,29 @@ def test_plan_pool_seeded_orders_with_equal_leading_key_bits(lap, oracle_mod):
     _check_plan(lap, oracle_mod, tr, [4, 4, 4], seeds)
 
 
+@pytest.mark.parametrize("seed,n,T", [(0, 1, 1), (1, 2, 2), (2, 65, 3), (3, 300, 12), (4, 4097, 9), (5, 20000, 40),
+                                      (6, 70000, 3000)])
+def test_orders_themselves(lap, oracle_mod, seed, n, T):
+    """the orders (not only the offsets they lead to) against the oracle's, rank by rank: every kind, ties in
+    the fixed kinds' keys (few steps, few sizes) kept in ascending index order, seeded keys that agree in the
+    bits the radix passes look at, an explicit order passed through"""
+    import torch
+    sizes = [1, 1, 2, 3, 5, 8, 13, 64, 1 << 20, (1 << 33) + 5] if seed % 2 else None
+    kw = dict(max_life=3, one_step_frac=0.9) if n > 10000 else {}
+    tr = random_trace(4400 + seed, n, T, size_choices=sizes, **kw)
+    kinds = [0, 1, 2, 3, 4, 6, 4, 6, 5, 4]
+    seeds = [0, 0, 0, 0, 5, 77, 1 << 40, 631, 0, 2 ** 64 - 1]
+    rng = np.random.default_rng(seed)
+    mine = rng.permutation(n).astype(np.uint32)
+    dt = lap.DeviceTrace(tr)
+    explicit = {8: torch.from_numpy(mine.view(np.int32)).to(dt.device)}
+    lap.plan_pool(dt, kinds, seeds, explicit=explicit, want_all=False)
+    got = lap.plan_pool_orders(dt, len(kinds)).cpu().numpy().view(np.uint32)
+    for b, (k, s) in enumerate(zip(kinds, seeds)):
+        want = mine if k == 5 else oracle_mod.make_perm(tr, k, s)
+        assert np.array_equal(got[b], np.asarray(want, dtype=np.uint32)), f"ordering {b} kind {k}"
+
+
 @pytest.mark.parametrize("n", [2, 63, 64, 65, 127, 253, 257, 4095, 4096, 4097, 8193])
 def test_plan_pool_orders_around_wave_and_tile_sizes(lap, oracle_mod, n):
     """every kind of order with the variable count at, just below and just above what a wave (64 ranks;
